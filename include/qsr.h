@@ -1,0 +1,158 @@
+/*
+ * qsr.h -- C ABI of the MI355X (gfx950) library for Local SGD / Local AdamW with the
+ * Quadratic Synchronization Rule (arXiv 2310.14423).
+ *
+ * K simulated workers are held on ONE GPU as replica-stacked row-major buffers [K][P]
+ * (worker k owns elements k*P .. k*P+P-1).  One global iteration of Alg. 2 (Local OPT) is
+ *
+ *     qsr_local_step   -- every worker's local gradient (Eq. (1)) and its OPT update
+ *     qsr_maybe_sync   -- if the round's H-th local step has just run: parameter averaging
+ *                         (the All-Reduce line of Alg. 2) and the next round's H from
+ *                         Eq. (2), H = max{H_base, floor((alpha/eta_t)^2)}
+ *
+ * The scheduler state (t, s, h, H), the learning-rate table and the log of averaging
+ * points live in device memory; the two calls above only enqueue kernels on the caller's
+ * stream and never synchronise.  All `float*` / `void*` buffer arguments are DEVICE
+ * pointers unless marked (host); they stay owned by the caller, who must keep them alive
+ * and untouched by other streams until qsr_destroy.  The library allocates only its own
+ * small scheduler tables.  Every function returns QSR_OK (0) or a negative QSR_E* code;
+ * nothing throws or aborts across this boundary.  Argument checks happen on the host
+ * before any GPU work.  A context is not thread-safe.
+ */
+#ifndef QSR_H
+#define QSR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct qsr_ctx qsr_ctx; /* opaque, library-owned */
+
+enum {
+    QSR_OK = 0,
+    QSR_EINVAL = -1,   /* bad argument or configuration                                 */
+    QSR_ESTATE = -2,   /* call out of protocol (e.g. a local step after iteration T)    */
+    QSR_EHIP = -3,     /* a HIP runtime call failed; qsr_last_hip_error() has its code  */
+    QSR_ENOMEM = -4,   /* workspace too small / allocation failed                       */
+    QSR_ENOGPU = -5    /* no usable gfx950 device                                       */
+};
+
+enum { QSR_OPT_SGDM = 0, QSR_OPT_ADAMW = 1 };
+enum { QSR_LR_COSINE = 0, QSR_LR_STEP = 1, QSR_LR_TABLE = 2 };
+enum {
+    QSR_MODEL_EXTERNAL = 0, /* caller writes `grads` before each qsr_local_step          */
+    QSR_MODEL_NOISE = 1,    /* g = grad_sigma * N(0,1), optimizer-only workloads          */
+    QSR_MODEL_LINREG = 2,   /* linear least squares, P = d_in                             */
+    QSR_MODEL_MLP2 = 3,     /* d_in - d_hidden - d_out perceptron, ReLU, softmax CE       */
+    QSR_MODEL_RESMLP = 4    /* n_blocks pre-LN residual MLP blocks, bf16 GEMMs            */
+};
+
+/* Plain-data configuration (Alg. 2's inputs and hyper-parameters, Eq. (2)'s alpha and H_base,
+ * OPT's hyper-parameters per App. C).  Pointers inside are HOST pointers, read during
+ * qsr_init only. */
+typedef struct {
+    int32_t K;            /* workers (replica rows), >= 1                                  */
+    int32_t opt;          /* QSR_OPT_*                                                     */
+    int32_t model;        /* QSR_MODEL_*                                                   */
+    int32_t lr_kind;      /* QSR_LR_*                                                      */
+    int32_t H_base;       /* minimum synchronization period, >= 1 (Eq. (2))                */
+    int32_t n_milestones; /* QSR_LR_STEP: entries of `milestones`                          */
+    int32_t n_blocks;     /* QSR_MODEL_RESMLP                                              */
+    int32_t reserved;     /* must be 0                                                     */
+    int64_t P;            /* parameters per worker, >= 1                                   */
+    int64_t T;            /* total iterations, eta_t is defined for t in 0..T-1, >= 1      */
+    int64_t T_warm;       /* linear warm-up 0 -> eta_max over the first T_warm iterations  */
+    int64_t B_loc;        /* local batch: samples (RESMLP: tokens) per worker per step     */
+    int64_t d_in, d_hidden, d_out;
+    double momentum;      /* SGD heavy-ball coefficient                                    */
+    double beta1, beta2, eps; /* AdamW                                                     */
+    double weight_decay;  /* SGD: coupled (added to the gradient); AdamW: decoupled        */
+    double eta_max, eta_min;  /* QSR_LR_COSINE / QSR_LR_STEP peak; cosine floor            */
+    double step_factor;   /* QSR_LR_STEP: eta = eta_max / step_factor^(#milestones <= t)   */
+    double alpha;         /* growth coefficient of Eq. (2); 0 gives constant H = H_base    */
+    double grad_sigma;    /* QSR_MODEL_NOISE: standard deviation of the gradient           */
+    double data_sigma;    /* LINREG: observation noise; MLP2: input noise                  */
+    uint64_t seed;        /* Philox4x32-10 key of all per-iteration draws                  */
+    const int64_t *milestones; /* (host) ascending iteration indices, QSR_LR_STEP          */
+    const double *eta_table;   /* (host) T entries, QSR_LR_TABLE                           */
+    void *stream;         /* hipStream_t all work is enqueued on (NULL = default stream)   */
+} qsr_config;
+
+/* Checks a configuration on the host (no GPU needed).  QSR_OK or QSR_EINVAL;
+ * *why, if given, receives a static string naming the offending field. */
+int qsr_validate(const qsr_config *cfg, const char **why);
+
+/* Bytes of device workspace qsr_init needs for this configuration (activations, batches,
+ * bf16 weight copies).  0 for the EXTERNAL and NOISE models.  QSR_EINVAL on a bad config. */
+int qsr_workspace_bytes(const qsr_config *cfg, size_t *bytes);
+
+/* Creates a context.  Alg. 2's initialisation: copies theta0 [P] into each of the K rows
+ * of `params`, zeroes the optimizer state, sets t = s = h = 0 and computes H^(0).
+ *   params, grads, state0 : [K][P] float, 16-byte aligned; state1 likewise for AdamW
+ *                           (second moment), NULL for SGD.  state0 = momentum buffer / m.
+ *   theta0                : [P] float, or NULL to keep what `params` holds.
+ *   model_const           : LINREG w* [d_in]; MLP2 class means [d_out][d_in];
+ *                           RESMLP teacher [d_in][d_in]; else NULL.  Borrowed like the rest.
+ *   workspace             : at least qsr_workspace_bytes() bytes, 256-byte aligned, or NULL
+ *                           when that is 0.
+ * Synchronises the stream once.  On failure *out is NULL. */
+int qsr_init(const qsr_config *cfg, float *params, float *grads, float *state0, float *state1,
+             const float *theta0, const float *model_const, void *workspace,
+             size_t workspace_bytes, qsr_ctx **out);
+
+/* One global iteration for all K workers: local gradients at each worker's own parameters
+ * (Eq. (1)) unless the model is EXTERNAL, then the fused OPT update with eta_t (Alg. 2's
+ * inner loop body), then t += 1, h += 1.  Asynchronous.  QSR_ESTATE once T steps have run
+ * or when the previous step's qsr_maybe_sync is missing. */
+int qsr_local_step(qsr_ctx *ctx);
+
+/* If h == H^(s): theta_k <- (1/K) sum_k theta_k for every k, the pair (t, H^(s)) is appended
+ * to the log, s += 1, h = 0 and H^(s+1) follows from Eq. (2) at the new t (cut to T - t;
+ * warm-up rule of Sec. 2).  Otherwise nothing changes.  The decision is taken on the device.
+ * Asynchronous. */
+int qsr_maybe_sync(qsr_ctx *ctx);
+
+/* Synchronises the stream and reads the scheduler state: period of the current round (0 once
+ * t == T), number of finished rounds, iteration counter.  Any pointer may be NULL. */
+int qsr_get_H(qsr_ctx *ctx, int64_t *H, int64_t *round, int64_t *t);
+
+/* Synchronises and copies the log of finished rounds: t_out[i] = iteration count after which
+ * averaging i ran, H_out[i] = that round's period.  Writes min(*n, cap) entries; *n = rounds
+ * so far.  t_out / H_out may be NULL. */
+int qsr_read_sync_log(qsr_ctx *ctx, int64_t *t_out, int64_t *H_out, int64_t cap, int64_t *n);
+
+/* (host) copy of the learning-rate table eta_0..eta_{T-1} the context uses. */
+int qsr_eta_table(qsr_ctx *ctx, double *eta_out, int64_t cap);
+
+/* Synchronises and copies the K per-worker losses of the last local step (models LINREG,
+ * MLP2, RESMLP) to the host array loss_out [K]. */
+int qsr_read_loss(qsr_ctx *ctx, float *loss_out);
+
+/* Puts the scheduler back to t = s = h = 0 (H^(0) recomputed, log cleared) without touching
+ * parameters or optimizer state.  Asynchronous. */
+int qsr_restart(qsr_ctx *ctx);
+
+/* Per-kernel timing with HIP events on the context's stream.  After qsr_timing(ctx, 1) each
+ * gradient stage, update kernel and averaging kernel is bracketed by an event pair;
+ * qsr_read_timing synchronises, adds up the pairs recorded since the last read and recycles
+ * them.  ms[0..2] / count[0..2] = gradient stage, update kernel, averaging kernel (averaging is
+ * counted only in steps whose averaging really ran). */
+int qsr_timing(qsr_ctx *ctx, int enable);
+int qsr_read_timing(qsr_ctx *ctx, double ms[3], int64_t count[3]);
+
+int qsr_destroy(qsr_ctx *ctx);
+
+/* Stateless replica averaging (the All-Reduce line of Alg. 2 / Alg. 1 on any [K][P] buffer):
+ * buf_k <- (1/K) sum_k buf_k for every k.  Asynchronous on `stream`. */
+int qsr_average_rows(float *buf, int32_t K, int64_t P, void *stream);
+
+const char *qsr_strerror(int code);
+int qsr_last_hip_error(void); /* hipError_t of the last failed runtime call in this thread */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QSR_H */

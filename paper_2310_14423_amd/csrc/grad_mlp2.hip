@@ -1,0 +1,180 @@
+// grad_mlp2.hip -- local gradient (Eq. (1) of arXiv 2310.14423) of the two-layer perceptron
+// workload for all K workers in batched launches.  Parameters of one worker are packed as
+// W1 [d_in][d_hidden], b1 [d_hidden], W2 [d_hidden][d_out], b2 [d_out]; the gradient uses the
+// same packing.  hidden = relu(x W1 + b1); logits = hidden W2 + b2; loss = mean softmax
+// cross-entropy.  Inputs: label_i uniform over the classes, x_i = mean[label_i] + sigma*N(0,I),
+// drawn per (worker, iteration) from Philox4x32-10.
+#include "philox.h"
+#include "qsr_internal.h"
+#include "sgemm.h"
+
+namespace qsr {
+
+struct Mlp2Ws {
+    float *X, *hid, *dhid, *logit;
+    int *label;
+};
+
+static size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+static Mlp2Ws carve(const ModelDims &d, void *ws, size_t *total)
+{
+    char *p = (char *)ws;
+    size_t off = 0;
+    Mlp2Ws w;
+    size_t K = (size_t)d.K, B = (size_t)d.B;
+    w.X = (float *)(p + off);     off += up256(K * B * d.d_in * sizeof(float));
+    w.hid = (float *)(p + off);   off += up256(K * B * d.d_hidden * sizeof(float));
+    w.dhid = (float *)(p + off);  off += up256(K * B * d.d_hidden * sizeof(float));
+    w.logit = (float *)(p + off); off += up256(K * B * d.d_out * sizeof(float));
+    w.label = (int *)(p + off);   off += up256(K * B * sizeof(int));
+    if (total) *total = off;
+    return w;
+}
+
+size_t mlp2_workspace_bytes(const ModelDims &d)
+{
+    size_t total = 0;
+    carve(d, nullptr, &total);
+    return total;
+}
+
+__global__ __launch_bounds__(256) void mlp2_labels_kernel(int *__restrict__ label, long long B,
+                                                          uint32_t classes, uint64_t seed,
+                                                          const DevState *__restrict__ st)
+{
+    const uint32_t k = blockIdx.y;
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= B) return;
+    U4 r = draw4(seed, STREAM_LABEL, k, (uint32_t)st->t, (uint32_t)(i >> 2));
+    uint32_t w = (i & 3) == 0 ? r.x : (i & 3) == 1 ? r.y : (i & 3) == 2 ? r.z : r.w;
+    label[(long long)k * B + i] = (int)index_from_word(w, classes);
+}
+
+// X holds sigma*z on entry; add the class mean of each sample's label
+__global__ __launch_bounds__(256) void mlp2_add_means_kernel(float *__restrict__ X,
+                                                             const int *__restrict__ label,
+                                                             const float *__restrict__ means,
+                                                             long long B, long long d_in)
+{
+    const int k = blockIdx.y;
+    const long long n = B * d_in;
+    const long long stride = (long long)gridDim.x * 256;
+    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < n; e += stride) {
+        long long i = e / d_in, j = e - i * d_in;
+        int c = label[(long long)k * B + i];
+        X[(long long)k * n + e] += means[(long long)c * d_in + j];
+    }
+}
+
+// per sample: logits -> (softmax - onehot)/B in place; per worker: mean cross-entropy.
+// One block per worker, samples strided over its threads (d_out is small).
+__global__ __launch_bounds__(256) void mlp2_softmax_ce_kernel(float *__restrict__ logit,
+                                                              const int *__restrict__ label,
+                                                              float *__restrict__ loss,
+                                                              long long B, int C)
+{
+    __shared__ float red[4];
+    const int k = blockIdx.x;
+    const float invB = 1.0f / (float)B;
+    float lsum = 0.f;
+    for (long long i = threadIdx.x; i < B; i += 256) {
+        float *z = logit + ((long long)k * B + i) * C;
+        const int y = label[(long long)k * B + i];
+        float mx = z[0];
+        for (int o = 1; o < C; ++o) mx = fmaxf(mx, z[o]);
+        float se = 0.f;
+        for (int o = 0; o < C; ++o) se += expf(z[o] - mx);
+        lsum += (mx + logf(se)) - z[y];
+        const float inv = 1.0f / se;
+        for (int o = 0; o < C; ++o) z[o] = (expf(z[o] - mx) * inv - (o == y ? 1.f : 0.f)) * invB;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) lsum += __shfl_down(lsum, o, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = lsum;
+    __syncthreads();
+    if (threadIdx.x == 0) loss[k] = (red[0] + red[1] + red[2] + red[3]) * invB;
+}
+
+// out[k][j] = sum_i A[k][i][j]   (bias gradients)
+__global__ __launch_bounds__(256) void colsum_kernel(const float *__restrict__ A,
+                                                     float *__restrict__ out, long long rows,
+                                                     long long cols, long long sA, long long sOut)
+{
+    const int k = blockIdx.y;
+    const long long j = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (j >= cols) return;
+    const float *a = A + (long long)k * sA;
+    float acc = 0.f;
+    for (long long i = 0; i < rows; ++i) acc += a[i * cols + j];
+    out[(long long)k * sOut + j] = acc;
+}
+
+hipError_t launch_mlp2_grad(const ModelDims &d, const float *theta, float *g, const float *means,
+                            void *ws, float *loss, const DevState *st, hipStream_t s)
+{
+    const long long B = d.B, di = d.d_in, dh = d.d_hidden, dz = d.d_out, P = d.P;
+    const int K = d.K;
+    Mlp2Ws w = carve(d, ws, nullptr);
+    const long long oW1 = 0, ob1 = di * dh, oW2 = ob1 + dh, ob2 = oW2 + dh * dz;
+    hipError_t e;
+
+    // Sample(): labels, then inputs
+    mlp2_labels_kernel<<<dim3((unsigned)((B + 255) / 256), (unsigned)K), 256, 0, s>>>(
+        w.label, B, (uint32_t)dz, d.seed, st);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if ((e = launch_fill_normal(w.X, K, B * di, d.data_sigma, STREAM_X, d.seed, st, s)) != hipSuccess) return e;
+    {
+        long long bx = (B * di + 255) / 256;
+        if (bx > 4096) bx = 4096;
+        mlp2_add_means_kernel<<<dim3((unsigned)bx, (unsigned)K), 256, 0, s>>>(w.X, w.label, means, B, di);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    // forward
+    GemmArgs a{};
+    a.A = w.X; a.lda = di; a.sA = B * di;
+    a.B = theta + oW1; a.ldb = dh; a.sB = P;
+    a.C = w.hid; a.ldc = dh; a.sC = B * dh;
+    a.M = (int)B; a.N = (int)dh; a.Kd = (int)di; a.bias = theta + ob1; a.sBias = P;
+    if ((e = launch_sgemm<false, false, EPI_BIAS_RELU>(a, K, s)) != hipSuccess) return e;
+
+    a = GemmArgs{};
+    a.A = w.hid; a.lda = dh; a.sA = B * dh;
+    a.B = theta + oW2; a.ldb = dz; a.sB = P;
+    a.C = w.logit; a.ldc = dz; a.sC = B * dz;
+    a.M = (int)B; a.N = (int)dz; a.Kd = (int)dh; a.bias = theta + ob2; a.sBias = P;
+    if ((e = launch_sgemm<false, false, EPI_BIAS>(a, K, s)) != hipSuccess) return e;
+
+    mlp2_softmax_ce_kernel<<<K, 256, 0, s>>>(w.logit, w.label, loss, B, (int)dz);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+
+    // backward; w.logit now holds d loss / d logits
+    a = GemmArgs{};                                        // gW2 = hid^T dlogits
+    a.A = w.hid; a.lda = dh; a.sA = B * dh;
+    a.B = w.logit; a.ldb = dz; a.sB = B * dz;
+    a.C = g + oW2; a.ldc = dz; a.sC = P;
+    a.M = (int)dh; a.N = (int)dz; a.Kd = (int)B;
+    if ((e = launch_sgemm<true, false, EPI_NONE>(a, K, s)) != hipSuccess) return e;
+    colsum_kernel<<<dim3((unsigned)((dz + 255) / 256), (unsigned)K), 256, 0, s>>>(
+        w.logit, g + ob2, B, dz, B * dz, P);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+
+    a = GemmArgs{};                                        // dhid = (dlogits W2^T) * [hid > 0]
+    a.A = w.logit; a.lda = dz; a.sA = B * dz;
+    a.B = theta + oW2; a.ldb = dz; a.sB = P;
+    a.C = w.dhid; a.ldc = dh; a.sC = B * dh;
+    a.M = (int)B; a.N = (int)dh; a.Kd = (int)dz; a.aux = w.hid;
+    if ((e = launch_sgemm<false, true, EPI_MASK_POS>(a, K, s)) != hipSuccess) return e;
+
+    a = GemmArgs{};                                        // gW1 = X^T dhid
+    a.A = w.X; a.lda = di; a.sA = B * di;
+    a.B = w.dhid; a.ldb = dh; a.sB = B * dh;
+    a.C = g + oW1; a.ldc = dh; a.sC = P;
+    a.M = (int)di; a.N = (int)dh; a.Kd = (int)B;
+    if ((e = launch_sgemm<true, false, EPI_NONE>(a, K, s)) != hipSuccess) return e;
+    colsum_kernel<<<dim3((unsigned)((dh + 255) / 256), (unsigned)K), 256, 0, s>>>(
+        w.dhid, g + ob1, B, dh, B * dh, P);
+    return hipGetLastError();
+}
+
+}  // namespace qsr

@@ -1,0 +1,516 @@
+// qsr_api.hip -- host side of the C ABI declared in include/qsr.h: configuration checks,
+// learning-rate and per-step scalar tables (double precision on the host), context life
+// cycle, and the launch sequence of one iteration of Alg. 2 (arXiv 2310.14423).
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "qsr_internal.h"
+
+using namespace qsr;
+
+static thread_local int g_last_hip = 0;
+
+#define HIP_TRY(expr)                                    \
+    do {                                                 \
+        hipError_t e_ = (expr);                          \
+        if (e_ != hipSuccess) {                          \
+            g_last_hip = (int)e_;                        \
+            (void)hipGetLastError();                     \
+            return QSR_EHIP;                             \
+        }                                                \
+    } while (0)
+
+struct TimedPair {
+    hipEvent_t a, b;
+    int kind;            // 0 gradient stage, 1 update, 2 averaging
+    long long t_after;   // host iteration counter when recorded (averaging: value of t)
+};
+
+struct qsr_ctx {
+    qsr_config cfg;
+    hipStream_t stream;
+    int device;
+    float *params, *grads, *state0, *state1;
+    const float *model_const;
+    void *workspace;
+    size_t workspace_bytes;
+    // library-owned device memory
+    DevState *d_state;
+    double *d_eta;
+    StepScalars *d_scal;
+    long long *d_log_t, *d_log_H;
+    float *d_loss;
+    // host mirrors
+    std::vector<double> eta;
+    DevState *h_state;       // pinned
+    long long t_host;        // local steps enqueued
+    bool need_sync_call;     // a local step was enqueued and its maybe_sync not yet
+    SchedParams sp;
+    ModelDims dims;
+    // timing
+    bool timing;
+    std::vector<TimedPair> pairs;
+    std::vector<hipEvent_t> free_events;
+};
+
+// ------------------------------------------------------------------------------------------
+// configuration
+// ------------------------------------------------------------------------------------------
+static long long mlp2_params(const qsr_config *c)
+{
+    return c->d_in * c->d_hidden + c->d_hidden + c->d_hidden * c->d_out + c->d_out;
+}
+static long long resmlp_params(const qsr_config *c)
+{
+    return (long long)c->n_blocks *
+           (2 * c->d_in + c->d_in * c->d_hidden + c->d_hidden + c->d_hidden * c->d_in + c->d_in);
+}
+
+extern "C" int qsr_validate(const qsr_config *c, const char **why)
+{
+    const char *w = nullptr;
+    auto finite_ge0 = [](double x) { return std::isfinite(x) && x >= 0.0; };
+    if (!c) w = "cfg is NULL";
+    else if (c->K < 1 || c->K > 65535) w = "K";
+    else if (c->P < 1) w = "P";
+    else if (c->P > ((long long)1 << 34)) w = "P (above 2^34)";
+    else if (c->T < 1 || c->T > 0xFFFFFFFFll) w = "T";
+    else if (c->T_warm < 0 || c->T_warm > c->T) w = "T_warm";
+    else if (c->opt != QSR_OPT_SGDM && c->opt != QSR_OPT_ADAMW) w = "opt";
+    else if (c->model < QSR_MODEL_EXTERNAL || c->model > QSR_MODEL_RESMLP) w = "model";
+    else if (c->lr_kind < QSR_LR_COSINE || c->lr_kind > QSR_LR_TABLE) w = "lr_kind";
+    else if (c->H_base < 1) w = "H_base";
+    else if (c->reserved != 0) w = "reserved";
+    else if (!finite_ge0(c->alpha)) w = "alpha";
+    else if (!finite_ge0(c->weight_decay)) w = "weight_decay";
+    else if (c->opt == QSR_OPT_SGDM && !(finite_ge0(c->momentum) && c->momentum < 1.0)) w = "momentum";
+    else if (c->opt == QSR_OPT_ADAMW &&
+             !(finite_ge0(c->beta1) && c->beta1 < 1.0 && finite_ge0(c->beta2) && c->beta2 < 1.0))
+        w = "beta1/beta2";
+    else if (c->opt == QSR_OPT_ADAMW && !(std::isfinite(c->eps) && c->eps > 0.0)) w = "eps";
+    else if (c->lr_kind != QSR_LR_TABLE && !(std::isfinite(c->eta_max) && c->eta_max > 0.0)) w = "eta_max";
+    else if (c->lr_kind == QSR_LR_COSINE && !(finite_ge0(c->eta_min) && c->eta_min <= c->eta_max)) w = "eta_min";
+    else if (c->lr_kind == QSR_LR_STEP &&
+             (c->n_milestones < 0 || (c->n_milestones > 0 && !c->milestones) ||
+              !(std::isfinite(c->step_factor) && c->step_factor > 0.0)))
+        w = "milestones/step_factor";
+    else if (c->lr_kind == QSR_LR_TABLE && !c->eta_table) w = "eta_table";
+    if (!w && c->lr_kind == QSR_LR_TABLE) {
+        for (long long t = 0; t < c->T; ++t)
+            if (!(std::isfinite(c->eta_table[t]) && c->eta_table[t] >= 0.0)) { w = "eta_table entry"; break; }
+    }
+    if (!w && c->lr_kind == QSR_LR_STEP) {
+        for (int i = 1; i < c->n_milestones; ++i)
+            if (c->milestones[i] < c->milestones[i - 1]) { w = "milestones not ascending"; break; }
+    }
+    if (!w) {
+        switch (c->model) {
+        case QSR_MODEL_NOISE:
+            if (!finite_ge0(c->grad_sigma)) w = "grad_sigma";
+            break;
+        case QSR_MODEL_LINREG:
+            if (c->d_in < 1 || c->B_loc < 1) w = "d_in/B_loc";
+            else if (c->P != c->d_in) w = "P != d_in";
+            else if (c->B_loc * c->d_in > ((long long)1 << 34)) w = "B_loc*d_in";
+            else if (!finite_ge0(c->data_sigma)) w = "data_sigma";
+            break;
+        case QSR_MODEL_MLP2:
+            if (c->d_in < 1 || c->d_hidden < 1 || c->d_out < 1 || c->B_loc < 1) w = "d_in/d_hidden/d_out/B_loc";
+            else if (c->d_out > 1024) w = "d_out (above 1024)";
+            else if (c->P != mlp2_params(c)) w = "P != MLP parameter count";
+            else if (c->B_loc * c->d_in > ((long long)1 << 34)) w = "B_loc*d_in";
+            else if (!finite_ge0(c->data_sigma)) w = "data_sigma";
+            break;
+        case QSR_MODEL_RESMLP:
+            if (c->d_in < 1 || c->d_hidden < 1 || c->n_blocks < 1 || c->B_loc < 1) w = "d_in/d_hidden/n_blocks/B_loc";
+            else if (c->P != resmlp_params(c)) w = "P != residual-MLP parameter count";
+            else if (c->B_loc * c->d_in > ((long long)1 << 34)) w = "B_loc*d_in";
+            break;
+        default: break;
+        }
+    }
+    if (why) *why = w ? w : "ok";
+    return w ? QSR_EINVAL : QSR_OK;
+}
+
+static ModelDims make_dims(const qsr_config *c)
+{
+    ModelDims d;
+    d.K = c->K; d.P = c->P; d.B = c->B_loc; d.d_in = c->d_in; d.d_hidden = c->d_hidden;
+    d.d_out = c->d_out; d.n_blocks = c->n_blocks; d.data_sigma = (float)c->data_sigma;
+    d.seed = c->seed;
+    return d;
+}
+
+extern "C" int qsr_workspace_bytes(const qsr_config *cfg, size_t *bytes)
+{
+    if (!bytes) return QSR_EINVAL;
+    *bytes = 0;
+    int rc = qsr_validate(cfg, nullptr);
+    if (rc != QSR_OK) return rc;
+    ModelDims d = make_dims(cfg);
+    switch (cfg->model) {
+    case QSR_MODEL_LINREG: *bytes = linreg_workspace_bytes(d); break;
+    case QSR_MODEL_MLP2: *bytes = mlp2_workspace_bytes(d); break;
+    case QSR_MODEL_RESMLP: return QSR_EINVAL;   // not built yet
+    default: break;
+    }
+    return QSR_OK;
+}
+
+// Learning-rate schedules (Sec. 4 of the paper: cosine decay, optionally after a linear warm-up
+// from 0; step decay divides the peak by a factor at each milestone).
+static void build_eta(const qsr_config *c, std::vector<double> &eta)
+{
+    const long long T = c->T, Tw = c->T_warm;
+    eta.resize((size_t)T);
+    const double pi = 3.14159265358979323846;
+    for (long long t = 0; t < T; ++t) {
+        double e;
+        if (c->lr_kind == QSR_LR_TABLE) {
+            e = c->eta_table[t];
+        } else if (t < Tw) {
+            e = c->eta_max * (double)t / (double)Tw;
+        } else if (c->lr_kind == QSR_LR_COSINE) {
+            double frac = (double)(t - Tw) / (double)(T - Tw);
+            e = c->eta_min + 0.5 * (c->eta_max - c->eta_min) * (1.0 + std::cos(pi * frac));
+        } else {
+            double div = 1.0;
+            for (int i = 0; i < c->n_milestones; ++i)
+                if (c->milestones[i] <= t) div *= c->step_factor;
+            e = c->eta_max / div;
+        }
+        eta[(size_t)t] = e;
+    }
+}
+
+static void build_scalars(const qsr_config *c, const std::vector<double> &eta,
+                          std::vector<StepScalars> &sc)
+{
+    sc.resize(eta.size());
+    for (size_t t = 0; t < eta.size(); ++t) {
+        StepScalars s{0.f, 0.f, 0.f, 0.f};
+        if (c->opt == QSR_OPT_SGDM) {
+            s.x = (float)eta[t];
+        } else {
+            double n = (double)(t + 1);      // Adam's step count = global iteration count
+            double bc1 = 1.0 - std::pow(c->beta1, n);
+            double bc2 = 1.0 - std::pow(c->beta2, n);
+            s.x = (float)(eta[t] * c->weight_decay);
+            s.y = (float)(eta[t] / bc1);
+            s.z = (float)(1.0 / std::sqrt(bc2));
+        }
+        sc[t] = s;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// life cycle
+// ------------------------------------------------------------------------------------------
+static void free_ctx(qsr_ctx *c)
+{
+    if (!c) return;
+    for (auto &p : c->pairs) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
+    for (auto e : c->free_events) (void)hipEventDestroy(e);
+    if (c->d_state) (void)hipFree(c->d_state);
+    if (c->d_eta) (void)hipFree(c->d_eta);
+    if (c->d_scal) (void)hipFree(c->d_scal);
+    if (c->d_log_t) (void)hipFree(c->d_log_t);
+    if (c->d_log_H) (void)hipFree(c->d_log_H);
+    if (c->d_loss) (void)hipFree(c->d_loss);
+    if (c->h_state) (void)hipHostFree(c->h_state);
+    delete c;
+}
+
+static int init_impl(qsr_ctx *c, const float *theta0)
+{
+    const qsr_config &cfg = c->cfg;
+    const size_t T = (size_t)cfg.T;
+    HIP_TRY(hipGetDevice(&c->device));
+    hipDeviceProp_t prop;
+    HIP_TRY(hipGetDeviceProperties(&prop, c->device));
+    if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return QSR_ENOGPU;
+
+    HIP_TRY(hipMalloc((void **)&c->d_state, sizeof(DevState)));
+    HIP_TRY(hipMalloc((void **)&c->d_eta, T * sizeof(double)));
+    HIP_TRY(hipMalloc((void **)&c->d_scal, T * sizeof(StepScalars)));
+    HIP_TRY(hipMalloc((void **)&c->d_log_t, T * sizeof(long long)));
+    HIP_TRY(hipMalloc((void **)&c->d_log_H, T * sizeof(long long)));
+    HIP_TRY(hipMalloc((void **)&c->d_loss, (size_t)cfg.K * sizeof(float)));
+    HIP_TRY(hipHostMalloc((void **)&c->h_state, sizeof(DevState), hipHostMallocDefault));
+
+    std::vector<StepScalars> sc;
+    build_eta(&cfg, c->eta);
+    build_scalars(&cfg, c->eta, sc);
+    // the two tables are copied from pageable memory: finish the copies before `sc` dies
+    HIP_TRY(hipMemcpyAsync(c->d_eta, c->eta.data(), T * sizeof(double), hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(hipMemcpyAsync(c->d_scal, sc.data(), T * sizeof(StepScalars), hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(hipStreamSynchronize(c->stream));
+
+    c->sp.T = cfg.T; c->sp.T_warm = cfg.T_warm; c->sp.H_base = cfg.H_base; c->sp.alpha = cfg.alpha;
+    c->sp.eta = c->d_eta; c->sp.log_t = c->d_log_t; c->sp.log_H = c->d_log_H;
+
+    const long long n = (long long)cfg.K * cfg.P;
+    if (theta0) HIP_TRY(launch_broadcast_rows(c->params, theta0, cfg.K, cfg.P, c->stream));
+    HIP_TRY(launch_fill_zero(c->state0, n, c->stream));
+    if (c->state1) HIP_TRY(launch_fill_zero(c->state1, n, c->stream));
+    HIP_TRY(launch_fill_zero(c->d_loss, cfg.K, c->stream));
+    HIP_TRY(launch_sched_init(c->d_state, c->sp, c->stream));
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    return QSR_OK;
+}
+
+extern "C" int qsr_init(const qsr_config *cfg, float *params, float *grads, float *state0,
+                        float *state1, const float *theta0, const float *model_const,
+                        void *workspace, size_t workspace_bytes, qsr_ctx **out)
+{
+    if (!out) return QSR_EINVAL;
+    *out = nullptr;
+    int rc = qsr_validate(cfg, nullptr);
+    if (rc != QSR_OK) return rc;
+    if (!params || !grads || !state0) return QSR_EINVAL;
+    if (cfg->opt == QSR_OPT_ADAMW && !state1) return QSR_EINVAL;
+    auto misaligned = [](const void *p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) != 0; };
+    if (misaligned(params, 16) || misaligned(grads, 16) || misaligned(state0, 16) ||
+        (state1 && misaligned(state1, 16)))
+        return QSR_EINVAL;
+    size_t need = 0;
+    rc = qsr_workspace_bytes(cfg, &need);
+    if (rc != QSR_OK) return rc;
+    if (need > 0 && (!workspace || misaligned(workspace, 256))) return QSR_EINVAL;
+    if (workspace_bytes < need) return QSR_ENOMEM;
+    if (cfg->model >= QSR_MODEL_LINREG && !model_const) return QSR_EINVAL;
+
+    qsr_ctx *c = new (std::nothrow) qsr_ctx();
+    if (!c) return QSR_ENOMEM;
+    c->cfg = *cfg;                     // its host pointers are valid during this call only
+    c->stream = (hipStream_t)cfg->stream;
+    c->params = params; c->grads = grads; c->state0 = state0;
+    c->state1 = cfg->opt == QSR_OPT_ADAMW ? state1 : nullptr;
+    c->model_const = model_const; c->workspace = workspace; c->workspace_bytes = workspace_bytes;
+    c->d_state = nullptr; c->d_eta = nullptr; c->d_scal = nullptr; c->d_log_t = nullptr;
+    c->d_log_H = nullptr; c->d_loss = nullptr; c->h_state = nullptr;
+    c->t_host = 0; c->need_sync_call = false; c->timing = false;
+    c->dims = make_dims(cfg);
+    rc = init_impl(c, theta0);
+    c->cfg.milestones = nullptr;
+    c->cfg.eta_table = nullptr;
+    if (rc != QSR_OK) { free_ctx(c); return rc; }
+    *out = c;
+    return QSR_OK;
+}
+
+extern "C" int qsr_destroy(qsr_ctx *ctx)
+{
+    if (!ctx) return QSR_EINVAL;
+    (void)hipStreamSynchronize(ctx->stream);
+    free_ctx(ctx);
+    return QSR_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// timing helpers
+// ------------------------------------------------------------------------------------------
+static int get_event(qsr_ctx *c, hipEvent_t *e)
+{
+    if (!c->free_events.empty()) { *e = c->free_events.back(); c->free_events.pop_back(); return QSR_OK; }
+    HIP_TRY(hipEventCreate(e));
+    return QSR_OK;
+}
+
+struct Bracket {
+    qsr_ctx *c; int kind; hipEvent_t a, b; bool on; int rc;
+    Bracket(qsr_ctx *c_, int kind_) : c(c_), kind(kind_), a(nullptr), b(nullptr), on(c_->timing), rc(QSR_OK)
+    {
+        if (!on) return;
+        rc = get_event(c, &a);
+        if (rc == QSR_OK) rc = get_event(c, &b);
+        if (rc == QSR_OK && hipEventRecord(a, c->stream) != hipSuccess) rc = QSR_EHIP;
+    }
+    int close(long long t_after)
+    {
+        if (!on || rc != QSR_OK) return rc;
+        if (hipEventRecord(b, c->stream) != hipSuccess) return QSR_EHIP;
+        c->pairs.push_back(TimedPair{a, b, kind, t_after});
+        return QSR_OK;
+    }
+};
+
+// ------------------------------------------------------------------------------------------
+// the iteration
+// ------------------------------------------------------------------------------------------
+extern "C" int qsr_local_step(qsr_ctx *c)
+{
+    if (!c) return QSR_EINVAL;
+    if (c->t_host >= c->cfg.T || c->need_sync_call) return QSR_ESTATE;
+    const qsr_config &cfg = c->cfg;
+    const long long n = (long long)cfg.K * cfg.P;
+
+    if (cfg.model != QSR_MODEL_EXTERNAL) {             // Eq. (1): every worker's local gradient
+        Bracket br(c, 0);
+        if (br.rc != QSR_OK) return br.rc;
+        switch (cfg.model) {
+        case QSR_MODEL_NOISE:
+            HIP_TRY(launch_noise_grad(c->grads, cfg.K, cfg.P, (float)cfg.grad_sigma, cfg.seed,
+                                      c->d_state, c->stream));
+            break;
+        case QSR_MODEL_LINREG:
+            HIP_TRY(launch_linreg_grad(c->dims, c->params, c->grads, c->model_const, c->workspace,
+                                       c->d_loss, c->d_state, c->stream));
+            break;
+        case QSR_MODEL_MLP2:
+            HIP_TRY(launch_mlp2_grad(c->dims, c->params, c->grads, c->model_const, c->workspace,
+                                     c->d_loss, c->d_state, c->stream));
+            break;
+        default: return QSR_EINVAL;
+        }
+        int rc = br.close(c->t_host);
+        if (rc != QSR_OK) return rc;
+    }
+    {                                                   // OPT for all K workers at once
+        Bracket br(c, 1);
+        if (br.rc != QSR_OK) return br.rc;
+        if (cfg.opt == QSR_OPT_SGDM)
+            HIP_TRY(launch_update_sgdm(c->params, c->grads, c->state0, n, c->d_state, c->d_scal,
+                                       (float)cfg.momentum, (float)cfg.weight_decay, c->stream));
+        else
+            HIP_TRY(launch_update_adamw(c->params, c->grads, c->state0, c->state1, n, c->d_state,
+                                        c->d_scal, (float)(1.0 - cfg.beta1), (float)(1.0 - cfg.beta2),
+                                        (float)cfg.eps, c->stream));
+        int rc = br.close(c->t_host);
+        if (rc != QSR_OK) return rc;
+    }
+    HIP_TRY(launch_sched_tick(c->d_state, c->stream));
+    c->t_host += 1;
+    c->need_sync_call = true;
+    return QSR_OK;
+}
+
+extern "C" int qsr_maybe_sync(qsr_ctx *c)
+{
+    if (!c) return QSR_EINVAL;
+    if (!c->need_sync_call) return QSR_ESTATE;
+    {
+        Bracket br(c, 2);
+        if (br.rc != QSR_OK) return br.rc;
+        HIP_TRY(launch_average_rows(c->params, c->cfg.K, c->cfg.P, c->d_state, c->stream));
+        int rc = br.close(c->t_host);
+        if (rc != QSR_OK) return rc;
+    }
+    HIP_TRY(launch_sched_next_round(c->d_state, c->sp, c->stream));
+    c->need_sync_call = false;
+    return QSR_OK;
+}
+
+static int fetch_state(qsr_ctx *c)
+{
+    HIP_TRY(hipMemcpyAsync(c->h_state, c->d_state, sizeof(DevState), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    return QSR_OK;
+}
+
+extern "C" int qsr_get_H(qsr_ctx *c, int64_t *H, int64_t *round, int64_t *t)
+{
+    if (!c) return QSR_EINVAL;
+    int rc = fetch_state(c);
+    if (rc != QSR_OK) return rc;
+    if (H) *H = c->h_state->H;
+    if (round) *round = c->h_state->s;
+    if (t) *t = c->h_state->t;
+    return QSR_OK;
+}
+
+extern "C" int qsr_read_sync_log(qsr_ctx *c, int64_t *t_out, int64_t *H_out, int64_t cap, int64_t *n)
+{
+    if (!c || !n || cap < 0) return QSR_EINVAL;
+    int rc = fetch_state(c);
+    if (rc != QSR_OK) return rc;
+    long long rounds = c->h_state->s;
+    *n = rounds;
+    long long m = rounds < cap ? rounds : cap;
+    if (m > 0 && t_out) HIP_TRY(hipMemcpy(t_out, c->d_log_t, (size_t)m * sizeof(long long), hipMemcpyDeviceToHost));
+    if (m > 0 && H_out) HIP_TRY(hipMemcpy(H_out, c->d_log_H, (size_t)m * sizeof(long long), hipMemcpyDeviceToHost));
+    return QSR_OK;
+}
+
+extern "C" int qsr_eta_table(qsr_ctx *c, double *eta_out, int64_t cap)
+{
+    if (!c || !eta_out || cap < c->cfg.T) return QSR_EINVAL;
+    std::memcpy(eta_out, c->eta.data(), (size_t)c->cfg.T * sizeof(double));
+    return QSR_OK;
+}
+
+extern "C" int qsr_read_loss(qsr_ctx *c, float *loss_out)
+{
+    if (!c || !loss_out) return QSR_EINVAL;
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    HIP_TRY(hipMemcpy(loss_out, c->d_loss, (size_t)c->cfg.K * sizeof(float), hipMemcpyDeviceToHost));
+    return QSR_OK;
+}
+
+extern "C" int qsr_restart(qsr_ctx *c)
+{
+    if (!c) return QSR_EINVAL;
+    HIP_TRY(launch_sched_init(c->d_state, c->sp, c->stream));
+    c->t_host = 0;
+    c->need_sync_call = false;
+    return QSR_OK;
+}
+
+extern "C" int qsr_timing(qsr_ctx *c, int enable)
+{
+    if (!c) return QSR_EINVAL;
+    c->timing = enable != 0;
+    return QSR_OK;
+}
+
+extern "C" int qsr_read_timing(qsr_ctx *c, double ms[3], int64_t count[3])
+{
+    if (!c || !ms || !count) return QSR_EINVAL;
+    for (int i = 0; i < 3; ++i) { ms[i] = 0.0; count[i] = 0; }
+    int rc = fetch_state(c);
+    if (rc != QSR_OK) return rc;
+    // averaging really ran after exactly the iteration counts in the device's log
+    long long rounds = c->h_state->s;
+    std::vector<long long> log((size_t)rounds);
+    if (rounds > 0) HIP_TRY(hipMemcpy(log.data(), c->d_log_t, (size_t)rounds * sizeof(long long), hipMemcpyDeviceToHost));
+    size_t li = 0;
+    for (auto &p : c->pairs) {
+        float e = 0.f;
+        HIP_TRY(hipEventElapsedTime(&e, p.a, p.b));
+        bool counted = true;
+        if (p.kind == 2) {
+            while (li < log.size() && log[li] < p.t_after) ++li;
+            counted = li < log.size() && log[li] == p.t_after;
+        }
+        if (counted) { ms[p.kind] += (double)e; count[p.kind] += 1; }
+        c->free_events.push_back(p.a);
+        c->free_events.push_back(p.b);
+    }
+    c->pairs.clear();
+    return QSR_OK;
+}
+
+extern "C" int qsr_average_rows(float *buf, int32_t K, int64_t P, void *stream)
+{
+    if (!buf || K < 1 || P < 1 || ((uintptr_t)buf & 15) != 0) return QSR_EINVAL;
+    HIP_TRY(launch_average_rows(buf, K, P, nullptr, (hipStream_t)stream));
+    return QSR_OK;
+}
+
+extern "C" const char *qsr_strerror(int code)
+{
+    switch (code) {
+    case QSR_OK: return "ok";
+    case QSR_EINVAL: return "invalid argument or configuration";
+    case QSR_ESTATE: return "call out of protocol";
+    case QSR_EHIP: return "HIP runtime error";
+    case QSR_ENOMEM: return "workspace too small or allocation failed";
+    case QSR_ENOGPU: return "no gfx950 device";
+    default: return "unknown error";
+    }
+}
+
+extern "C" int qsr_last_hip_error(void) { return g_last_hip; }

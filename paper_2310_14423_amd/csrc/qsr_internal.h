@@ -1,0 +1,94 @@
+// qsr_internal.h -- declarations shared by the library's HIP sources (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "qsr.h"
+
+namespace qsr {
+
+// Scheduler state of Alg. 2 (arXiv 2310.14423), resident in device memory.  Kernels read the
+// iteration counter from here, so the host never has to wait for the device between steps.
+struct DevState {
+    long long t;        // global iterations done
+    long long s;        // finished rounds
+    long long h;        // local steps done in the current round
+    long long H;        // synchronization period of the current round (0 once t == T)
+    int do_sync;        // 1 between the H-th local step of a round and its averaging
+    int pad;
+};
+
+// Per-iteration scalars of the OPT update, prepared on the host in double precision and
+// rounded once to float.  SGD: x = eta_t.  AdamW: x = eta_t*lambda, y = eta_t/(1-beta1^n),
+// z = 1/sqrt(1-beta2^n), n = t+1.
+struct StepScalars {
+    float x, y, z, w;
+};
+
+struct SchedParams {
+    long long T, T_warm;
+    long long H_base;
+    double alpha;
+    const double *eta;      // [T] device
+    long long *log_t;       // [T] device: iteration count at each averaging
+    long long *log_H;       // [T] device: period of each finished round
+};
+
+// 128-bit streaming (non-temporal) global accesses: data touched once per kernel
+typedef float vf4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 ld_nt4(const float4 *p)
+{
+    vf4 v = __builtin_nontemporal_load((const vf4 *)p);
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void st_nt4(float4 *p, float4 v)
+{
+    vf4 w = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(w, (vf4 *)p);
+}
+
+// streams of the counter-based generator (second counter word)
+enum : uint32_t { STREAM_GRAD = 0, STREAM_X = 1, STREAM_NOISE = 2, STREAM_LABEL = 3 };
+
+// ---- launchers (each returns the hipError_t of its launch) --------------------------------
+hipError_t launch_sched_init(DevState *st, SchedParams sp, hipStream_t s);
+hipError_t launch_sched_tick(DevState *st, hipStream_t s);
+hipError_t launch_sched_next_round(DevState *st, SchedParams sp, hipStream_t s);
+
+hipError_t launch_update_sgdm(float *theta, const float *g, float *buf, long long n,
+                              const DevState *st, const StepScalars *sc, float mu, float lambda,
+                              hipStream_t s);
+hipError_t launch_update_adamw(float *theta, const float *g, float *m, float *v, long long n,
+                               const DevState *st, const StepScalars *sc, float c1, float c2,
+                               float eps, hipStream_t s);
+
+// mean over the K rows of buf [K][P], written to all rows; skipped on the device when
+// st != nullptr and st->do_sync == 0
+hipError_t launch_average_rows(float *buf, int K, long long P, const DevState *st, hipStream_t s);
+
+hipError_t launch_broadcast_rows(float *dst, const float *src, int K, long long P, hipStream_t s);
+hipError_t launch_fill_zero(float *dst, long long n, hipStream_t s);
+
+// out[k][i] = sigma * z, z ~ N(0,1) keyed (seed; i/4, stream, k, st->t); out is [K][n]
+hipError_t launch_fill_normal(float *out, int K, long long n, float sigma, uint32_t stream,
+                              uint64_t seed, const DevState *st, hipStream_t s);
+hipError_t launch_noise_grad(float *g, int K, long long P, float sigma, uint64_t seed,
+                             const DevState *st, hipStream_t s);
+
+struct ModelDims {
+    int K;
+    long long P, B, d_in, d_hidden, d_out;
+    int n_blocks;
+    float data_sigma;
+    uint64_t seed;
+};
+
+size_t linreg_workspace_bytes(const ModelDims &d);
+hipError_t launch_linreg_grad(const ModelDims &d, const float *theta, float *g, const float *wstar,
+                              void *ws, float *loss, const DevState *st, hipStream_t s);
+
+size_t mlp2_workspace_bytes(const ModelDims &d);
+hipError_t launch_mlp2_grad(const ModelDims &d, const float *theta, float *g, const float *means,
+                            void *ws, float *loss, const DevState *st, hipStream_t s);
+
+}  // namespace qsr

@@ -1,0 +1,88 @@
+"""Host-only checks of the C-ABI library: it loads without a GPU, exports every symbol the
+header declares, and rejects bad configurations before touching the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2310_14423_amd as qsr
+import workloads
+from paper_2310_14423_amd.binding import make_config
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "qsr.h")).read()
+    declared = set(re.findall(r"\b(qsr_[a-z_A-Z]+)\s*\(", hdr))
+    assert declared == set(qsr.EXPORTS)
+    L = C.CDLL(qsr.lib_path())
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_strerror():
+    L = qsr.lib()
+    assert L.qsr_strerror(0) == b"ok"
+    for code in (-1, -2, -3, -4, -5):
+        assert len(L.qsr_strerror(code)) > 3
+    assert L.qsr_strerror(-99) == b"unknown error"
+
+
+@pytest.mark.parametrize("name", ["lsq", "mlp", "flat60m", "flat350m"])
+def test_named_workloads_validate(name):
+    cfg, keep = make_config(workloads.get(name))
+    assert qsr.validate(cfg) == (0, "ok")
+    assert qsr.workspace_bytes(cfg) >= 0
+
+
+@pytest.mark.parametrize("field,value,why", [
+    ("K", 0, "K"), ("P", 0, "P"), ("T", 0, "T"), ("T_warm", -1, "T_warm"), ("T_warm", 6000, "T_warm"),
+    ("opt", 2, "opt"), ("model", 5, "model"), ("lr_kind", 3, "lr_kind"), ("H_base", 0, "H_base"),
+    ("alpha", -0.1, "alpha"), ("alpha", float("nan"), "alpha"), ("eta_max", 0.0, "eta_max"),
+    ("eta_min", 1.0, "eta_min"), ("beta2", 1.0, "beta1/beta2"), ("eps", 0.0, "eps"),
+    ("weight_decay", -1.0, "weight_decay"), ("grad_sigma", -1.0, "grad_sigma"), ("reserved", 1, "reserved"),
+])
+def test_bad_configurations_are_rejected(field, value, why):
+    cfg, keep = make_config(workloads.get("flat60m"))
+    setattr(cfg, field, value)
+    rc, msg = qsr.validate(cfg)
+    assert rc == -1 and msg == why
+    n = C.c_size_t(7)
+    assert qsr.lib().qsr_workspace_bytes(C.byref(cfg), C.byref(n)) == -1 and n.value == 0
+    out = C.c_void_p(1)
+    rc = qsr.lib().qsr_init(C.byref(cfg), C.c_void_p(16), C.c_void_p(16), C.c_void_p(16), C.c_void_p(16),
+                            None, None, None, C.c_size_t(0), C.byref(out))
+    assert rc == -1 and not out.value
+
+
+def test_model_shape_checks():
+    cfg, _ = make_config(workloads.get("mlp"))
+    cfg.P += 1
+    assert qsr.validate(cfg)[0] == -1
+    cfg, _ = make_config(workloads.get("lsq"))
+    cfg.d_in = 1000
+    assert qsr.validate(cfg)[0] == -1
+
+
+def test_null_arguments():
+    L = qsr.lib()
+    assert L.qsr_validate(None, None) == -1
+    assert L.qsr_local_step(None) == -1 and L.qsr_maybe_sync(None) == -1
+    assert L.qsr_get_H(None, None, None, None) == -1
+    assert L.qsr_destroy(None) == -1
+    assert L.qsr_average_rows(None, 2, C.c_int64(8), None) == -1
+    cfg, _ = make_config(workloads.get("flat60m"))
+    out = C.c_void_p()
+    # NULL / misaligned buffers, missing second moment for AdamW
+    assert L.qsr_init(C.byref(cfg), None, C.c_void_p(16), C.c_void_p(16), C.c_void_p(16), None, None, None,
+                      C.c_size_t(0), C.byref(out)) == -1
+    assert L.qsr_init(C.byref(cfg), C.c_void_p(20), C.c_void_p(16), C.c_void_p(16), C.c_void_p(16), None, None,
+                      None, C.c_size_t(0), C.byref(out)) == -1
+    assert L.qsr_init(C.byref(cfg), C.c_void_p(16), C.c_void_p(16), C.c_void_p(16), None, None, None, None,
+                      C.c_size_t(0), C.byref(out)) == -1
+    # model workloads need their workspace and constants
+    cfg, keep = make_config(workloads.get("lsq"))
+    assert L.qsr_init(C.byref(cfg), C.c_void_p(16), C.c_void_p(16), C.c_void_p(16), None, None, None, None,
+                      C.c_size_t(0), C.byref(out)) == -1

@@ -1,0 +1,247 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the same seeded
+inputs.  Integers (H schedule, averaging points) bit-exact; fp32 parameters within
+RTOL_F32 = 1e-5 (see tests/util.py)."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from util import assert_params_close, eta_of, gpu_ctx, oracle_run
+
+pytestmark = pytest.mark.gpu
+
+
+def _ext_workload(opt, K, P, T, **kw):
+    w = dict(model="external", K=K, P=P, T=T, T_warm=kw.pop("T_warm", 0), opt=opt, lr="cosine",
+             eta_max=kw.pop("eta_max", 0.05), eta_min=0.0, H_base=kw.pop("H_base", 3),
+             alpha=kw.pop("alpha", 0.12), seed=1)
+    w.update(kw)
+    return w
+
+
+@pytest.mark.parametrize("opt,kw", [
+    ("adamw", dict(beta1=0.9, beta2=0.999, eps=1e-8, lam=0.05)),
+    ("adamw", dict(beta1=0.8, beta2=0.95, eps=1e-6, lam=0.0)),
+    ("sgdm", dict(mu=0.9, lam=5e-4)),
+    ("sgdm", dict(mu=0.0, lam=0.0)),
+])
+@pytest.mark.parametrize("K,P", [(3, 4099), (1, 5), (16, 65536 + 4), (2, 1 << 20)])
+def test_update_and_averaging_with_external_gradients(opt, kw, K, P):
+    import torch
+    T = 40
+    w = _ext_workload(opt, K, P, T, T_warm=4, **kw)
+    rng = np.random.default_rng(K * 1000 + P % 997)
+    th0 = rng.standard_normal(P).astype(np.float32)
+    ctx = gpu_ctx(w, theta0=th0)
+    orc = oracle_run(w, theta0=th0)
+    assert np.array_equal(ctx.eta_table(), orc.eta)
+    for t in range(T):
+        g = (rng.standard_normal((K, P)) * rng.choice([1e-3, 1.0, 30.0])).astype(np.float32)
+        ctx.grads.copy_(torch.from_numpy(g))
+        ctx.step()
+        orc.step(1, ext_g=g[None].astype(np.float64))
+        if t in (0, 1, 7, T - 1) or orc.state.h == 0:
+            H, s, tt = ctx.get_H()
+            assert (s, tt) == (orc.rounds, orc.t)
+            assert_params_close(ctx.params.cpu().numpy(), orc.theta, what="%s t=%d" % (opt, t))
+            if orc.state.h == 0:          # just averaged: every replica holds the same bits
+                p = ctx.params.cpu().numpy()
+                assert all(np.array_equal(p[k], p[0]) for k in range(K))
+    st, Hs = ctx.read_sync_log()
+    assert list(st) == list(orc.sync_log) and list(Hs) == list(orc.H_log)
+    assert st[-1] == T
+    # optimizer state is local: never averaged, compare it too
+    assert_params_close(ctx.state0.cpu().numpy(), orc.st0, what="state0")
+    if opt == "adamw":
+        assert_params_close(ctx.state1.cpu().numpy(), orc.st1, what="state1")
+    ctx.close()
+
+
+@pytest.mark.parametrize("K,P", [(1, 7), (2, 4096), (3, 1001), (16, 40000), (32, 12345), (5, 1 << 18)])
+def test_average_rows(K, P):
+    import torch
+    import paper_2310_14423_amd as qsr
+    rng = np.random.default_rng(K + P)
+    a = (rng.standard_normal((K, P)) * 3 + 1).astype(np.float32)
+    buf = torch.from_numpy(a).cuda()
+    qsr.average_rows(buf)
+    out = buf.cpu().numpy()
+    ref = a.astype(np.float64)
+    oracle.average(ref)
+    assert all(np.array_equal(out[k], out[0]) for k in range(K))
+    assert np.max(np.abs(out - ref) / np.abs(a).mean(axis=0)) <= 2.0**-22
+    if K & (K - 1) == 0:                 # power of two: averaging identical rows is exact
+        qsr.average_rows(buf)
+        assert np.array_equal(buf.cpu().numpy(), out)
+
+
+def test_noise_gradient_stream_matches_the_oracle():
+    w = workloads.get("flat60m", K=3, P=40003, T=8)
+    ctx = gpu_ctx(w)
+    orc = oracle_run(w)
+    for t in range(3):
+        ctx.local_step()                 # fills grads with the draws of iteration t
+        g = ctx.grads.cpu().numpy()
+        for k in range(3):
+            want, _ = orc.grad(k, t)
+            # same uint32 stream (else nothing would match), normals to a few ulp
+            assert np.max(np.abs(g[k] - want)) <= 2e-6 * 1e-3
+        ctx.maybe_sync()
+    ctx.close()
+
+
+@pytest.mark.parametrize("name", ["lsq", "mlp", "flat60m", "resmlp", "flat350m"])
+def test_schedule_is_bit_exact_for_the_full_run(name):
+    """The H sequence and averaging points do not depend on P: run every workload's schedule
+    for its full T on a tiny optimizer-only problem and compare integers with the oracle."""
+    w0 = workloads.get(name)
+    w = dict(w0, model="noise", P=8, K=2, grad_sigma=1e-3)
+    ctx = gpu_ctx(w, theta0=np.zeros(8, np.float32))
+    eta = eta_of(w0)
+    assert np.array_equal(ctx.eta_table(), eta)
+    H, st = oracle.schedule(eta, w0.get("T_warm", 0), w0["H_base"], w0["alpha"])
+    assert ctx.get_H()[0] == H[0]
+    ctx.step(w0["T"])
+    gt, gH = ctx.read_sync_log()
+    assert list(gt) == list(st) and list(gH) == list(H)
+    assert ctx.get_H() == (0, len(H), w0["T"])
+    ctx.close()
+
+
+def test_flat_adamw_full_schedule_sampled_elements():
+    """Optimizer-only workload, all 5000 iterations and 8 rounds, P shrunk to 2^20 + 4; the
+    oracle follows 2048 sampled parameters (the update is element-wise and the draws are keyed
+    by the global parameter index)."""
+    w = workloads.get("flat60m", P=(1 << 20) + 4)
+    rng = np.random.default_rng(0)
+    idx = np.sort(rng.choice(w["P"], 2048, replace=False)).astype(np.int64)
+    idx[0], idx[-1] = 0, w["P"] - 1
+    ctx = gpu_ctx(w)
+    orc = oracle_run(w, p_idx=idx)
+    done = 0
+    for upto in (1, 306, 617, 2000, 5000):
+        ctx.step(upto - done); orc.step(upto - done); done = upto
+        p = ctx.params[:, torch_idx(idx)].cpu().numpy()
+        assert_params_close(p, orc.theta, what="t=%d" % upto)
+    st, Hs = ctx.read_sync_log()
+    assert list(st) == [306, 617, 947, 1313, 1747, 2325, 3319, 5000] == list(orc.sync_log)
+    ctx.close()
+
+
+def torch_idx(idx):
+    import torch
+    return torch.from_numpy(idx).cuda()
+
+
+def test_lsq_full_run():
+    w = workloads.get("lsq")
+    ctx = gpu_ctx(w)
+    orc = oracle_run(w, n_threads=4)
+    done = 0
+    for upto in (1, 4, 5, 56, 137, 256):
+        ctx.step(upto - done); orc.step(upto - done); done = upto
+        assert_params_close(ctx.params.cpu().numpy(), orc.theta, what="lsq t=%d" % upto)
+    st, Hs = ctx.read_sync_log()
+    assert list(st) == list(orc.sync_log) and len(st) == 28
+    ctx.close()
+
+
+def test_lsq_gradient_and_loss_single_step():
+    w = workloads.get("lsq", d_in=203, B_loc=19, K=3, T=6)
+    rng = np.random.default_rng(3)
+    th0 = rng.standard_normal(203).astype(np.float32)
+    ctx = gpu_ctx(w, theta0=th0)
+    orc = oracle_run(w, theta0=th0)
+    ctx.local_step()
+    g = ctx.grads.cpu().numpy()
+    for k in range(3):
+        want, loss = orc.grad(k, 0, th0.astype(np.float64))
+        assert_params_close(g[k], want, what="lsq grad")
+        assert ctx.read_loss()[k] == pytest.approx(loss, rel=1e-5)
+    ctx.close()
+
+
+@pytest.mark.parametrize("dims", [dict(d_in=13, d_hidden=17, d_out=5, B_loc=11, K=2),
+                                  dict(d_in=70, d_hidden=130, d_out=10, B_loc=67, K=3)])
+def test_mlp2_gradient_single_step(dims):
+    w = workloads.get("mlp", T=4, **dims)
+    ctx = gpu_ctx(w)
+    orc = oracle_run(w)
+    th0 = workloads.theta0(w).astype(np.float64)
+    ctx.local_step()
+    g = ctx.grads.cpu().numpy()
+    for k in range(dims["K"]):
+        want, loss = orc.grad(k, 0, th0)
+        assert_params_close(g[k], want, what="mlp2 grad k=%d" % k)
+        assert ctx.read_loss()[k] == pytest.approx(loss, rel=1e-5)
+    ctx.close()
+
+
+def _load_oracle_state(ctx, orc):
+    """Overwrite the GPU run's (caller-owned) parameter and optimizer-state buffers with the
+    oracle's, rounded to fp32."""
+    import torch
+    ctx.params.copy_(torch.from_numpy(orc.theta.astype(np.float32)))
+    ctx.state0.copy_(torch.from_numpy(orc.st0.astype(np.float32)))
+    if ctx.state1 is not None:
+        ctx.state1.copy_(torch.from_numpy(orc.st1.astype(np.float32)))
+
+
+def test_mlp2_reduced_full_schedule():
+    """Reduced width, the workload's own schedule (T = 2000, 307 rounds).  Training a ReLU
+    network is a nonlinear iteration: rounding differences between an fp32 and an fp64
+    trajectory are amplified from step to step, so the free-running comparison is held to
+    1e-5 only over the first 100 iterations and to 1e-3 after that, while every 50-iteration
+    segment restarted from the oracle's state is held to 1e-5."""
+    w = workloads.get("mlp", d_in=24, d_hidden=40, d_out=10, B_loc=16, K=3, eta_max=0.05)
+    ctx = gpu_ctx(w)
+    orc = oracle_run(w, n_threads=3)
+    done = 0
+    for upto in (4, 100, 1000, 2000):
+        ctx.step(upto - done); orc.step(upto - done); done = upto
+        assert_params_close(ctx.params.cpu().numpy(), orc.theta, rtol=1e-5 if upto <= 100 else 1e-3,
+                            what="mlp2 free-running t=%d" % upto)
+    st, Hs = ctx.read_sync_log()
+    assert len(st) == 307 and list(st) == list(orc.sync_log)
+    ctx.close()
+
+    ctx = gpu_ctx(w)
+    orc = oracle_run(w, n_threads=3)
+    for seg in range(40):
+        _load_oracle_state(ctx, orc)
+        ctx.step(50); orc.step(50)
+        assert_params_close(ctx.params.cpu().numpy(), orc.theta, what="mlp2 segment %d" % seg)
+        assert_params_close(ctx.state0.cpu().numpy(), orc.st0, what="mlp2 momentum, segment %d" % seg)
+    assert ctx.get_H() == (0, 307, 2000)
+    ctx.close()
+
+
+def test_mlp2_full_size_first_steps():
+    w = workloads.get("mlp")
+    ctx = gpu_ctx(w)
+    orc = oracle_run(w, n_threads=8)
+    ctx.step(1); orc.step(1)
+    assert_params_close(ctx.params.cpu().numpy(), orc.theta, what="mlp full t=1")
+    ctx.step(3); orc.step(3)
+    assert_params_close(ctx.params.cpu().numpy(), orc.theta, rtol=1e-4, what="mlp full t=4")
+    assert ctx.get_H()[1] == 1
+    ctx.close()
+
+
+def test_protocol_errors():
+    import paper_2310_14423_amd as qsr
+    w = _ext_workload("sgdm", 2, 8, 2, mu=0.5, lam=0.0)
+    ctx = gpu_ctx(w, theta0=np.zeros(8, np.float32))
+    with pytest.raises(qsr.QSRError):
+        ctx.maybe_sync()                  # nothing to close
+    ctx.local_step()
+    with pytest.raises(qsr.QSRError):
+        ctx.local_step()                  # maybe_sync missing
+    ctx.maybe_sync(); ctx.step()
+    with pytest.raises(qsr.QSRError) as e:
+        ctx.local_step()                  # past T
+    assert e.value.code == -2
+    ctx.restart()
+    ctx.step(2)
+    assert ctx.get_H() == (0, 1, 2)
+    ctx.close()

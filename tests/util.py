@@ -1,0 +1,56 @@
+"""Helpers shared by the tests: build the oracle run and the GPU context of one workload
+from the same dictionary, and compare parameters to the stated tolerance."""
+import numpy as np
+
+import oracle
+import workloads
+
+
+def eta_of(w):
+    if w["lr"] == "cosine":
+        return oracle.lr_cosine(w["T"], w.get("T_warm", 0), w["eta_max"], w.get("eta_min", 0.0))
+    if w["lr"] == "step":
+        return oracle.lr_step(w["T"], w.get("T_warm", 0), w["eta_max"], list(w["milestones"]), w["factor"])
+    raise ValueError(w["lr"])
+
+
+def oracle_run(w, p_idx=None, n_threads=8, theta0=None, eta=None):
+    n = w["P"] if p_idx is None else len(p_idx)
+    th0 = workloads.theta0(w) if theta0 is None else theta0
+    if p_idx is not None:
+        th0 = np.asarray(th0)[p_idx]
+    return oracle.Run(K=w["K"], n=n, eta=eta_of(w) if eta is None else eta, T_warm=w.get("T_warm", 0),
+                      opt=w["opt"], mu=w.get("mu", 0.0), beta1=w.get("beta1", 0.9),
+                      beta2=w.get("beta2", 0.999), eps=w.get("eps", 1e-8), lam=w.get("lam", 0.0),
+                      H_base=w["H_base"], alpha=w["alpha"], model=w["model"], seed=w.get("seed", 0),
+                      grad_sigma=w.get("grad_sigma", 0.0), data_sigma=w.get("data_sigma", 0.0),
+                      B_loc=w.get("B_loc", 0), d_in=w.get("d_in", 0), d_hidden=w.get("d_hidden", 0),
+                      d_out=w.get("d_out", 0), n_blocks=w.get("n_blocks", 0),
+                      model_const=workloads.model_const(w), p_idx=p_idx, theta0=th0,
+                      n_threads=n_threads)
+
+
+def gpu_ctx(w, theta0=None, eta_table=None):
+    import paper_2310_14423_amd as qsr
+    th0 = workloads.theta0(w) if theta0 is None else theta0
+    return qsr.Context(w, theta0=th0, model_const=workloads.model_const(w), eta_table=eta_table)
+
+
+# fp32 tolerance of the parameter comparison: |gpu - oracle| <= RTOL * (|oracle| + rms(oracle)).
+# The rms term is the absolute floor for parameters that pass close to zero: an fp32 state
+# cannot track them to a relative 1e-5 of their own (tiny) value.
+RTOL_F32 = 1e-5
+
+
+def assert_params_close(gpu, orc, rtol=RTOL_F32, what=""):
+    gpu = np.asarray(gpu, dtype=np.float64)
+    orc = np.asarray(orc, dtype=np.float64)
+    assert gpu.shape == orc.shape
+    assert np.all(np.isfinite(gpu)), what
+    rms = np.sqrt(np.mean(orc * orc))
+    err = np.abs(gpu - orc)
+    bound = rtol * (np.abs(orc) + rms)
+    worst = np.max(err - bound)
+    assert worst <= 0, "%s: max |diff| %.3e, max ratio to bound %.3f (rms %.3e)" % (
+        what, err.max(), np.max(err / np.maximum(bound, 1e-300)), rms)
+    return float(np.max(err / np.maximum(bound, 1e-300)))
