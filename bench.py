@@ -1,0 +1,162 @@
+#!/usr/bin/env python3
+"""Benchmark of the QSR hot path on one MI355X.
+
+One "step" = one global iteration of Local OPT for all K workers: local gradients, the fused
+optimizer update, the device-side scheduler tick, and -- when the round's H-th step has run --
+the K-axis replica averaging and the next H from the quadratic rule.  The default workload is
+the optimizer-only 60 M-parameter, 16-replica Local AdamW run (T = 5000, 8 rounds): with the
+default --steps the timed region is exactly one complete run, all averaging rounds included.
+
+Prints ONE JSON line (see README for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
+BYTES_PER_UPDATE = {"adamw": 28, "sgdm": 20}   # algorithmic HBM bytes per replica-parameter
+BYTES_PER_AVERAGE = 8
+
+
+def cpu_baseline(w, seconds_target=15.0):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload."""
+    import numpy as np
+    import oracle
+    oracle.build()
+    threads = max(1, min(w["K"], os.cpu_count() or 1, 16))
+    P = min(w["P"], 1 << 18)
+    if w["model"] != "noise":
+        return None
+
+    def run(steps):
+        eta = oracle.lr_cosine(w["T"], w.get("T_warm", 0), w["eta_max"], w.get("eta_min", 0.0))
+        r = oracle.Run(K=w["K"], n=P, eta=eta, T_warm=w.get("T_warm", 0), opt=w["opt"],
+                       beta1=w["beta1"], beta2=w["beta2"], eps=w["eps"], lam=w["lam"],
+                       H_base=1, alpha=0.0, model="noise", seed=w["seed"],
+                       grad_sigma=w["grad_sigma"], n_threads=threads)
+        t0 = time.perf_counter()
+        r.step(steps)                 # H = 1: every step also averages, like the GPU's worst case
+        return time.perf_counter() - t0
+
+    t1 = run(2)
+    steps = int(max(2, min(200, seconds_target / max(t1 / 2, 1e-3))))
+    dt = run(steps)
+    return {"value": w["K"] * P * steps / dt, "unit": "replica-param updates/s", "cores": threads,
+            "kind": "oracle",
+            "sample": "K=%d, P=%d (of %d), %d iterations of noise gradient + AdamW + averaging "
+                      "every step, double precision, %.1f s wall" % (w["K"], P, w["P"], steps, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="flat60m", choices=["flat60m", "flat350m", "lsq", "mlp"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true",
+                    help="skip the per-kernel HIP events (the roofline object is then null)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (K simulated workers on one MI355X); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import workloads
+    import paper_2310_14423_amd as qsr
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    w = workloads.get(args.workload)
+    K, P, T = w["K"], w["P"], w["T"]
+    steps = args.steps if args.steps is not None else T
+    ctx = qsr.Context(w, theta0=workloads.theta0(w), model_const=workloads.model_const(w))
+
+    ctx.step(min(args.warmup, T))
+    ctx.restart()                              # the timed region starts a run at t = 0
+    ctx.timing(not args.no_kernel_timing)
+    ms = [0.0, 0.0, 0.0]
+    cnt = [0, 0, 0]
+    rounds = 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    left = steps
+    while left > 0:
+        n = min(left, T)
+        ctx.step(n)
+        left -= n
+        if left > 0 or n == T:                 # a run is complete: collect, start the next one
+            m, c = ctx.read_timing() if not args.no_kernel_timing else ([0] * 3, [0] * 3)
+            ms = [a + b for a, b in zip(ms, m)]; cnt = [a + b for a, b in zip(cnt, c)]
+            rounds += ctx.get_H()[1]
+            if left > 0:
+                ctx.restart()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    if steps % T != 0:
+        m, c = ctx.read_timing() if not args.no_kernel_timing else ([0] * 3, [0] * 3)
+        ms = [a + b for a, b in zip(ms, m)]; cnt = [a + b for a, b in zip(cnt, c)]
+        rounds += ctx.get_H()[1]
+    ctx.timing(False)
+
+    upd_bytes = BYTES_PER_UPDATE[w["opt"]] * K * P
+    roofline = None
+    kernels = {}
+    if cnt[1] > 0:
+        upd_ms = ms[1] / cnt[1]
+        ach = upd_bytes / (upd_ms * 1e-3) / 1e9
+        roofline = {"kernel": "update_%s_kernel" % w["opt"], "bound": "hbm", "achieved": ach,
+                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None,
+                    "avg_ms": upd_ms, "launches": cnt[1],
+                    "bytes_per_launch": upd_bytes}
+        kernels["update_ms_avg"] = upd_ms
+        if cnt[0] > 0:
+            kernels["gradient_ms_avg"] = ms[0] / cnt[0]
+        if cnt[2] > 0:
+            avg_ms = ms[2] / cnt[2]
+            kernels["average_in_run_ms_avg"] = avg_ms
+            kernels["average_in_run_GBs"] = BYTES_PER_AVERAGE * K * P / (avg_ms * 1e-3) / 1e9
+            kernels["average_in_run_launches"] = cnt[2]
+
+    # the averaging kernel runs only a handful of times per run: time it in a loop of its own
+    reps = 20
+    qsr.average_rows(ctx.params)
+    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        qsr.average_rows(ctx.params)
+    e1.record(); torch.cuda.synchronize()
+    a_ms = e0.elapsed_time(e1) / reps
+    kernels["average_standalone_ms_avg"] = a_ms
+    kernels["average_standalone_GBs"] = BYTES_PER_AVERAGE * K * P / (a_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "replica-param updates/s", "value": K * P * steps / dt, "unit": "updates/s",
+        "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": dt * 1e3 / steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "K": K, "P": P, "T": T, "optimizer": w["opt"],
+                   "model": w["model"], "H_base": w["H_base"], "alpha": w["alpha"],
+                   "lr": w["lr"], "eta_max": w["eta_max"]},
+        "sync_rounds": rounds,
+        "hbm_GBs_update": roofline["achieved"] if roofline else None,
+        "kernels": kernels,
+        "roofline": roofline,
+    }
+    ctx.close()
+    del ctx
+    torch.cuda.empty_cache()
+    out["cpu_baseline"] = None if args.no_cpu_baseline else cpu_baseline(w)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
