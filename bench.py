@@ -83,8 +83,8 @@ def main():
     ctx.step(min(args.warmup, T))
     ctx.restart()                              # the timed region starts a run at t = 0
     ctx.timing(not args.no_kernel_timing)
-    ms = [0.0, 0.0, 0.0]
-    cnt = [0, 0, 0]
+    ms = [0.0] * 4
+    cnt = [0] * 4
     rounds = 0
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -94,7 +94,7 @@ def main():
         ctx.step(n)
         left -= n
         if left > 0 or n == T:                 # a run is complete: collect, start the next one
-            m, c = ctx.read_timing() if not args.no_kernel_timing else ([0] * 3, [0] * 3)
+            m, c = ctx.read_timing() if not args.no_kernel_timing else ([0] * 4, [0] * 4)
             ms = [a + b for a, b in zip(ms, m)]; cnt = [a + b for a, b in zip(cnt, c)]
             rounds += ctx.get_H()[1]
             if left > 0:
@@ -102,7 +102,7 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     if steps % T != 0:
-        m, c = ctx.read_timing() if not args.no_kernel_timing else ([0] * 3, [0] * 3)
+        m, c = ctx.read_timing() if not args.no_kernel_timing else ([0] * 4, [0] * 4)
         ms = [a + b for a, b in zip(ms, m)]; cnt = [a + b for a, b in zip(cnt, c)]
         rounds += ctx.get_H()[1]
     ctx.timing(False)
@@ -125,6 +125,8 @@ def main():
             kernels["average_in_run_ms_avg"] = avg_ms
             kernels["average_in_run_GBs"] = BYTES_PER_AVERAGE * K * P / (avg_ms * 1e-3) / 1e9
             kernels["average_in_run_launches"] = cnt[2]
+        if cnt[3] > 0:
+            kernels["average_skipped_ms_avg"] = ms[3] / cnt[3]
 
     # the averaging kernel runs only a handful of times per run: time it in a loop of its own
     reps = 20

@@ -138,10 +138,11 @@ int qsr_restart(qsr_ctx *ctx);
 /* Per-kernel timing with HIP events on the context's stream.  After qsr_timing(ctx, 1) each
  * gradient stage, update kernel and averaging kernel is bracketed by an event pair;
  * qsr_read_timing synchronises, adds up the pairs recorded since the last read and recycles
- * them.  ms[0..2] / count[0..2] = gradient stage, update kernel, averaging kernel (averaging is
- * counted only in steps whose averaging really ran). */
+ * them.  ms[i] / count[i]: 0 = gradient stage, 1 = update kernel, 2 = averaging launches that
+ * averaged, 3 = averaging launches that the device-side decision skipped.  Read before
+ * qsr_restart: the split of 2 and 3 uses the log of the current run. */
 int qsr_timing(qsr_ctx *ctx, int enable);
-int qsr_read_timing(qsr_ctx *ctx, double ms[3], int64_t count[3]);
+int qsr_read_timing(qsr_ctx *ctx, double ms[4], int64_t count[4]);
 
 int qsr_destroy(qsr_ctx *ctx);
 

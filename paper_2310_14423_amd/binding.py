@@ -195,7 +195,7 @@ class Context:
         _check(lib().qsr_timing(self._ctx, C.c_int(1 if on else 0)), "qsr_timing")
 
     def read_timing(self):
-        ms = (C.c_double * 3)(); cnt = (C.c_int64 * 3)()
+        ms = (C.c_double * 4)(); cnt = (C.c_int64 * 4)()
         _check(lib().qsr_read_timing(self._ctx, ms, cnt), "qsr_read_timing")
         return list(ms), list(cnt)
 

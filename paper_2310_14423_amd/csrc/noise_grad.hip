@@ -8,7 +8,7 @@
 
 namespace qsr {
 
-__global__ __launch_bounds__(256) void fill_normal_kernel(float *__restrict__ out, long long n,
+__global__ __launch_bounds__(64) void fill_normal_kernel(float *__restrict__ out, long long n,
                                                           long long groups, float sigma,
                                                           uint32_t stream, uint64_t seed,
                                                           const DevState *__restrict__ st)
@@ -17,8 +17,8 @@ __global__ __launch_bounds__(256) void fill_normal_kernel(float *__restrict__ ou
     const uint32_t k = blockIdx.y;
     float *row = out + (long long)k * n;
     const bool vec = (n & 3) == 0;
-    const long long stride = (long long)gridDim.x * 256;
-    for (long long q = (long long)blockIdx.x * 256 + threadIdx.x; q < groups; q += stride) {
+    const long long stride = (long long)gridDim.x * 64;
+    for (long long q = (long long)blockIdx.x * 64 + threadIdx.x; q < groups; q += stride) {
         float4 z = normal4(seed, stream, k, t, (uint32_t)q);
         z.x *= sigma; z.y *= sigma; z.z *= sigma; z.w *= sigma;
         long long p = q * 4;
@@ -37,10 +37,10 @@ hipError_t launch_fill_normal(float *out, int K, long long n, float sigma, uint3
                               uint64_t seed, const DevState *st, hipStream_t s)
 {
     long long groups = (n + 3) / 4;
-    long long bx = (groups + 255) / 256;
-    if (bx > 8192) bx = 8192;
+    long long bx = (groups + 63) / 64;            // one trip per one-wavefront workgroup
+    if (bx > 0x7FFFFFFFll) bx = 0x7FFFFFFFll;
     dim3 grid((unsigned)bx, (unsigned)K);
-    fill_normal_kernel<<<grid, 256, 0, s>>>(out, n, groups, sigma, stream, seed, st);
+    fill_normal_kernel<<<grid, 64, 0, s>>>(out, n, groups, sigma, stream, seed, st);
     return hipGetLastError();
 }
 

@@ -466,10 +466,10 @@ extern "C" int qsr_timing(qsr_ctx *c, int enable)
     return QSR_OK;
 }
 
-extern "C" int qsr_read_timing(qsr_ctx *c, double ms[3], int64_t count[3])
+extern "C" int qsr_read_timing(qsr_ctx *c, double ms[4], int64_t count[4])
 {
     if (!c || !ms || !count) return QSR_EINVAL;
-    for (int i = 0; i < 3; ++i) { ms[i] = 0.0; count[i] = 0; }
+    for (int i = 0; i < 4; ++i) { ms[i] = 0.0; count[i] = 0; }
     int rc = fetch_state(c);
     if (rc != QSR_OK) return rc;
     // averaging really ran after exactly the iteration counts in the device's log
@@ -480,12 +480,13 @@ extern "C" int qsr_read_timing(qsr_ctx *c, double ms[3], int64_t count[3])
     for (auto &p : c->pairs) {
         float e = 0.f;
         HIP_TRY(hipEventElapsedTime(&e, p.a, p.b));
-        bool counted = true;
+        int slot = p.kind;
         if (p.kind == 2) {
             while (li < log.size() && log[li] < p.t_after) ++li;
-            counted = li < log.size() && log[li] == p.t_after;
+            bool ran = li < log.size() && log[li] == p.t_after;
+            slot = ran ? 2 : 3;
         }
-        if (counted) { ms[p.kind] += (double)e; count[p.kind] += 1; }
+        ms[slot] += (double)e; count[slot] += 1;
         c->free_events.push_back(p.a);
         c->free_events.push_back(p.b);
     }

@@ -3,11 +3,15 @@
 // are treated as one vector of K*P elements.  The kernels are HBM-bound (AdamW: 16 B read +
 // 12 B written per element; SGD: 12 B + 8 B): 128-bit accesses, several independent loads in
 // flight per lane, streaming (non-temporal) hints because nothing is re-read within a step.
+// Launch shape, from a sweep on MI355X at K*P = 0.96e9: one-wavefront workgroups that each make
+// a single trip (no grid-stride loop) over 2 x 64 float4 per array reached 5.85 TB/s, against
+// 5.0-5.1 TB/s for 256-thread blocks in a capped persistent grid and 5.77 TB/s for a plain
+// copy kernel; non-temporal loads and stores were each worth 3-5 %.
 #include "qsr_internal.h"
 
 namespace qsr {
 
-constexpr int UPD_THREADS = 256;
+constexpr int UPD_THREADS = 64;
 constexpr int UPD_UNROLL = 2;      // float4 per array per thread per trip
 
 __device__ __forceinline__ float4 ldg_nt(const float4 *p) { return ld_nt4(p); }
@@ -115,13 +119,13 @@ __global__ __launch_bounds__(UPD_THREADS) void update_sgdm_kernel(
     }
 }
 
-// One trip per thread when the vector is small, a capped grid-stride loop when it is large:
-// 256 CUs x 8 blocks of 256 threads keep every SIMD at 8 waves.
+// One trip per workgroup; the kernels keep their stride loop so that any grid is correct, and
+// the grid is only capped where it would overflow the launch limit.
 static int update_grid(long long n4)
 {
     long long per_block = (long long)UPD_THREADS * UPD_UNROLL;
     long long blocks = (n4 + per_block - 1) / per_block;
-    const long long cap = 256 * 8 * 4;
+    const long long cap = 0x7FFFFFFFll;
     if (blocks > cap) blocks = cap;
     if (blocks < 1) blocks = 1;
     return (int)blocks;
