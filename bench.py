@@ -22,6 +22,24 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
 BYTES_PER_UPDATE = {"adamw": 28, "sgdm": 20}   # algorithmic HBM bytes per replica-parameter
 BYTES_PER_AVERAGE = 8
 
+# HBM bytes per launch of the update kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE (scaled by a
+# kernel of known size; profiles/flat60m_hbm_traffic_pmc.md).  Valid only for the kernel source
+# the counters were taken on: keyed by the first 16 hex digits of its SHA-256.
+PMC_TRAFFIC = {"flat60m": {"source": "update.hip", "sha256_16": "a1633381720059d5", "bytes": 26.873e9}}
+
+
+def measured_traffic(workload):
+    import hashlib
+    ent = PMC_TRAFFIC.get(workload)
+    if not ent:
+        return None
+    src = os.path.join(ROOT, "paper_2310_14423_amd", "csrc", ent["source"])
+    try:
+        h = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
+    except OSError:
+        return None
+    return ent["bytes"] if h == ent["sha256_16"] else None
+
 
 def cpu_baseline(w, seconds_target=15.0):
     """The CPU oracle, as it stands, on a bounded sample of the same workload."""
@@ -114,7 +132,8 @@ def main():
         upd_ms = ms[1] / cnt[1]
         ach = upd_bytes / (upd_ms * 1e-3) / 1e9
         roofline = {"kernel": "update_%s_kernel" % w["opt"], "bound": "hbm", "achieved": ach,
-                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None,
+                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                    "traffic": measured_traffic(args.workload),
                     "avg_ms": upd_ms, "launches": cnt[1],
                     "bytes_per_launch": upd_bytes}
         kernels["update_ms_avg"] = upd_ms
