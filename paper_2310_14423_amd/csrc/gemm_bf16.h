@@ -1,0 +1,143 @@
+// gemm_bf16.h -- batched bf16 x bf16 -> fp32 GEMM on the gfx950 matrix cores, "NT" form:
+//
+//     C[z][m][n] = sum_k A[z][m][k] * B[z][n][k]        (both operands K-contiguous)
+//
+// which is the operand order the MFMA instruction wants: v_mfma_f32_32x32x16_bf16 takes, per
+// lane, 8 consecutive k of one row of A and 8 consecutive k of one column of B.  Lane layout
+// (checked on the hardware): lane l holds A[row l%32][k (l/32)*8 .. +7], B[k (l/32)*8 .. +7]
+// [col l%32], and accumulator element i is C[(i/4)*8 + (l/32)*4 + i%4][l%32].
+//
+// Tiling: a workgroup of WM x WN wavefronts computes a BM x BN tile; K is walked in BK slabs
+// staged through LDS (two buffers, register-prefetched: the global loads of slab j+1 are in
+// flight while slab j is multiplied).  LDS rows are padded by 16 B so that the 128-bit
+// fragment reads of 32 consecutive rows fall on different banks.  M and N may be ragged
+// (loads are zero-filled, the epilogue is bounds-checked); K must be a multiple of BK and
+// lda/ldb multiples of 8 elements (16-byte rows).
+//
+// The epilogue is a functor called as epi(z, m, n, acc) for every in-bounds element.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace qsr {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+struct GemmNT {
+    const bf16_t *A, *B;
+    int M, N, K;
+    long long lda, ldb;
+    long long sA, sB;      // per-batch strides (elements)
+};
+
+template <int BM, int BN, int BK, int WM, int WN, class Epi>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_nt_bf16_kernel(GemmNT p, Epi epi)
+{
+    constexpr int NT = WM * WN * 64;
+    constexpr int LDS_LD = BK + 8;                 // padded row, elements
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+    constexpr int KP = BK / 8;                     // 16-byte pieces per row
+    constexpr int A_PIECES = BM * KP / NT, B_PIECES = BN * KP / NT;
+    static_assert(BM * KP % NT == 0 && BN * KP % NT == 0, "tile / thread mismatch");
+
+    __shared__ __attribute__((aligned(16))) bf16_t As[2][BM * LDS_LD];
+    __shared__ __attribute__((aligned(16))) bf16_t Bs[2][BN * LDS_LD];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    const int z = blockIdx.z;
+    const bf16_t *A = p.A + (long long)z * p.sA;
+    const bf16_t *B = p.B + (long long)z * p.sB;
+
+    uint4 ra[A_PIECES], rb[B_PIECES];
+    auto load_global = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < A_PIECES; ++i) {
+            int pc = tid + i * NT, row = pc / KP, kc = pc % KP;
+            int gm = m0 + row;
+            ra[i] = gm < p.M ? *(const uint4 *)(A + (long long)gm * p.lda + k0 + kc * 8)
+                             : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < B_PIECES; ++i) {
+            int pc = tid + i * NT, row = pc / KP, kc = pc % KP;
+            int gn = n0 + row;
+            rb[i] = gn < p.N ? *(const uint4 *)(B + (long long)gn * p.ldb + k0 + kc * 8)
+                             : make_uint4(0, 0, 0, 0);
+        }
+    };
+    auto store_lds = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < A_PIECES; ++i) {
+            int pc = tid + i * NT, row = pc / KP, kc = pc % KP;
+            *(uint4 *)(&As[buf][row * LDS_LD + kc * 8]) = ra[i];
+        }
+#pragma unroll
+        for (int i = 0; i < B_PIECES; ++i) {
+            int pc = tid + i * NT, row = pc / KP, kc = pc % KP;
+            *(uint4 *)(&Bs[buf][row * LDS_LD + kc * 8]) = rb[i];
+        }
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    const int nk = p.K / BK;
+    load_global(0);
+    store_lds(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        if (kt + 1 < nk) load_global((kt + 1) * BK);
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            bf16x8 fa[TM], fb[TN];
+            const int koff = ks * 16 + (lane >> 5) * 8;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                fa[i] = *(const bf16x8 *)(&As[cur][(wm * TM * 32 + i * 32 + (lane & 31)) * LDS_LD + koff]);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                fb[j] = *(const bf16x8 *)(&Bs[cur][(wn * TN * 32 + j * 32 + (lane & 31)) * LDS_LD + koff]);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+        if (kt + 1 < nk) store_lds(cur ^ 1);
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = n0 + wn * TN * 32 + j * 32 + (lane & 31);
+            if (col >= p.N) continue;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int row = m0 + wm * TM * 32 + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+                if (row < p.M) epi(z, row, col, acc[i][j][e]);
+            }
+        }
+}
+
+template <int BM, int BN, int BK, int WM, int WN, class Epi>
+inline hipError_t launch_gemm_nt(const GemmNT &p, const Epi &epi, int batch, hipStream_t s)
+{
+    dim3 grid((unsigned)((p.N + BN - 1) / BN), (unsigned)((p.M + BM - 1) / BM), (unsigned)batch);
+    gemm_nt_bf16_kernel<BM, BN, BK, WM, WN, Epi><<<grid, WM * WN * 64, 0, s>>>(p, epi);
+    return hipGetLastError();
+}
+
+}  // namespace qsr

@@ -79,7 +79,7 @@ hipError_t launch_linreg_grad(const ModelDims &d, const float *theta, float *g, 
     float *X = (float *)ws;
     size_t xb = ((size_t)d.K * d.B * d.d_in * sizeof(float) + 255) & ~(size_t)255;
     float *r = (float *)((char *)ws + xb);
-    hipError_t e = launch_fill_normal(X, d.K, d.B * d.d_in, 1.0f, STREAM_X, d.seed, st, s);
+    hipError_t e = launch_fill_normal(X, d.B * d.d_in, d.K, d.B * d.d_in, 1.0f, STREAM_X, d.seed, st, s);
     if (e != hipSuccess) return e;
     linreg_residual_kernel<<<dim3((unsigned)d.B, (unsigned)d.K), 256, 0, s>>>(
         X, theta, wstar, r, d.B, d.d_in, d.data_sigma, d.seed, st);

@@ -123,7 +123,7 @@ hipError_t launch_mlp2_grad(const ModelDims &d, const float *theta, float *g, co
     mlp2_labels_kernel<<<dim3((unsigned)((B + 255) / 256), (unsigned)K), 256, 0, s>>>(
         w.label, B, (uint32_t)dz, d.seed, st);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    if ((e = launch_fill_normal(w.X, K, B * di, d.data_sigma, STREAM_X, d.seed, st, s)) != hipSuccess) return e;
+    if ((e = launch_fill_normal(w.X, B * di, K, B * di, d.data_sigma, STREAM_X, d.seed, st, s)) != hipSuccess) return e;
     {
         long long bx = (B * di + 255) / 256;
         if (bx > 4096) bx = 4096;

@@ -1,0 +1,499 @@
+// grad_resmlp.hip -- local gradient (Eq. (1) of arXiv 2310.14423) of the residual-MLP workload
+// for all K workers, batched over the workers in every launch.  The workload has the MLP
+// sub-block shapes of the paper's ViT-B (Sec. 4; width d, hidden width dh, L blocks):
+//
+//   x_0 = tokens [M][d] ~ N(0,1);  y = x_0 W_T / sqrt(d)
+//   u_l = LayerNorm(x_l; gamma_l, beta_l);  h_l = u_l W1_l + b1_l;  a_l = gelu_erf(h_l)
+//   x_l+1 = x_l + a_l W2_l + b2_l;  loss = 1/(2 M d) sum (x_L - y)^2
+//
+// The six GEMMs per block (2 forward, 2 data-gradient, 2 weight-gradient) run on the bf16
+// matrix cores with fp32 accumulation (gemm_bf16.h); the residual stream, LayerNorm statistics,
+// loss and all gradients stay fp32.  Every GEMM is brought to the K-contiguous "NT" form by
+// keeping bf16 copies of the weights in both orientations and transposed bf16 copies of the
+// activations that feed the weight gradients (their token axis padded with zeros to a multiple
+// of 64, so that it can serve as the reduction axis).
+// Per-block parameter packing: gamma[d], beta[d], W1[d][dh], b1[dh], W2[dh][d], b2[d].
+#include "gemm_bf16.h"
+#include "qsr_internal.h"
+
+namespace qsr {
+
+static inline size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
+static inline long long pad64(long long m) { return (m + 63) / 64 * 64; }
+
+constexpr float LN_EPS = 1e-5f;
+constexpr int LN_ROWS_PER_WAVE = 16;
+constexpr int CS_ROWS = 64;              // rows per partial column sum
+
+struct ResWs {
+    // per-replica strides are the element counts of one replica's array
+    float *X;      long long sX;       // [L+1][M][d]
+    float *MU, *RSTD; long long sStat; // [L][M]
+    bf16_t *UT;    long long sUT;      // [L][d][Mp]
+    bf16_t *H;     long long sH;       // [L][M][dh]
+    bf16_t *AT;    long long sAT;      // [L][dh][Mp]
+    bf16_t *U;     long long sU;       // [M][d]
+    bf16_t *A;     long long sA;       // [M][dh]
+    float *Y;      long long sY;       // [M][d]
+    float *DX;     long long sDX;      // [2][M][d]
+    bf16_t *DXb;   long long sDXb;     // [M][d]
+    bf16_t *DXT;   long long sDXT;     // [d][Mp]
+    bf16_t *DH;    long long sDH;      // [M][dh]
+    bf16_t *DHT;   long long sDHT;     // [dh][Mp]
+    float *DU;     long long sDU;      // [M][d]
+    bf16_t *W1b, *W1Tb, *W2b, *W2Tb; long long sW; // [L][d*dh] each
+    bf16_t *WTt;                       // [d][d], shared: teacher map transposed
+    float *PART;   long long sPART;    // column-sum partials
+    float *LPART;  long long sLPART;   // loss partials
+};
+
+static ResWs carve(const ModelDims &dm, void *ws, size_t *total)
+{
+    const long long K = dm.K, M = dm.B, d = dm.d_in, dh = dm.d_hidden, L = dm.n_blocks;
+    const long long Mp = pad64(M);
+    char *p = (char *)ws;
+    size_t off = 0;
+    ResWs w;
+    auto take = [&](long long per_replica, size_t elt, long long copies) {
+        void *r = p + off;
+        off += up256((size_t)per_replica * elt * (size_t)copies);
+        return r;
+    };
+    w.sX = (L + 1) * M * d;   w.X = (float *)take(w.sX, 4, K);
+    w.sStat = L * M;          w.MU = (float *)take(w.sStat, 4, K); w.RSTD = (float *)take(w.sStat, 4, K);
+    w.sUT = L * d * Mp;       w.UT = (bf16_t *)take(w.sUT, 2, K);
+    w.sH = L * M * dh;        w.H = (bf16_t *)take(w.sH, 2, K);
+    w.sAT = L * dh * Mp;      w.AT = (bf16_t *)take(w.sAT, 2, K);
+    w.sU = M * d;             w.U = (bf16_t *)take(w.sU, 2, K);
+    w.sA = M * dh;            w.A = (bf16_t *)take(w.sA, 2, K);
+    w.sY = M * d;             w.Y = (float *)take(w.sY, 4, K);
+    w.sDX = 2 * M * d;        w.DX = (float *)take(w.sDX, 4, K);
+    w.sDXb = M * d;           w.DXb = (bf16_t *)take(w.sDXb, 2, K);
+    w.sDXT = d * Mp;          w.DXT = (bf16_t *)take(w.sDXT, 2, K);
+    w.sDH = M * dh;           w.DH = (bf16_t *)take(w.sDH, 2, K);
+    w.sDHT = dh * Mp;         w.DHT = (bf16_t *)take(w.sDHT, 2, K);
+    w.sDU = M * d;            w.DU = (float *)take(w.sDU, 4, K);
+    w.sW = L * d * dh;
+    w.W1b = (bf16_t *)take(w.sW, 2, K);  w.W1Tb = (bf16_t *)take(w.sW, 2, K);
+    w.W2b = (bf16_t *)take(w.sW, 2, K);  w.W2Tb = (bf16_t *)take(w.sW, 2, K);
+    w.WTt = (bf16_t *)take(d * d, 2, 1);
+    const long long wave_rows = (M + LN_ROWS_PER_WAVE - 1) / LN_ROWS_PER_WAVE;
+    const long long cs_chunks = (M + CS_ROWS - 1) / CS_ROWS;
+    long long part = 2 * wave_rows * d;
+    if (cs_chunks * dh > part) part = cs_chunks * dh;
+    w.sPART = part;           w.PART = (float *)take(w.sPART, 4, K);
+    w.sLPART = (M * d + 1023) / 1024; w.LPART = (float *)take(w.sLPART, 4, K);
+    if (total) *total = off;
+    return w;
+}
+
+size_t resmlp_workspace_bytes(const ModelDims &d)
+{
+    size_t total = 0;
+    carve(d, nullptr, &total);
+    return total;
+}
+
+// ---------------------------------------------------------------------------------------------
+// layout / conversion kernels
+// ---------------------------------------------------------------------------------------------
+
+// in [R][C] (row stride ld_in) -> out [R][C] bf16 (optional) and outT [C][R] bf16 (row stride
+// ld_t), 64x64 tiles through LDS; batch index z with element strides.
+template <class TIn>
+__global__ __launch_bounds__(256) void cvt_transpose_kernel(const TIn *__restrict__ in, long long ld_in,
+                                                            long long s_in, bf16_t *__restrict__ out,
+                                                            long long s_out, bf16_t *__restrict__ outT,
+                                                            long long ld_t, long long s_t, int R, int C)
+{
+    __shared__ bf16_t tile[64][66];
+    const int z = blockIdx.z;
+    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    in += (long long)z * s_in;
+    for (int r = ty; r < 64; r += 4) {
+        bf16_t v = (bf16_t)0.0f;
+        if (r0 + r < R && c0 + tx < C) {
+            v = (bf16_t)in[(long long)(r0 + r) * ld_in + c0 + tx];
+            if (out) out[(long long)z * s_out + (long long)(r0 + r) * C + c0 + tx] = v;
+        }
+        tile[r][tx] = v;
+    }
+    __syncthreads();
+    if (outT) {
+        for (int c = ty; c < 64; c += 4)
+            if (c0 + c < C && r0 + tx < R)
+                outT[(long long)z * s_t + (long long)(c0 + c) * ld_t + r0 + tx] = tile[tx][c];
+    }
+}
+
+template <class TIn>
+static hipError_t launch_cvt_transpose(const TIn *in, long long ld_in, long long s_in, bf16_t *out,
+                                       long long s_out, bf16_t *outT, long long ld_t, long long s_t,
+                                       int R, int C, int batch, hipStream_t s)
+{
+    dim3 grid((unsigned)((C + 63) / 64), (unsigned)((R + 63) / 64), (unsigned)batch);
+    cvt_transpose_kernel<TIn><<<grid, 256, 0, s>>>(in, ld_in, s_in, out, s_out, outT, ld_t, s_t, R, C);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void f32_to_bf16_kernel(const float *__restrict__ in,
+                                                          bf16_t *__restrict__ out, long long n)
+{
+    const long long stride = (long long)gridDim.x * 256;
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) out[i] = (bf16_t)in[i];
+}
+
+// ---------------------------------------------------------------------------------------------
+// LayerNorm
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// one wavefront per token row: statistics in fp32, output u = gamma*xhat + beta in bf16
+__global__ __launch_bounds__(256) void ln_fwd_kernel(const float *__restrict__ X, long long sX,
+                                                     const float *__restrict__ theta, long long sTh,
+                                                     long long off_gamma, bf16_t *__restrict__ U,
+                                                     long long sU, float *__restrict__ MU,
+                                                     float *__restrict__ RSTD, long long sStat, int M, int d)
+{
+    const int z = blockIdx.y;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (row >= M) return;
+    const float *x = X + (long long)z * sX + (long long)row * d;
+    const float *gam = theta + (long long)z * sTh + off_gamma, *bet = gam + d;
+    float s = 0.f;
+    for (int j = lane; j < d; j += 64) s += x[j];
+    const float mean = wave_sum(s) / (float)d;
+    float q = 0.f;
+    for (int j = lane; j < d; j += 64) { float c = x[j] - mean; q = fmaf(c, c, q); }
+    const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + LN_EPS);
+    bf16_t *u = U + (long long)z * sU + (long long)row * d;
+    for (int j = lane; j < d; j += 64) u[j] = (bf16_t)fmaf(gam[j], (x[j] - mean) * rstd, bet[j]);
+    if (lane == 0) { MU[(long long)z * sStat + row] = mean; RSTD[(long long)z * sStat + row] = rstd; }
+}
+
+// Backward of LayerNorm plus the residual path, one wavefront per LN_ROWS_PER_WAVE token rows:
+//   dn = du*gamma; dx_out = dx_in + rstd*(dn - mean(dn) - xhat*mean(dn*xhat))
+// and per-wavefront partial sums of dgamma = sum_m du*xhat, dbeta = sum_m du (reduced by
+// colsum_final_kernel).  DPL = columns per lane.
+template <int DPL>
+__global__ __launch_bounds__(256) void ln_bwd_kernel(const float *__restrict__ DU, long long sDU,
+                                                     const float *__restrict__ X, long long sX,
+                                                     const float *__restrict__ MU,
+                                                     const float *__restrict__ RSTD, long long sStat,
+                                                     const float *__restrict__ theta, long long sTh,
+                                                     long long off_gamma, const float *__restrict__ DXin,
+                                                     float *__restrict__ DXout, long long sDX,
+                                                     bf16_t *__restrict__ DXb, long long sDXb,
+                                                     float *__restrict__ PART, long long sPART,
+                                                     int wave_rows, int M, int d)
+{
+    const int z = blockIdx.y;
+    const int wr = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (wr >= wave_rows) return;
+    const float *gam = theta + (long long)z * sTh + off_gamma;
+    float g[DPL], dg[DPL], db[DPL];
+#pragma unroll
+    for (int c = 0; c < DPL; ++c) {
+        int j = lane + c * 64;
+        g[c] = j < d ? gam[j] : 0.f;
+        dg[c] = 0.f; db[c] = 0.f;
+    }
+    const int r_end = min(M, (wr + 1) * LN_ROWS_PER_WAVE);
+    for (int row = wr * LN_ROWS_PER_WAVE; row < r_end; ++row) {
+        const long long o = (long long)row * d;
+        const float mean = MU[(long long)z * sStat + row], rstd = RSTD[(long long)z * sStat + row];
+        float xh[DPL], dn[DPL];
+        float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+        for (int c = 0; c < DPL; ++c) {
+            int j = lane + c * 64;
+            float du = 0.f; xh[c] = 0.f;
+            if (j < d) { du = DU[(long long)z * sDU + o + j]; xh[c] = (X[(long long)z * sX + o + j] - mean) * rstd; }
+            dn[c] = du * g[c];
+            s1 += dn[c]; s2 = fmaf(dn[c], xh[c], s2);
+            dg[c] = fmaf(du, xh[c], dg[c]); db[c] += du;
+        }
+        const float m1 = wave_sum(s1) / (float)d, m2 = wave_sum(s2) / (float)d;
+#pragma unroll
+        for (int c = 0; c < DPL; ++c) {
+            int j = lane + c * 64;
+            if (j < d) {
+                float v = DXin[(long long)z * sDX + o + j] + rstd * (dn[c] - m1 - xh[c] * m2);
+                DXout[(long long)z * sDX + o + j] = v;
+                DXb[(long long)z * sDXb + o + j] = (bf16_t)v;
+            }
+        }
+    }
+    float *pg = PART + (long long)z * sPART + (long long)wr * d;
+    float *pb = PART + (long long)z * sPART + ((long long)wave_rows + wr) * d;
+#pragma unroll
+    for (int c = 0; c < DPL; ++c) {
+        int j = lane + c * 64;
+        if (j < d) { pg[j] = dg[c]; pb[j] = db[c]; }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// column sums (bias gradients; final stage of the LayerNorm parameter gradients)
+// ---------------------------------------------------------------------------------------------
+template <class T>
+__global__ __launch_bounds__(256) void colsum_partial_kernel(const T *__restrict__ A, long long sA,
+                                                             float *__restrict__ PART, long long sPART,
+                                                             int rows, int cols)
+{
+    const int z = blockIdx.z;
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= cols) return;
+    const int r0 = blockIdx.y * CS_ROWS, r1 = min(rows, r0 + CS_ROWS);
+    const T *a = A + (long long)z * sA;
+    float acc = 0.f;
+    for (int r = r0; r < r1; ++r) acc += (float)a[(long long)r * cols + j];
+    PART[(long long)z * sPART + (long long)blockIdx.y * cols + j] = acc;
+}
+
+// out[z][j] = sum_c PART[z][c][j], chunks summed in ascending order (deterministic)
+__global__ __launch_bounds__(256) void colsum_final_kernel(const float *__restrict__ PART, long long sPART,
+                                                           long long part_off, float *__restrict__ out,
+                                                           long long sOut, int chunks, int cols)
+{
+    const int z = blockIdx.y;
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= cols) return;
+    const float *p = PART + (long long)z * sPART + part_off;
+    float acc = 0.f;
+    for (int c = 0; c < chunks; ++c) acc += p[(long long)c * cols + j];
+    out[(long long)z * sOut + j] = acc;
+}
+
+template <class T>
+static hipError_t colsum(const T *A, long long sA, float *PART, long long sPART, float *out, long long sOut,
+                         int rows, int cols, int batch, hipStream_t s)
+{
+    const int chunks = (rows + CS_ROWS - 1) / CS_ROWS;
+    colsum_partial_kernel<T><<<dim3((unsigned)((cols + 255) / 256), (unsigned)chunks, (unsigned)batch), 256, 0, s>>>(
+        A, sA, PART, sPART, rows, cols);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    colsum_final_kernel<<<dim3((unsigned)((cols + 255) / 256), (unsigned)batch), 256, 0, s>>>(
+        PART, sPART, 0, out, sOut, chunks, cols);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// loss
+// ---------------------------------------------------------------------------------------------
+// r = x_L - y; dx = r/(M d) (fp32 and bf16); per-block partial sums of r^2
+__global__ __launch_bounds__(256) void loss_kernel(const float *__restrict__ XL, long long sX,
+                                                   const float *__restrict__ Y, long long sY,
+                                                   float *__restrict__ DX, long long sDX,
+                                                   bf16_t *__restrict__ DXb, long long sDXb,
+                                                   float *__restrict__ LPART, long long sLPART,
+                                                   long long n, float inv)
+{
+    __shared__ float red[4];
+    const int z = blockIdx.y;
+    float acc = 0.f;
+    const long long base = (long long)blockIdx.x * 1024;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        long long i = base + u * 256 + threadIdx.x;
+        if (i < n) {
+            float r = XL[(long long)z * sX + i] - Y[(long long)z * sY + i];
+            acc = fmaf(r, r, acc);
+            float g = r * inv;
+            DX[(long long)z * sDX + i] = g;
+            DXb[(long long)z * sDXb + i] = (bf16_t)g;
+        }
+    }
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) LPART[(long long)z * sLPART + blockIdx.x] = red[0] + red[1] + red[2] + red[3];
+}
+
+__global__ __launch_bounds__(256) void loss_final_kernel(const float *__restrict__ LPART, long long sLPART,
+                                                         int nparts, float scale, float *__restrict__ loss)
+{
+    __shared__ float red[4];
+    const int z = blockIdx.x;
+    float acc = 0.f;
+    for (int i = threadIdx.x; i < nparts; i += 256) acc += LPART[(long long)z * sLPART + i];
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) loss[z] = (red[0] + red[1] + red[2] + red[3]) * scale;
+}
+
+// ---------------------------------------------------------------------------------------------
+// GEMM epilogues
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float gelu_cdf(float h) { return 0.5f * (1.0f + erff(h * 0.70710678118654752f)); }
+
+struct EpiScaleF32 {             // C = scale * acc
+    float *C; long long ldc, sC; float scale;
+    __device__ void operator()(int z, int m, int n, float v) const { C[(long long)z * sC + (long long)m * ldc + n] = v * scale; }
+};
+struct EpiBiasGelu {             // h = acc + b1; H = bf16(h); A = bf16(gelu(h))
+    const float *bias; long long sBias; bf16_t *H; long long sH; bf16_t *A; long long sA; long long ld;
+    __device__ void operator()(int z, int m, int n, float v) const
+    {
+        float h = v + bias[(long long)z * sBias + n];
+        H[(long long)z * sH + (long long)m * ld + n] = (bf16_t)h;
+        A[(long long)z * sA + (long long)m * ld + n] = (bf16_t)(h * gelu_cdf(h));
+    }
+};
+struct EpiBiasResidual {         // x_out = x_in + acc + b2
+    const float *bias; long long sBias; const float *Xin; float *Xout; long long sX; long long ld;
+    __device__ void operator()(int z, int m, int n, float v) const
+    {
+        long long o = (long long)z * sX + (long long)m * ld + n;
+        Xout[o] = Xin[o] + v + bias[(long long)z * sBias + n];
+    }
+};
+struct EpiGeluBwd {              // dh = acc * gelu'(h)
+    const bf16_t *H; long long sH; bf16_t *DH; long long sDH; long long ld;
+    __device__ void operator()(int z, int m, int n, float v) const
+    {
+        float h = (float)H[(long long)z * sH + (long long)m * ld + n];
+        float pdf = 0.3989422804014327f * expf(-0.5f * h * h);
+        DH[(long long)z * sDH + (long long)m * ld + n] = (bf16_t)(v * (gelu_cdf(h) + h * pdf));
+    }
+};
+
+// tile shape of every GEMM of this workload
+#define QSR_GEMM_SHAPE 128, 128, 32, 2, 2
+
+#define TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return e_; } while (0)
+
+hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g, const float *teacher,
+                              void *ws, float *loss, const DevState *st, hipStream_t s)
+{
+    const int K = dm.K, M = (int)dm.B, d = (int)dm.d_in, dh = (int)dm.d_hidden, L = dm.n_blocks;
+    const long long Mp = pad64(M), P = dm.P;
+    const long long per_block = 2LL * d + (long long)d * dh + dh + (long long)dh * d + d;
+    ResWs w = carve(dm, ws, nullptr);
+    const long long Md = (long long)M * d, Mdh = (long long)M * dh;
+
+    // bf16 copies of the weights in both orientations (the master weights changed last step)
+    for (int l = 0; l < L; ++l) {
+        const long long oW1 = l * per_block + 2LL * d, oW2 = oW1 + (long long)d * dh + dh;
+        const long long ow = (long long)l * d * dh;
+        TRY(launch_cvt_transpose<float>(theta + oW1, dh, P, w.W1b + ow, w.sW, w.W1Tb + ow, d, w.sW, d, dh, K, s));
+        TRY(launch_cvt_transpose<float>(theta + oW2, d, P, w.W2b + ow, w.sW, w.W2Tb + ow, dh, w.sW, dh, d, K, s));
+    }
+    TRY(launch_cvt_transpose<float>(teacher, d, 0, nullptr, 0, w.WTt, d, 0, d, d, 1, s));
+
+    // Sample(): tokens x_0 (fp32 in X[0], bf16 in U), teacher targets y = x_0 W_T / sqrt(d)
+    TRY(launch_fill_normal(w.X, w.sX, K, Md, 1.0f, STREAM_X, dm.seed, st, s));
+    for (int k = 0; k < K; ++k) {
+        long long blocks = (Md + 255) / 256; if (blocks > 65535) blocks = 65535;
+        f32_to_bf16_kernel<<<(unsigned)blocks, 256, 0, s>>>(w.X + k * w.sX, w.U + k * w.sU, Md);
+        TRY(hipGetLastError());
+    }
+    {
+        GemmNT p{w.U, w.WTt, M, d, d, d, d, w.sU, 0};
+        EpiScaleF32 epi{w.Y, d, w.sY, 1.0f / sqrtf((float)d)};
+        TRY((launch_gemm_nt<QSR_GEMM_SHAPE>(p, epi, K, s)));
+    }
+
+    // forward
+    for (int l = 0; l < L; ++l) {
+        const long long og = l * per_block, ob1 = og + 2LL * d + (long long)d * dh,
+                        ob2 = ob1 + dh + (long long)dh * d;
+        const long long ow = (long long)l * d * dh;
+        const float *Xl = w.X + (long long)l * Md;
+        float *Xn = w.X + (long long)(l + 1) * Md;
+        ln_fwd_kernel<<<dim3((unsigned)((M + 3) / 4), (unsigned)K), 256, 0, s>>>(
+            Xl, w.sX, theta, P, og, w.U, w.sU, w.MU + (long long)l * M, w.RSTD + (long long)l * M, w.sStat, M, d);
+        TRY(hipGetLastError());
+        TRY(launch_cvt_transpose<bf16_t>(w.U, d, w.sU, nullptr, 0, w.UT + (long long)l * d * Mp, Mp, w.sUT, M, d, K, s));
+        {
+            GemmNT p{w.U, w.W1Tb + ow, M, dh, d, d, d, w.sU, w.sW};
+            EpiBiasGelu epi{theta + ob1, P, w.H + (long long)l * Mdh, w.sH, w.A, w.sA, dh};
+            TRY((launch_gemm_nt<QSR_GEMM_SHAPE>(p, epi, K, s)));
+        }
+        TRY(launch_cvt_transpose<bf16_t>(w.A, dh, w.sA, nullptr, 0, w.AT + (long long)l * dh * Mp, Mp, w.sAT, M, dh, K, s));
+        {
+            GemmNT p{w.A, w.W2Tb + ow, M, d, dh, dh, dh, w.sA, w.sW};
+            EpiBiasResidual epi{theta + ob2, P, Xl, Xn, w.sX, d};
+            TRY((launch_gemm_nt<QSR_GEMM_SHAPE>(p, epi, K, s)));
+        }
+    }
+
+    // loss and d loss / d x_L
+    {
+        const int nparts = (int)((Md + 1023) / 1024);
+        const float inv = 1.0f / ((float)M * (float)d);
+        loss_kernel<<<dim3((unsigned)nparts, (unsigned)K), 256, 0, s>>>(
+            w.X + (long long)L * Md, w.sX, w.Y, w.sY, w.DX, w.sDX, w.DXb, w.sDXb, w.LPART, w.sLPART, Md, inv);
+        TRY(hipGetLastError());
+        loss_final_kernel<<<K, 256, 0, s>>>(w.LPART, w.sLPART, nparts, 0.5f * inv, loss);
+        TRY(hipGetLastError());
+    }
+
+    // backward
+    int cur = 0;                                  // DX[cur] holds d loss / d x_{l+1}
+    const int wave_rows = (M + LN_ROWS_PER_WAVE - 1) / LN_ROWS_PER_WAVE;
+    for (int l = L - 1; l >= 0; --l) {
+        const long long og = l * per_block, oW1 = og + 2LL * d, ob1 = oW1 + (long long)d * dh,
+                        oW2 = ob1 + dh, ob2 = oW2 + (long long)dh * d;
+        const long long ow = (long long)l * d * dh;
+        float *DXc = w.DX + (long long)cur * Md, *DXn = w.DX + (long long)(cur ^ 1) * Md;
+        // b2 and W2:  db2 = colsum(dx);  dW2 = a^T dx
+        TRY(colsum<float>(DXc, w.sDX, w.PART, w.sPART, g + ob2, P, M, d, K, s));
+        TRY(launch_cvt_transpose<bf16_t>(w.DXb, d, w.sDXb, nullptr, 0, w.DXT, Mp, w.sDXT, M, d, K, s));
+        {
+            GemmNT p{w.AT + (long long)l * dh * Mp, w.DXT, dh, d, (int)Mp, Mp, Mp, w.sAT, w.sDXT};
+            EpiScaleF32 epi{g + oW2, d, P, 1.0f};
+            TRY((launch_gemm_nt<QSR_GEMM_SHAPE>(p, epi, K, s)));
+        }
+        // dh = (dx W2^T) * gelu'(h)
+        {
+            GemmNT p{w.DXb, w.W2b + ow, M, dh, d, d, d, w.sDXb, w.sW};
+            EpiGeluBwd epi{w.H + (long long)l * Mdh, w.sH, w.DH, w.sDH, dh};
+            TRY((launch_gemm_nt<QSR_GEMM_SHAPE>(p, epi, K, s)));
+        }
+        // b1 and W1:  db1 = colsum(dh);  dW1 = u^T dh
+        TRY(colsum<bf16_t>(w.DH, w.sDH, w.PART, w.sPART, g + ob1, P, M, dh, K, s));
+        TRY(launch_cvt_transpose<bf16_t>(w.DH, dh, w.sDH, nullptr, 0, w.DHT, Mp, w.sDHT, M, dh, K, s));
+        {
+            GemmNT p{w.UT + (long long)l * d * Mp, w.DHT, d, dh, (int)Mp, Mp, Mp, w.sUT, w.sDHT};
+            EpiScaleF32 epi{g + oW1, dh, P, 1.0f};
+            TRY((launch_gemm_nt<QSR_GEMM_SHAPE>(p, epi, K, s)));
+        }
+        // du = dh W1^T, then LayerNorm backward + residual: dx_l
+        {
+            GemmNT p{w.DH, w.W1b + ow, M, d, dh, dh, dh, w.sDH, w.sW};
+            EpiScaleF32 epi{w.DU, d, w.sDU, 1.0f};
+            TRY((launch_gemm_nt<QSR_GEMM_SHAPE>(p, epi, K, s)));
+        }
+        {
+            dim3 grid((unsigned)((wave_rows + 3) / 4), (unsigned)K);
+            const float *Xl = w.X + (long long)l * Md;
+            const float *mu = w.MU + (long long)l * M, *rs = w.RSTD + (long long)l * M;
+#define LN_BWD(DPL) ln_bwd_kernel<DPL><<<grid, 256, 0, s>>>(w.DU, w.sDU, Xl, w.sX, mu, rs, w.sStat, theta, P, og, \
+                        DXc, DXn, w.sDX, w.DXb, w.sDXb, w.PART, w.sPART, wave_rows, M, d)
+            const int dpl = (d + 63) / 64;
+            if (dpl <= 2) LN_BWD(2); else if (dpl <= 4) LN_BWD(4); else if (dpl <= 8) LN_BWD(8);
+            else if (dpl <= 12) LN_BWD(12); else LN_BWD(16);
+#undef LN_BWD
+            TRY(hipGetLastError());
+            colsum_final_kernel<<<dim3((unsigned)((d + 255) / 256), (unsigned)K), 256, 0, s>>>(
+                w.PART, w.sPART, 0, g + og, P, wave_rows, d);
+            TRY(hipGetLastError());
+            colsum_final_kernel<<<dim3((unsigned)((d + 255) / 256), (unsigned)K), 256, 0, s>>>(
+                w.PART, w.sPART, (long long)wave_rows * d, g + og + d, P, wave_rows, d);
+            TRY(hipGetLastError());
+        }
+        cur ^= 1;
+    }
+    return hipSuccess;
+}
+
+}  // namespace qsr

@@ -8,15 +8,15 @@
 
 namespace qsr {
 
-__global__ __launch_bounds__(64) void fill_normal_kernel(float *__restrict__ out, long long n,
-                                                          long long groups, float sigma,
+__global__ __launch_bounds__(64) void fill_normal_kernel(float *__restrict__ out, long long row_stride,
+                                                          long long n, long long groups, float sigma,
                                                           uint32_t stream, uint64_t seed,
                                                           const DevState *__restrict__ st)
 {
     const uint32_t t = (uint32_t)st->t;
     const uint32_t k = blockIdx.y;
-    float *row = out + (long long)k * n;
-    const bool vec = (n & 3) == 0;
+    float *row = out + (long long)k * row_stride;
+    const bool vec = ((n | row_stride) & 3) == 0;
     const long long stride = (long long)gridDim.x * 64;
     for (long long q = (long long)blockIdx.x * 64 + threadIdx.x; q < groups; q += stride) {
         float4 z = normal4(seed, stream, k, t, (uint32_t)q);
@@ -33,21 +33,21 @@ __global__ __launch_bounds__(64) void fill_normal_kernel(float *__restrict__ out
     }
 }
 
-hipError_t launch_fill_normal(float *out, int K, long long n, float sigma, uint32_t stream,
-                              uint64_t seed, const DevState *st, hipStream_t s)
+hipError_t launch_fill_normal(float *out, long long row_stride, int K, long long n, float sigma,
+                              uint32_t stream, uint64_t seed, const DevState *st, hipStream_t s)
 {
     long long groups = (n + 3) / 4;
     long long bx = (groups + 63) / 64;            // one trip per one-wavefront workgroup
     if (bx > 0x7FFFFFFFll) bx = 0x7FFFFFFFll;
     dim3 grid((unsigned)bx, (unsigned)K);
-    fill_normal_kernel<<<grid, 64, 0, s>>>(out, n, groups, sigma, stream, seed, st);
+    fill_normal_kernel<<<grid, 64, 0, s>>>(out, row_stride, n, groups, sigma, stream, seed, st);
     return hipGetLastError();
 }
 
 hipError_t launch_noise_grad(float *g, int K, long long P, float sigma, uint64_t seed,
                              const DevState *st, hipStream_t s)
 {
-    return launch_fill_normal(g, K, P, sigma, STREAM_GRAD, seed, st, s);
+    return launch_fill_normal(g, P, K, P, sigma, STREAM_GRAD, seed, st, s);
 }
 
 }  // namespace qsr

@@ -125,6 +125,9 @@ extern "C" int qsr_validate(const qsr_config *c, const char **why)
             break;
         case QSR_MODEL_RESMLP:
             if (c->d_in < 1 || c->d_hidden < 1 || c->n_blocks < 1 || c->B_loc < 1) w = "d_in/d_hidden/n_blocks/B_loc";
+            else if (c->d_in % 64 != 0 || c->d_hidden % 64 != 0) w = "d_in/d_hidden not multiples of 64";
+            else if (c->d_in > 1024) w = "d_in (above 1024)";
+            else if (c->B_loc > (1 << 24) || c->d_hidden > (1 << 20)) w = "B_loc/d_hidden too large";
             else if (c->P != resmlp_params(c)) w = "P != residual-MLP parameter count";
             else if (c->B_loc * c->d_in > ((long long)1 << 34)) w = "B_loc*d_in";
             break;
@@ -154,7 +157,7 @@ extern "C" int qsr_workspace_bytes(const qsr_config *cfg, size_t *bytes)
     switch (cfg->model) {
     case QSR_MODEL_LINREG: *bytes = linreg_workspace_bytes(d); break;
     case QSR_MODEL_MLP2: *bytes = mlp2_workspace_bytes(d); break;
-    case QSR_MODEL_RESMLP: return QSR_EINVAL;   // not built yet
+    case QSR_MODEL_RESMLP: *bytes = resmlp_workspace_bytes(d); break;
     default: break;
     }
     return QSR_OK;
@@ -257,6 +260,8 @@ static int init_impl(qsr_ctx *c, const float *theta0)
     HIP_TRY(launch_fill_zero(c->state0, n, c->stream));
     if (c->state1) HIP_TRY(launch_fill_zero(c->state1, n, c->stream));
     HIP_TRY(launch_fill_zero(c->d_loss, cfg.K, c->stream));
+    if (cfg.model == QSR_MODEL_RESMLP)   // the zero padding of the transposed activations lives here
+        HIP_TRY(launch_fill_zero((float *)c->workspace, (long long)(c->workspace_bytes / 4), c->stream));
     HIP_TRY(launch_sched_init(c->d_state, c->sp, c->stream));
     HIP_TRY(hipStreamSynchronize(c->stream));
     return QSR_OK;
@@ -363,6 +368,10 @@ extern "C" int qsr_local_step(qsr_ctx *c)
         case QSR_MODEL_MLP2:
             HIP_TRY(launch_mlp2_grad(c->dims, c->params, c->grads, c->model_const, c->workspace,
                                      c->d_loss, c->d_state, c->stream));
+            break;
+        case QSR_MODEL_RESMLP:
+            HIP_TRY(launch_resmlp_grad(c->dims, c->params, c->grads, c->model_const, c->workspace,
+                                       c->d_loss, c->d_state, c->stream));
             break;
         default: return QSR_EINVAL;
         }

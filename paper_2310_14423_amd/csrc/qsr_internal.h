@@ -69,9 +69,9 @@ hipError_t launch_average_rows(float *buf, int K, long long P, const DevState *s
 hipError_t launch_broadcast_rows(float *dst, const float *src, int K, long long P, hipStream_t s);
 hipError_t launch_fill_zero(float *dst, long long n, hipStream_t s);
 
-// out[k][i] = sigma * z, z ~ N(0,1) keyed (seed; i/4, stream, k, st->t); out is [K][n]
-hipError_t launch_fill_normal(float *out, int K, long long n, float sigma, uint32_t stream,
-                              uint64_t seed, const DevState *st, hipStream_t s);
+// out[k*row_stride + i] = sigma * z for i < n, z ~ N(0,1) keyed (seed; i/4, stream, k, st->t)
+hipError_t launch_fill_normal(float *out, long long row_stride, int K, long long n, float sigma,
+                              uint32_t stream, uint64_t seed, const DevState *st, hipStream_t s);
 hipError_t launch_noise_grad(float *g, int K, long long P, float sigma, uint64_t seed,
                              const DevState *st, hipStream_t s);
 
@@ -90,5 +90,9 @@ hipError_t launch_linreg_grad(const ModelDims &d, const float *theta, float *g, 
 size_t mlp2_workspace_bytes(const ModelDims &d);
 hipError_t launch_mlp2_grad(const ModelDims &d, const float *theta, float *g, const float *means,
                             void *ws, float *loss, const DevState *st, hipStream_t s);
+
+size_t resmlp_workspace_bytes(const ModelDims &d);
+hipError_t launch_resmlp_grad(const ModelDims &d, const float *theta, float *g, const float *teacher,
+                              void *ws, float *loss, const DevState *st, hipStream_t s);
 
 }  // namespace qsr

@@ -30,7 +30,7 @@ def test_strerror():
     assert L.qsr_strerror(-99) == b"unknown error"
 
 
-@pytest.mark.parametrize("name", ["lsq", "mlp", "flat60m", "flat350m"])
+@pytest.mark.parametrize("name", ["lsq", "mlp", "flat60m", "resmlp", "flat350m"])
 def test_named_workloads_validate(name):
     cfg, keep = make_config(workloads.get(name))
     assert qsr.validate(cfg) == (0, "ok")

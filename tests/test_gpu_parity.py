@@ -234,6 +234,57 @@ def test_mlp2_full_size_first_steps():
     ctx.close()
 
 
+def _resmlp_groups(w):
+    d, dh, L = w["d_in"], w["d_hidden"], w["n_blocks"]
+    per = 2 * d + d * dh + dh + dh * d + d
+    out = []
+    for l in range(L):
+        o = l * per
+        for name, n in (("gamma", d), ("beta", d), ("W1", d * dh), ("b1", dh), ("W2", dh * d), ("b2", d)):
+            out.append(("%s[%d]" % (name, l), slice(o, o + n)))
+            o += n
+    return out
+
+
+RTOL_BF16 = 2e-2      # bf16 GEMM inputs, fp32 accumulation
+
+
+@pytest.mark.parametrize("dims", [dict(d_in=64, d_hidden=128, n_blocks=2, B_loc=100, K=2),
+                                  dict(d_in=128, d_hidden=320, n_blocks=3, B_loc=333, K=3)])
+def test_resmlp_gradient_single_step(dims):
+    w = workloads.get("resmlp", T=8, T_warm=2, **dims)
+    rng = np.random.default_rng(7)
+    th0 = workloads.theta0(w)
+    th0 = (th0 + 0.02 * rng.standard_normal(th0.size)).astype(np.float32)   # non-trivial biases / LN
+    ctx = gpu_ctx(w, theta0=th0)
+    orc = oracle_run(w, theta0=th0)
+    ctx.local_step()
+    g = ctx.grads.cpu().numpy()
+    loss = ctx.read_loss()
+    for k in range(dims["K"]):
+        want, wl = orc.grad(k, 0, th0.astype(np.float64))
+        assert loss[k] == pytest.approx(wl, rel=1e-2)
+        for name, sl in _resmlp_groups(w):
+            assert_params_close(g[k, sl], want[sl], rtol=RTOL_BF16, what="resmlp grad %s k=%d" % (name, k))
+    ctx.close()
+
+
+def test_resmlp_short_run():
+    """Local AdamW + QSR on the residual-MLP workload at reduced size: warm-up rule, two rounds."""
+    w = workloads.get("resmlp", d_in=64, d_hidden=128, n_blocks=2, B_loc=100, K=2, T=40, T_warm=4,
+                      eta_max=8e-4, alpha=0.0035)
+    ctx = gpu_ctx(w)
+    orc = oracle_run(w, n_threads=2)
+    ctx.step(40); orc.step(40)
+    st, Hs = ctx.read_sync_log()
+    assert list(st) == list(orc.sync_log) and list(Hs) == list(orc.H_log) and len(st) >= 2
+    p = ctx.params.cpu().numpy()
+    for name, sl in _resmlp_groups(w):
+        assert_params_close(p[:, sl], orc.theta[:, sl], rtol=RTOL_BF16, what="resmlp params %s" % name)
+    assert all(np.array_equal(p[k], p[0]) for k in range(2))
+    ctx.close()
+
+
 def test_protocol_errors():
     import paper_2310_14423_amd as qsr
     w = _ext_workload("sgdm", 2, 8, 2, mu=0.5, lam=0.0)
