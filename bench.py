@@ -75,7 +75,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="flat60m", choices=["flat60m", "flat350m", "lsq", "mlp"])
+    ap.add_argument("--workload", default="flat60m", choices=["flat60m", "flat350m", "lsq", "mlp", "resmlp"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="skip the per-kernel HIP events (the roofline object is then null)")

@@ -5,7 +5,7 @@
 // which is the operand order the MFMA instruction wants: v_mfma_f32_32x32x16_bf16 takes, per
 // lane, 8 consecutive k of one row of A and 8 consecutive k of one column of B.  Lane layout
 // (checked on the hardware): lane l holds A[row l%32][k (l/32)*8 .. +7], B[k (l/32)*8 .. +7]
-// [col l%32], and accumulator element i is C[(i/4)*8 + (l/32)*4 + i%4][l%32].
+// [col l%32], and accumulator element i is D[(i/4)*8 + (l/32)*4 + i%4][l%32].
 //
 // Tiling: a workgroup of WM x WN wavefronts computes a BM x BN tile; K is walked in BK slabs
 // staged through LDS (two buffers, register-prefetched: the global loads of slab j+1 are in
@@ -14,7 +14,11 @@
 // (loads are zero-filled, the epilogue is bounds-checked); K must be a multiple of BK and
 // lda/ldb multiples of 8 elements (16-byte rows).
 //
-// The epilogue is a functor called as epi(z, m, n, acc) for every in-bounds element.
+// The two operands are handed to the instruction in swapped roles (the B rows as its "A", the A
+// rows as its "B"), so that it produces the transposed tile: lane l then owns, for token row
+// m = l%32, four consecutive output columns n.  The epilogue functor is called as
+// epi(z, m, n, v[4]) for C[z][m][n..n+3] (N must be a multiple of 4), which lets it use 64-bit
+// bf16x4 and 128-bit fp32x4 accesses on row-major outputs.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -43,8 +47,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_bf16_kernel(GemmNT p, Ep
     constexpr int A_PIECES = BM * KP / NT, B_PIECES = BN * KP / NT;
     static_assert(BM * KP % NT == 0 && BN * KP % NT == 0, "tile / thread mismatch");
 
-    __shared__ __attribute__((aligned(16))) bf16_t As[2][BM * LDS_LD];
-    __shared__ __attribute__((aligned(16))) bf16_t Bs[2][BN * LDS_LD];
+    extern __shared__ __attribute__((aligned(16))) unsigned char gemm_smem[];
+    bf16_t(*As)[BM * LDS_LD] = (bf16_t(*)[BM * LDS_LD])gemm_smem;
+    bf16_t(*Bs)[BN * LDS_LD] = (bf16_t(*)[BN * LDS_LD])(gemm_smem + 2 * BM * LDS_LD * sizeof(bf16_t));
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
@@ -112,31 +117,42 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_bf16_kernel(GemmNT p, Ep
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
         }
         if (kt + 1 < nk) store_lds(cur ^ 1);
         __syncthreads();
     }
 
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i) {
+        const int row = m0 + wm * TM * 32 + i * 32 + (lane & 31);
+        if (row >= p.M) continue;
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int col = n0 + wn * TN * 32 + j * 32 + (lane & 31);
-            if (col >= p.N) continue;
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int row = m0 + wm * TM * 32 + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-                if (row < p.M) epi(z, row, col, acc[i][j][e]);
+            for (int eg = 0; eg < 4; ++eg) {
+                const int col = n0 + wn * TN * 32 + j * 32 + eg * 8 + (lane >> 5) * 4;
+                if (col < p.N) {
+                    const float v[4] = {acc[i][j][eg * 4 + 0], acc[i][j][eg * 4 + 1], acc[i][j][eg * 4 + 2],
+                                        acc[i][j][eg * 4 + 3]};
+                    epi(z, row, col, v);
+                }
             }
-        }
+    }
 }
 
 template <int BM, int BN, int BK, int WM, int WN, class Epi>
 inline hipError_t launch_gemm_nt(const GemmNT &p, const Epi &epi, int batch, hipStream_t s)
 {
     dim3 grid((unsigned)((p.N + BN - 1) / BN), (unsigned)((p.M + BM - 1) / BM), (unsigned)batch);
-    gemm_nt_bf16_kernel<BM, BN, BK, WM, WN, Epi><<<grid, WM * WN * 64, 0, s>>>(p, epi);
+    constexpr size_t smem = 2 * (size_t)(BM + BN) * (BK + 8) * sizeof(bf16_t);
+    static_assert(smem <= 160 * 1024, "tile does not fit the 160 KB LDS");
+    auto kern = gemm_nt_bf16_kernel<BM, BN, BK, WM, WN, Epi>;
+    if (smem > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+    }
+    kern<<<grid, WM * WN * 64, smem, s>>>(p, epi);
     return hipGetLastError();
 }
 

@@ -257,18 +257,27 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const T *__restrict
     PART[(long long)z * sPART + (long long)blockIdx.y * cols + j] = acc;
 }
 
-// out[z][j] = sum_c PART[z][c][j], chunks summed in ascending order (deterministic)
+// out[z][j] = sum_c PART[z][c][j].  A workgroup owns 64 columns; its 4 wavefronts each sum a
+// contiguous quarter of the chunks in ascending order and the four partial sums are added in
+// wavefront order (fixed order: deterministic).
 __global__ __launch_bounds__(256) void colsum_final_kernel(const float *__restrict__ PART, long long sPART,
                                                            long long part_off, float *__restrict__ out,
                                                            long long sOut, int chunks, int cols)
 {
+    __shared__ float red[4][64];
     const int z = blockIdx.y;
-    const int j = blockIdx.x * 256 + threadIdx.x;
-    if (j >= cols) return;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int j = blockIdx.x * 64 + lane;
     const float *p = PART + (long long)z * sPART + part_off;
+    const int per = (chunks + 3) / 4;
+    const int c0 = wave * per, c1 = min(chunks, c0 + per);
     float acc = 0.f;
-    for (int c = 0; c < chunks; ++c) acc += p[(long long)c * cols + j];
-    out[(long long)z * sOut + j] = acc;
+    if (j < cols)
+        for (int c = c0; c < c1; ++c) acc += p[(long long)c * cols + j];
+    red[wave][lane] = acc;
+    __syncthreads();
+    if (wave == 0 && j < cols)
+        out[(long long)z * sOut + j] = ((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane];
 }
 
 template <class T>
@@ -280,7 +289,7 @@ static hipError_t colsum(const T *A, long long sA, float *PART, long long sPART,
         A, sA, PART, sPART, rows, cols);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    colsum_final_kernel<<<dim3((unsigned)((cols + 255) / 256), (unsigned)batch), 256, 0, s>>>(
+    colsum_final_kernel<<<dim3((unsigned)((cols + 63) / 64), (unsigned)batch), 256, 0, s>>>(
         PART, sPART, 0, out, sOut, chunks, cols);
     return hipGetLastError();
 }
@@ -333,41 +342,87 @@ __global__ __launch_bounds__(256) void loss_final_kernel(const float *__restrict
 // ---------------------------------------------------------------------------------------------
 // GEMM epilogues
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ float gelu_cdf(float h) { return 0.5f * (1.0f + erff(h * 0.70710678118654752f)); }
+// Phi(h) and phi(h) of the standard normal, for GELU(h) = h Phi(h) and its derivative
+// Phi(h) + h phi(h).  erf by the rational-times-Gaussian formula 7.1.26 of Abramowitz & Stegun
+// (|error| <= 1.5e-7, far below the bf16 rounding of the outputs); its exp(-x^2) with
+// x = |h|/sqrt(2) is exactly the Gaussian factor phi needs, so one exponential serves both.
+__device__ __forceinline__ void gelu_parts(float h, float &cdf, float &pdf)
+{
+    const float x = fabsf(h) * 0.70710678118654752f;
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
+    const float ex = __expf(-x * x);
+    float poly = fmaf(1.061405429f, t, -1.453152027f);
+    poly = fmaf(poly, t, 1.421413741f);
+    poly = fmaf(poly, t, -0.284496736f);
+    poly = fmaf(poly, t, 0.254829592f);
+    const float half_tail = 0.5f * poly * t * ex;       // (1 - erf(x)) / 2
+    cdf = h >= 0.f ? 1.0f - half_tail : half_tail;
+    pdf = 0.3989422804014327f * ex;
+}
+
+__device__ __forceinline__ bf16x4 pack4(float a, float b, float c, float d)
+{
+    bf16x4 r = {(bf16_t)a, (bf16_t)b, (bf16_t)c, (bf16_t)d};
+    return r;
+}
 
 struct EpiScaleF32 {             // C = scale * acc
     float *C; long long ldc, sC; float scale;
-    __device__ void operator()(int z, int m, int n, float v) const { C[(long long)z * sC + (long long)m * ldc + n] = v * scale; }
+    __device__ void operator()(int z, int m, int n, const float (&v)[4]) const
+    {
+        *(float4 *)(C + (long long)z * sC + (long long)m * ldc + n) =
+            make_float4(v[0] * scale, v[1] * scale, v[2] * scale, v[3] * scale);
+    }
 };
 struct EpiBiasGelu {             // h = acc + b1; H = bf16(h); A = bf16(gelu(h))
     const float *bias; long long sBias; bf16_t *H; long long sH; bf16_t *A; long long sA; long long ld;
-    __device__ void operator()(int z, int m, int n, float v) const
+    __device__ void operator()(int z, int m, int n, const float (&v)[4]) const
     {
-        float h = v + bias[(long long)z * sBias + n];
-        H[(long long)z * sH + (long long)m * ld + n] = (bf16_t)h;
-        A[(long long)z * sA + (long long)m * ld + n] = (bf16_t)(h * gelu_cdf(h));
+        const float4 b = *(const float4 *)(bias + (long long)z * sBias + n);
+        const float h[4] = {v[0] + b.x, v[1] + b.y, v[2] + b.z, v[3] + b.w};
+        float a[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { float c, pdf; gelu_parts(h[i], c, pdf); a[i] = h[i] * c; }
+        const long long o = (long long)m * ld + n;
+        *(bf16x4 *)(H + (long long)z * sH + o) = pack4(h[0], h[1], h[2], h[3]);
+        *(bf16x4 *)(A + (long long)z * sA + o) = pack4(a[0], a[1], a[2], a[3]);
     }
 };
 struct EpiBiasResidual {         // x_out = x_in + acc + b2
     const float *bias; long long sBias; const float *Xin; float *Xout; long long sX; long long ld;
-    __device__ void operator()(int z, int m, int n, float v) const
+    __device__ void operator()(int z, int m, int n, const float (&v)[4]) const
     {
-        long long o = (long long)z * sX + (long long)m * ld + n;
-        Xout[o] = Xin[o] + v + bias[(long long)z * sBias + n];
+        const long long o = (long long)z * sX + (long long)m * ld + n;
+        const float4 b = *(const float4 *)(bias + (long long)z * sBias + n);
+        const float4 x = *(const float4 *)(Xin + o);
+        *(float4 *)(Xout + o) = make_float4(x.x + v[0] + b.x, x.y + v[1] + b.y, x.z + v[2] + b.z, x.w + v[3] + b.w);
     }
 };
 struct EpiGeluBwd {              // dh = acc * gelu'(h)
     const bf16_t *H; long long sH; bf16_t *DH; long long sDH; long long ld;
-    __device__ void operator()(int z, int m, int n, float v) const
+    __device__ void operator()(int z, int m, int n, const float (&v)[4]) const
     {
-        float h = (float)H[(long long)z * sH + (long long)m * ld + n];
-        float pdf = 0.3989422804014327f * expf(-0.5f * h * h);
-        DH[(long long)z * sDH + (long long)m * ld + n] = (bf16_t)(v * (gelu_cdf(h) + h * pdf));
+        const long long o = (long long)m * ld + n;
+        const bf16x4 hb = *(const bf16x4 *)(H + (long long)z * sH + o);
+        float r[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float h = (float)hb[i];
+            float c, pdf;
+            gelu_parts(h, c, pdf);
+            r[i] = v[i] * fmaf(h, pdf, c);
+        }
+        *(bf16x4 *)(DH + (long long)z * sDH + o) = pack4(r[0], r[1], r[2], r[3]);
     }
 };
 
-// tile shape of every GEMM of this workload
-#define QSR_GEMM_SHAPE 128, 128, 32, 2, 2
+// Tile shapes (BM, BN, BK, wavefronts in M, wavefronts in N), from timing the three GEMM shapes of
+// the benchmark size (tokens x width x hidden = 12608 x 768 x 3072, batch 8) on MI355X:
+// 256x256x64 tiles with 8 wavefronts were fastest where the token axis is M (fwd, dgrad: 4800 or
+// 1200 workgroups); the weight-gradient GEMMs have only 3072 x 768 outputs per worker, where
+// 256x256 tiles would leave 288 workgroups for 256 CUs, so they use 128x128x64 (1152 workgroups).
+#define QSR_GEMM_BIG 256, 256, 64, 2, 4
+#define QSR_GEMM_WGRAD 128, 128, 64, 2, 2
 
 #define TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return e_; } while (0)
 
@@ -399,7 +454,7 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
     {
         GemmNT p{w.U, w.WTt, M, d, d, d, d, w.sU, 0};
         EpiScaleF32 epi{w.Y, d, w.sY, 1.0f / sqrtf((float)d)};
-        TRY((launch_gemm_nt<QSR_GEMM_SHAPE>(p, epi, K, s)));
+        TRY((launch_gemm_nt<QSR_GEMM_BIG>(p, epi, K, s)));
     }
 
     // forward
@@ -416,13 +471,13 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
         {
             GemmNT p{w.U, w.W1Tb + ow, M, dh, d, d, d, w.sU, w.sW};
             EpiBiasGelu epi{theta + ob1, P, w.H + (long long)l * Mdh, w.sH, w.A, w.sA, dh};
-            TRY((launch_gemm_nt<QSR_GEMM_SHAPE>(p, epi, K, s)));
+            TRY((launch_gemm_nt<QSR_GEMM_BIG>(p, epi, K, s)));
         }
         TRY(launch_cvt_transpose<bf16_t>(w.A, dh, w.sA, nullptr, 0, w.AT + (long long)l * dh * Mp, Mp, w.sAT, M, dh, K, s));
         {
             GemmNT p{w.A, w.W2Tb + ow, M, d, dh, dh, dh, w.sA, w.sW};
             EpiBiasResidual epi{theta + ob2, P, Xl, Xn, w.sX, d};
-            TRY((launch_gemm_nt<QSR_GEMM_SHAPE>(p, epi, K, s)));
+            TRY((launch_gemm_nt<QSR_GEMM_BIG>(p, epi, K, s)));
         }
     }
 
@@ -451,13 +506,13 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
         {
             GemmNT p{w.AT + (long long)l * dh * Mp, w.DXT, dh, d, (int)Mp, Mp, Mp, w.sAT, w.sDXT};
             EpiScaleF32 epi{g + oW2, d, P, 1.0f};
-            TRY((launch_gemm_nt<QSR_GEMM_SHAPE>(p, epi, K, s)));
+            TRY((launch_gemm_nt<QSR_GEMM_WGRAD>(p, epi, K, s)));
         }
         // dh = (dx W2^T) * gelu'(h)
         {
             GemmNT p{w.DXb, w.W2b + ow, M, dh, d, d, d, w.sDXb, w.sW};
             EpiGeluBwd epi{w.H + (long long)l * Mdh, w.sH, w.DH, w.sDH, dh};
-            TRY((launch_gemm_nt<QSR_GEMM_SHAPE>(p, epi, K, s)));
+            TRY((launch_gemm_nt<QSR_GEMM_BIG>(p, epi, K, s)));
         }
         // b1 and W1:  db1 = colsum(dh);  dW1 = u^T dh
         TRY(colsum<bf16_t>(w.DH, w.sDH, w.PART, w.sPART, g + ob1, P, M, dh, K, s));
@@ -465,13 +520,13 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
         {
             GemmNT p{w.UT + (long long)l * d * Mp, w.DHT, d, dh, (int)Mp, Mp, Mp, w.sUT, w.sDHT};
             EpiScaleF32 epi{g + oW1, dh, P, 1.0f};
-            TRY((launch_gemm_nt<QSR_GEMM_SHAPE>(p, epi, K, s)));
+            TRY((launch_gemm_nt<QSR_GEMM_WGRAD>(p, epi, K, s)));
         }
         // du = dh W1^T, then LayerNorm backward + residual: dx_l
         {
             GemmNT p{w.DH, w.W1b + ow, M, d, dh, dh, dh, w.sDH, w.sW};
             EpiScaleF32 epi{w.DU, d, w.sDU, 1.0f};
-            TRY((launch_gemm_nt<QSR_GEMM_SHAPE>(p, epi, K, s)));
+            TRY((launch_gemm_nt<QSR_GEMM_BIG>(p, epi, K, s)));
         }
         {
             dim3 grid((unsigned)((wave_rows + 3) / 4), (unsigned)K);
@@ -484,10 +539,10 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
             else if (dpl <= 12) LN_BWD(12); else LN_BWD(16);
 #undef LN_BWD
             TRY(hipGetLastError());
-            colsum_final_kernel<<<dim3((unsigned)((d + 255) / 256), (unsigned)K), 256, 0, s>>>(
+            colsum_final_kernel<<<dim3((unsigned)((d + 63) / 64), (unsigned)K), 256, 0, s>>>(
                 w.PART, w.sPART, 0, g + og, P, wave_rows, d);
             TRY(hipGetLastError());
-            colsum_final_kernel<<<dim3((unsigned)((d + 255) / 256), (unsigned)K), 256, 0, s>>>(
+            colsum_final_kernel<<<dim3((unsigned)((d + 63) / 64), (unsigned)K), 256, 0, s>>>(
                 w.PART, w.sPART, (long long)wave_rows * d, g + og + d, P, wave_rows, d);
             TRY(hipGetLastError());
         }
