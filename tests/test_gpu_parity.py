@@ -128,6 +128,57 @@ def test_flat_adamw_full_schedule_sampled_elements():
     ctx.close()
 
 
+def test_flat60m_full_size_sampled():
+    """The benchmark's own shape (K = 16, P = 60e6, same launch configuration): the first 310
+    iterations, which include the first averaging at t = 306, on 4096 sampled parameters plus
+    the two ends of the vector."""
+    w = workloads.get("flat60m")
+    rng = np.random.default_rng(1)
+    idx = np.sort(rng.choice(w["P"], 4096, replace=False)).astype(np.int64)
+    idx[0], idx[-1] = 0, w["P"] - 1
+    ctx = gpu_ctx(w)
+    orc = oracle_run(w, p_idx=idx)
+    done = 0
+    for upto in (2, 305, 306, 310):
+        ctx.step(upto - done); orc.step(upto - done); done = upto
+        p = ctx.params[:, torch_idx(idx)].cpu().numpy()
+        assert_params_close(p, orc.theta, what="flat60m t=%d" % upto)
+        assert all(np.array_equal(p[k], p[0]) for k in range(16)) == (upto == 306)
+    assert ctx.get_H() == (311, 1, 310)
+    m = ctx.state0[:, torch_idx(idx)].cpu().numpy()
+    v = ctx.state1[:, torch_idx(idx)].cpu().numpy()
+    assert_params_close(m, orc.st0, what="m"); assert_params_close(v, orc.st1, what="v")
+    ctx.close()
+
+
+def test_flat350m_full_size_sampled():
+    """The largest workload (K = 32, P = 350e6, 179 GB of state): three iterations and one
+    stand-alone averaging of the full buffer, on sampled parameters."""
+    import torch
+    import paper_2310_14423_amd as qsr
+    w = workloads.get("flat350m")
+    free, total = torch.cuda.mem_get_info()
+    if free < 200e9:
+        pytest.skip("needs 200 GB of free HBM, have %.0f GB" % (free / 1e9))
+    rng = np.random.default_rng(2)
+    idx = np.sort(rng.choice(w["P"], 2048, replace=False)).astype(np.int64)
+    idx[0], idx[-1] = 0, w["P"] - 1
+    ctx = gpu_ctx(w, theta0=np.zeros(w["P"], np.float32))
+    orc = oracle_run(w, p_idx=idx, theta0=np.zeros(w["P"], np.float32))
+    ctx.step(3); orc.step(3)
+    p = ctx.params[:, torch_idx(idx)].cpu().numpy()
+    assert_params_close(p, orc.theta, what="flat350m t=3")
+    qsr.average_rows(ctx.params)
+    oracle.average(orc.theta)
+    p = ctx.params[:, torch_idx(idx)].cpu().numpy()
+    assert_params_close(p, orc.theta, what="flat350m averaged")
+    assert all(np.array_equal(p[k], p[0]) for k in range(32))
+    assert ctx.get_H() == (277, 0, 3)
+    ctx.close()
+    del ctx
+    torch.cuda.empty_cache()
+
+
 def torch_idx(idx):
     import torch
     return torch.from_numpy(idx).cuda()
@@ -266,6 +317,22 @@ def test_resmlp_gradient_single_step(dims):
         assert loss[k] == pytest.approx(wl, rel=1e-2)
         for name, sl in _resmlp_groups(w):
             assert_params_close(g[k, sl], want[sl], rtol=RTOL_BF16, what="resmlp grad %s k=%d" % (name, k))
+    ctx.close()
+
+
+def test_resmlp_mid_size_gradient():
+    """Several 256-row tiles with a ragged token tail and both GEMM tile shapes exercised."""
+    dims = dict(d_in=256, d_hidden=1024, n_blocks=2, B_loc=600, K=2)
+    w = workloads.get("resmlp", T=4, T_warm=1, **dims)
+    ctx = gpu_ctx(w)
+    orc = oracle_run(w, n_threads=2)
+    th0 = workloads.theta0(w).astype(np.float64)
+    ctx.local_step()
+    g = ctx.grads.cpu().numpy()
+    want, wl = orc.grad(1, 0, th0)
+    assert ctx.read_loss()[1] == pytest.approx(wl, rel=1e-2)
+    for name, sl in _resmlp_groups(w):
+        assert_params_close(g[1, sl], want[sl], rtol=RTOL_BF16, what="resmlp mid grad %s" % name)
     ctx.close()
 
 
