@@ -61,10 +61,19 @@ typedef struct {
     int32_t H_base;       /* minimum synchronization period, >= 1 (Eq. (2))                */
     int32_t n_milestones; /* QSR_LR_STEP: entries of `milestones`                          */
     int32_t n_blocks;     /* QSR_MODEL_RESMLP                                              */
+    int32_t power;        /* exponent gamma of H = max{H_base, floor((alpha/eta_t)^gamma)}:
+                             2 = QSR (Eq. (2)); 1 = the H ~ 1/eta rule and 3 = the cubic rule the
+                             paper compares with (Sec. 2, App. F; alpha then plays beta / rho);
+                             0 = constant H = H_base (conventional Local OPT)               */
+    int32_t parallel;     /* 1 = Parallel OPT (Alg. 1): the K local gradients are averaged every
+                             step before OPT, so all workers take the same update; every step
+                             counts as a round.  Needs H_base = 1, power = 0.  0 = Local OPT  */
     int32_t reserved;     /* must be 0                                                     */
     int64_t P;            /* parameters per worker, >= 1                                   */
     int64_t T;            /* total iterations, eta_t is defined for t in 0..T-1, >= 1      */
     int64_t T_warm;       /* linear warm-up 0 -> eta_max over the first T_warm iterations  */
+    int64_t t_local_start;/* post-local schedule (Sec. 1): rounds that start before this
+                             iteration use H = 1; 0 = off                                  */
     int64_t B_loc;        /* local batch: samples (RESMLP: tokens) per worker per step     */
     int64_t d_in, d_hidden, d_out;
     double momentum;      /* SGD heavy-ball coefficient                                    */

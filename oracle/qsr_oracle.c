@@ -112,6 +112,19 @@ int64_t qsro_get_H(const double *eta, int64_t T, int64_t T_warm, int64_t t,
     return qsro_get_H_power(eta, T, T_warm, t, H_base, alpha, 2);
 }
 
+/* The rule of a configured run: power rule (gamma = 0: constant H_base), preceded by the
+ * post-local phase of Lin et al. (Sec. 1, Sec. 4 "Comparison with other synchronization
+ * strategies"): H = 1 for rounds that start before t_local_start. */
+static int64_t run_get_H(const qsro_config *c, const double *eta, int64_t t)
+{
+    if (t < c->t_local_start) return 1;
+    if (c->power == 0) {
+        int64_t rem = c->T - t;
+        return c->H_base < rem ? c->H_base : rem;
+    }
+    return qsro_get_H_power(eta, c->T, c->T_warm, t, c->H_base, c->alpha, c->power);
+}
+
 /* Whole-run schedule: writes H^(s) and the iteration count after which each
  * averaging runs; returns the number of rounds (also when it exceeds cap). */
 int64_t qsro_schedule(const double *eta, int64_t T, int64_t T_warm, int64_t H_base,
@@ -399,13 +412,13 @@ int qsro_run(const qsro_config *c, const double *eta, qsro_state *st, double *th
 {
     int32_t K = c->K;
     int64_t n = c->n;
-    double *gbuf = NULL;
+    double *gbuf = NULL, *gavg = NULL;
     if (c->model != 0) gbuf = (double *)malloc(sizeof(double) * (size_t)K * (size_t)n);
     int rc = 0;
     for (int64_t it = 0; it < n_steps; ++it) {
         if (st->t >= c->T || c->model < 0 || c->model > 4) { rc = -1; break; }
         if (st->H == 0) {                          /* a round starts at st->t */
-            st->H = qsro_get_H(eta, c->T, c->T_warm, st->t, c->H_base, c->alpha);
+            st->H = run_get_H(c, eta, st->t);
             if (H_log && st->s < log_cap) H_log[st->s] = st->H;
         }
         int64_t t = st->t;
@@ -414,19 +427,29 @@ int qsro_run(const qsro_config *c, const double *eta, qsro_state *st, double *th
 #endif
         for (int32_t k = 0; k < K; ++k) {          /* "for each worker in parallel" */
             double *th = theta + (int64_t)k * n;
-            const double *g;
             double loss = 0.0;
-            if (c->model == 0) {
-                g = ext_g + ((int64_t)it * K + k) * n;
-            } else {
+            if (c->model != 0) {
                 double *gk = gbuf + (int64_t)k * n;
                 if (c->model == 1) qsro_grad_noise(c, k, t, gk);
                 else if (c->model == 2) loss = qsro_grad_linreg(c, k, t, th, gk);
                 else if (c->model == 3) loss = qsro_grad_mlp2(c, k, t, th, gk);
                 else loss = qsro_grad_resmlp(c, k, t, th, gk);
-                g = gk;
             }
             if (loss_out) loss_out[it * K + k] = loss;
+        }
+        const double *gall = c->model == 0 ? ext_g + (int64_t)it * K * n : gbuf;
+        if (c->parallel) {                         /* Alg. 1: All-Reduce of the local gradients */
+            if (!gavg) gavg = (double *)malloc(sizeof(double) * (size_t)K * (size_t)n);
+            memcpy(gavg, gall, sizeof(double) * (size_t)K * (size_t)n);
+            qsro_average(gavg, K, n);
+            gall = gavg;
+        }
+#ifdef _OPENMP
+#pragma omp parallel for num_threads(c->n_threads > 0 ? c->n_threads : 1) schedule(static)
+#endif
+        for (int32_t k = 0; k < K; ++k) {
+            double *th = theta + (int64_t)k * n;
+            const double *g = gall + (int64_t)k * n;
             if (c->opt == 0)
                 qsro_sgdm_step(th, st0 + (int64_t)k * n, g, n, eta[t], c->mu, c->lambda);
             else
@@ -444,5 +467,6 @@ int qsro_run(const qsro_config *c, const double *eta, qsro_state *st, double *th
         }
     }
     free(gbuf);
+    free(gavg);
     return rc;
 }

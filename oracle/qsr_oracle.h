@@ -12,8 +12,14 @@ typedef struct {
     int32_t H_base;
     int32_t n_threads;    /* OpenMP threads over the worker loop (>=1)        */
     int32_t n_blocks;     /* model 4                                          */
+    int32_t power;        /* exponent of the rule, 2 = QSR (Eq. 2); 1, 3: the
+                             variants of Sec. 2 / App. F; 0 = constant H_base    */
+    int32_t parallel;     /* 1 = Parallel OPT (Alg. 1): gradients are averaged
+                             every step and all workers take the same update  */
     int64_t n;            /* tracked parameters per worker (= P, or a sample) */
     int64_t T, T_warm;
+    int64_t t_local_start;/* post-local schedule: rounds that start before this
+                             iteration have H = 1; 0 = off                     */
     int64_t B_loc;        /* samples (model 4: tokens) per worker per step    */
     int64_t d_in, d_hidden, d_out;
     double mu, beta1, beta2, eps, lambda;

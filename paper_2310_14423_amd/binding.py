@@ -32,8 +32,9 @@ class Config(C.Structure):
     _fields_ = [
         ("K", C.c_int32), ("opt", C.c_int32), ("model", C.c_int32), ("lr_kind", C.c_int32),
         ("H_base", C.c_int32), ("n_milestones", C.c_int32), ("n_blocks", C.c_int32),
-        ("reserved", C.c_int32),
-        ("P", C.c_int64), ("T", C.c_int64), ("T_warm", C.c_int64), ("B_loc", C.c_int64),
+        ("power", C.c_int32), ("parallel", C.c_int32), ("reserved", C.c_int32),
+        ("P", C.c_int64), ("T", C.c_int64), ("T_warm", C.c_int64), ("t_local_start", C.c_int64),
+        ("B_loc", C.c_int64),
         ("d_in", C.c_int64), ("d_hidden", C.c_int64), ("d_out", C.c_int64),
         ("momentum", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double),
         ("weight_decay", C.c_double), ("eta_max", C.c_double), ("eta_min", C.c_double),
@@ -73,6 +74,8 @@ def make_config(w, stream=0, eta_table=None):
     c = Config()
     c.K = w["K"]; c.opt = OPTS[w["opt"]]; c.model = MODELS[w["model"]]
     c.H_base = w["H_base"]; c.alpha = w["alpha"]
+    c.power = w.get("power", 2); c.parallel = int(w.get("parallel", False))
+    c.t_local_start = w.get("t_local_start", 0)
     c.P = w["P"]; c.T = w["T"]; c.T_warm = w.get("T_warm", 0)
     c.B_loc = w.get("B_loc", 0); c.d_in = w.get("d_in", 0); c.d_hidden = w.get("d_hidden", 0)
     c.d_out = w.get("d_out", 0); c.n_blocks = w.get("n_blocks", 0)

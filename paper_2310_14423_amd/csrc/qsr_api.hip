@@ -83,6 +83,11 @@ extern "C" int qsr_validate(const qsr_config *c, const char **why)
     else if (c->lr_kind < QSR_LR_COSINE || c->lr_kind > QSR_LR_TABLE) w = "lr_kind";
     else if (c->H_base < 1) w = "H_base";
     else if (c->reserved != 0) w = "reserved";
+    else if (c->power < 0 || c->power > 8) w = "power";
+    else if (c->parallel != 0 && c->parallel != 1) w = "parallel";
+    else if (c->parallel == 1 && (c->H_base != 1 || c->power != 0 || c->t_local_start != 0))
+        w = "parallel needs H_base = 1, power = 0";
+    else if (c->t_local_start < 0 || c->t_local_start > c->T) w = "t_local_start";
     else if (!finite_ge0(c->alpha)) w = "alpha";
     else if (!finite_ge0(c->weight_decay)) w = "weight_decay";
     else if (c->opt == QSR_OPT_SGDM && !(finite_ge0(c->momentum) && c->momentum < 1.0)) w = "momentum";
@@ -253,6 +258,7 @@ static int init_impl(qsr_ctx *c, const float *theta0)
     HIP_TRY(hipStreamSynchronize(c->stream));
 
     c->sp.T = cfg.T; c->sp.T_warm = cfg.T_warm; c->sp.H_base = cfg.H_base; c->sp.alpha = cfg.alpha;
+    c->sp.power = cfg.power; c->sp.t_local_start = cfg.t_local_start;
     c->sp.eta = c->d_eta; c->sp.log_t = c->d_log_t; c->sp.log_H = c->d_log_H;
 
     const long long n = (long long)cfg.K * cfg.P;
@@ -378,6 +384,13 @@ extern "C" int qsr_local_step(qsr_ctx *c)
         int rc = br.close(c->t_host);
         if (rc != QSR_OK) return rc;
     }
+    if (cfg.parallel) {                                 // Alg. 1: All-Reduce of the local gradients
+        Bracket br(c, 2);
+        if (br.rc != QSR_OK) return br.rc;
+        HIP_TRY(launch_average_rows(c->grads, cfg.K, cfg.P, nullptr, c->stream));
+        int rc = br.close(c->t_host + 1);
+        if (rc != QSR_OK) return rc;
+    }
     {                                                   // OPT for all K workers at once
         Bracket br(c, 1);
         if (br.rc != QSR_OK) return br.rc;
@@ -401,7 +414,7 @@ extern "C" int qsr_maybe_sync(qsr_ctx *c)
 {
     if (!c) return QSR_EINVAL;
     if (!c->need_sync_call) return QSR_ESTATE;
-    {
+    if (!c->cfg.parallel) {      // Parallel OPT keeps the workers identical: nothing to average
         Bracket br(c, 2);
         if (br.rc != QSR_OK) return br.rc;
         HIP_TRY(launch_average_rows(c->params, c->cfg.K, c->cfg.P, c->d_state, c->stream));

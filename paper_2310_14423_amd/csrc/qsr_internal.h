@@ -28,6 +28,8 @@ struct StepScalars {
 struct SchedParams {
     long long T, T_warm;
     long long H_base;
+    long long t_local_start; // post-local phase: H = 1 for rounds starting before it
+    int power;               // exponent of the rule; 0 = constant H_base
     double alpha;
     const double *eta;      // [T] device
     long long *log_t;       // [T] device: iteration count at each averaging

@@ -11,18 +11,24 @@ namespace qsr {
 //    ("Dealing with Learning Rate Warmup");
 //  - the last round is cut so that training ends with a synchronization: H = T - t.
 // Evaluated in double precision as one division and one multiplication (no pow, no fused
-// operations), so that the integer result is reproducible bit for bit.
+// operations), so that the integer result is reproducible bit for bit.  The same routine
+// serves the schedules the paper compares with: a general integer power gamma (1: H ~ 1/eta,
+// 3: the cubic rule of App. F) by repeated multiplication, constant H (gamma = 0), and the
+// post-local schedule (H = 1 for rounds that start before a switching iteration).
 #pragma clang fp contract(off)
 __device__ long long get_H(const SchedParams &sp, long long t)
 {
     long long rem = sp.T - t;
     if (rem <= 0) return 0;
+    if (t < sp.t_local_start) return 1;
+    if (sp.power == 0) return sp.H_base < rem ? sp.H_base : rem;
     long long te = t < sp.T_warm ? sp.T_warm : t;
     if (te >= sp.T) return rem;
     double e = sp.eta[te];
     if (!(e > 0.0)) return rem;
     double q = sp.alpha / e;
-    double v = q * q;
+    double v = q;
+    for (int i = 1; i < sp.power; ++i) v = v * q;
     if (!(v < (double)rem)) return rem;       // also catches inf / NaN
     long long H = (long long)floor(v);
     if (H < sp.H_base) H = sp.H_base;

@@ -352,6 +352,39 @@ def test_resmlp_short_run():
     ctx.close()
 
 
+@pytest.mark.parametrize("kw", [dict(power=3, alpha=0.012, H_base=4), dict(power=1, alpha=0.03, H_base=4),
+                                dict(power=0, H_base=7), dict(power=0, H_base=8, t_local_start=700),
+                                dict(power=2, alpha=0.0175, H_base=4, t_local_start=300)])
+def test_other_synchronization_schedules_are_bit_exact(kw):
+    """The schedules the paper compares QSR with (H ~ 1/eta, the cubic rule, constant H,
+    post-local): integer sequences against the oracle for a whole run."""
+    w = dict(workloads.get("flat60m"), P=8, K=2, T=2000, eta_max=0.008, **kw)
+    ctx = gpu_ctx(w, theta0=np.zeros(8, np.float32))
+    orc = oracle_run(w, theta0=np.zeros(8, np.float32))
+    ctx.step(2000); orc.step(2000)
+    gt, gH = ctx.read_sync_log()
+    assert list(gt) == list(orc.sync_log) and list(gH) == list(orc.H_log) and gt[-1] == 2000
+    assert len(gt) > 3
+    ctx.close()
+
+
+@pytest.mark.parametrize("opt", ["sgdm", "adamw"])
+def test_parallel_opt(opt):
+    """Alg. 1 (gradient averaging every step) on the least-squares workload: all workers stay
+    identical, every step is a round, parameters match the oracle."""
+    kw = dict(mu=0.9, lam=1e-4) if opt == "sgdm" else dict(beta1=0.9, beta2=0.999, eps=1e-8, lam=0.05)
+    w = workloads.get("lsq", d_in=300, B_loc=16, K=4, T=40, eta_max=0.003, opt=opt, H_base=1, power=0,
+                      alpha=0.0, parallel=True, **kw)
+    ctx = gpu_ctx(w)
+    orc = oracle_run(w, n_threads=4)
+    ctx.step(40); orc.step(40)
+    p = ctx.params.cpu().numpy()
+    assert_params_close(p, orc.theta, what="parallel %s" % opt)
+    assert all(np.array_equal(p[k], p[0]) for k in range(4))
+    assert ctx.get_H() == (0, 40, 40)
+    ctx.close()
+
+
 def test_protocol_errors():
     import paper_2310_14423_amd as qsr
     w = _ext_workload("sgdm", 2, 8, 2, mu=0.5, lam=0.0)

@@ -179,3 +179,71 @@ def test_step_past_T_is_an_error():
     run.step(2, ext_g=np.zeros((2, 1, 1)))
     with pytest.raises(RuntimeError):
         run.step(1, ext_g=np.zeros((1, 1, 1)))
+
+
+# ---------------------------------------------------------------------------------------------
+# Parallel OPT (Alg. 1) and the other synchronization schedules the paper compares with
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("opt", ["sgdm", "adamw"])
+def test_parallel_opt_is_the_serial_optimizer_on_the_mean_gradient(opt):
+    rng = np.random.default_rng(11)
+    K, n, T = 3, 5, 12
+    eta = oracle.lr_cosine(T, 2, 0.05, 0.0)
+    g = rng.standard_normal((T, K, n))
+    th0 = rng.standard_normal(n)
+    kw = dict(mu=0.9, lam=0.01) if opt == "sgdm" else dict(beta1=0.9, beta2=0.95, eps=1e-8, lam=0.1)
+    run = oracle.Run(K=K, n=n, eta=eta, T_warm=2, opt=opt, H_base=1, alpha=0.0, power=0, parallel=True,
+                     theta0=th0, **kw)
+    run.step(T, ext_g=g)
+    p = torch.tensor(th0, dtype=torch.float64, requires_grad=True)
+    o = (torch.optim.SGD([p], lr=1.0, momentum=0.9, weight_decay=0.01) if opt == "sgdm" else
+         torch.optim.AdamW([p], lr=1.0, betas=(0.9, 0.95), eps=1e-8, weight_decay=0.1))
+    for t in range(T):
+        for grp in o.param_groups:
+            grp["lr"] = float(eta[t])
+        p.grad = torch.tensor(g[t].mean(axis=0))
+        o.step()
+    for k in range(K):
+        assert np.allclose(run.theta[k], p.detach().numpy(), rtol=1e-11, atol=1e-13)
+    assert run.rounds == T                     # every step communicates: volume 100 %
+
+
+def test_parallel_sgd_equals_local_sgd_with_H1():
+    """Sec. 3 of the paper: parallel SGD is Local SGD with H = 1 (also with momentum, since the
+    update is linear in the gradient and every worker restarts from the same point)."""
+    rng = np.random.default_rng(12)
+    K, n, T = 4, 6, 15
+    eta = oracle.lr_cosine(T, 0, 0.1, 0.0)
+    g = rng.standard_normal((T, K, n))
+    for mu in (0.0, 0.9):
+        a = oracle.Run(K=K, n=n, eta=eta, opt="sgdm", mu=mu, H_base=1, alpha=0.0, parallel=True)
+        b = oracle.Run(K=K, n=n, eta=eta, opt="sgdm", mu=mu, H_base=1, alpha=0.0)
+        a.step(T, ext_g=g); b.step(T, ext_g=g)
+        assert np.allclose(a.theta, b.theta, rtol=1e-12, atol=1e-14)
+
+
+def test_post_local_and_constant_and_power_schedules():
+    T = 60
+    eta = oracle.lr_cosine(T, 0, 0.1, 0.0)
+    g = np.zeros((T, 1, 1))
+    # constant H (power 0): rounds of 7, last one cut
+    r = oracle.Run(K=1, n=1, eta=eta, H_base=7, alpha=0.3, power=0)
+    r.step(T, ext_g=g)
+    assert list(r.H_log) == [7] * 8 + [4]
+    # post-local: H = 1 for rounds starting before t = 20, then constant 8
+    r = oracle.Run(K=1, n=1, eta=eta, H_base=8, alpha=0.0, power=0, t_local_start=20)
+    r.step(T, ext_g=g)
+    assert list(r.H_log) == [1] * 20 + [8] * 5
+    # H ~ 1/eta and the cubic rule follow the power form of Eq. (2)
+    for gamma, coef in ((1, 0.9), (3, 0.12)):
+        r = oracle.Run(K=1, n=1, eta=eta, H_base=2, alpha=coef, power=gamma)
+        r.step(T, ext_g=g)
+        H, st = oracle.schedule(eta, 0, 2, coef, gamma)
+        assert list(r.H_log) == list(H) and list(r.sync_log) == list(st) and len(H) > 3
+        t = 0
+        for Hs in H:
+            v = (coef / eta[t]) ** gamma if eta[t] > 0 else np.inf
+            want = T - t if not v < T - t else min(max(2, int(np.floor(v + 1e-12))), T - t)
+            if abs(v - round(v)) > 1e-6:
+                assert Hs == want
+            t += Hs
