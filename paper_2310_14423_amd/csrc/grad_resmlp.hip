@@ -8,10 +8,10 @@
 //
 // The six GEMMs per block (2 forward, 2 data-gradient, 2 weight-gradient) run on the bf16
 // matrix cores with fp32 accumulation (gemm_bf16.h); the residual stream, LayerNorm statistics,
-// loss and all gradients stay fp32.  Every GEMM is brought to the K-contiguous "NT" form by
-// keeping bf16 copies of the weights in both orientations and transposed bf16 copies of the
-// activations that feed the weight gradients (their token axis padded with zeros to a multiple
-// of 64, so that it can serve as the reduction axis).
+// loss and all gradients stay fp32.  The forward and data-gradient GEMMs are brought to the
+// K-contiguous "NT" form by keeping bf16 copies of the weights in both orientations; the
+// weight-gradient GEMMs reduce over the token axis and read the row-major bf16 activations as
+// they are ("TN" form, LDS transpose reads), so no transposed activation copies exist.
 // Per-block parameter packing: gamma[d], beta[d], W1[d][dh], b1[dh], W2[dh][d], b2[d].
 #include "gemm_bf16.h"
 #include "qsr_internal.h"
@@ -19,7 +19,6 @@
 namespace qsr {
 
 static inline size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
-static inline long long pad64(long long m) { return (m + 63) / 64 * 64; }
 
 constexpr float LN_EPS = 1e-5f;
 constexpr int LN_ROWS_PER_WAVE = 16;
@@ -29,17 +28,13 @@ struct ResWs {
     // per-replica strides are the element counts of one replica's array
     float *X;      long long sX;       // [L+1][M][d]
     float *MU, *RSTD; long long sStat; // [L][M]
-    bf16_t *UT;    long long sUT;      // [L][d][Mp]
-    bf16_t *H;     long long sH;       // [L][M][dh]
-    bf16_t *AT;    long long sAT;      // [L][dh][Mp]
-    bf16_t *U;     long long sU;       // [M][d]
-    bf16_t *A;     long long sA;       // [M][dh]
+    bf16_t *H;     long long sH;       // [L][M][dh]  pre-GELU
+    bf16_t *U;     long long sU;       // [L][M][d]   LayerNorm output
+    bf16_t *A;     long long sA;       // [L][M][dh]  GELU output
     float *Y;      long long sY;       // [M][d]
     float *DX;     long long sDX;      // [2][M][d]
     bf16_t *DXb;   long long sDXb;     // [M][d]
-    bf16_t *DXT;   long long sDXT;     // [d][Mp]
     bf16_t *DH;    long long sDH;      // [M][dh]
-    bf16_t *DHT;   long long sDHT;     // [dh][Mp]
     float *DU;     long long sDU;      // [M][d]
     bf16_t *W1b, *W1Tb, *W2b, *W2Tb; long long sW; // [L][d*dh] each
     bf16_t *WTt;                       // [d][d], shared: teacher map transposed
@@ -50,7 +45,6 @@ struct ResWs {
 static ResWs carve(const ModelDims &dm, void *ws, size_t *total)
 {
     const long long K = dm.K, M = dm.B, d = dm.d_in, dh = dm.d_hidden, L = dm.n_blocks;
-    const long long Mp = pad64(M);
     char *p = (char *)ws;
     size_t off = 0;
     ResWs w;
@@ -61,17 +55,13 @@ static ResWs carve(const ModelDims &dm, void *ws, size_t *total)
     };
     w.sX = (L + 1) * M * d;   w.X = (float *)take(w.sX, 4, K);
     w.sStat = L * M;          w.MU = (float *)take(w.sStat, 4, K); w.RSTD = (float *)take(w.sStat, 4, K);
-    w.sUT = L * d * Mp;       w.UT = (bf16_t *)take(w.sUT, 2, K);
     w.sH = L * M * dh;        w.H = (bf16_t *)take(w.sH, 2, K);
-    w.sAT = L * dh * Mp;      w.AT = (bf16_t *)take(w.sAT, 2, K);
-    w.sU = M * d;             w.U = (bf16_t *)take(w.sU, 2, K);
-    w.sA = M * dh;            w.A = (bf16_t *)take(w.sA, 2, K);
+    w.sU = L * M * d;         w.U = (bf16_t *)take(w.sU, 2, K);
+    w.sA = L * M * dh;        w.A = (bf16_t *)take(w.sA, 2, K);
     w.sY = M * d;             w.Y = (float *)take(w.sY, 4, K);
     w.sDX = 2 * M * d;        w.DX = (float *)take(w.sDX, 4, K);
     w.sDXb = M * d;           w.DXb = (bf16_t *)take(w.sDXb, 2, K);
-    w.sDXT = d * Mp;          w.DXT = (bf16_t *)take(w.sDXT, 2, K);
     w.sDH = M * dh;           w.DH = (bf16_t *)take(w.sDH, 2, K);
-    w.sDHT = dh * Mp;         w.DHT = (bf16_t *)take(w.sDHT, 2, K);
     w.sDU = M * d;            w.DU = (float *)take(w.sDU, 4, K);
     w.sW = L * d * dh;
     w.W1b = (bf16_t *)take(w.sW, 2, K);  w.W1Tb = (bf16_t *)take(w.sW, 2, K);
@@ -430,7 +420,7 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
                               void *ws, float *loss, const DevState *st, hipStream_t s)
 {
     const int K = dm.K, M = (int)dm.B, d = (int)dm.d_in, dh = (int)dm.d_hidden, L = dm.n_blocks;
-    const long long Mp = pad64(M), P = dm.P;
+    const long long P = dm.P;
     const long long per_block = 2LL * d + (long long)d * dh + dh + (long long)dh * d + d;
     ResWs w = carve(dm, ws, nullptr);
     const long long Md = (long long)M * d, Mdh = (long long)M * dh;
@@ -464,18 +454,17 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
         const long long ow = (long long)l * d * dh;
         const float *Xl = w.X + (long long)l * Md;
         float *Xn = w.X + (long long)(l + 1) * Md;
+        bf16_t *Ul = w.U + (long long)l * Md, *Al = w.A + (long long)l * Mdh;
         ln_fwd_kernel<<<dim3((unsigned)((M + 3) / 4), (unsigned)K), 256, 0, s>>>(
-            Xl, w.sX, theta, P, og, w.U, w.sU, w.MU + (long long)l * M, w.RSTD + (long long)l * M, w.sStat, M, d);
+            Xl, w.sX, theta, P, og, Ul, w.sU, w.MU + (long long)l * M, w.RSTD + (long long)l * M, w.sStat, M, d);
         TRY(hipGetLastError());
-        TRY(launch_cvt_transpose<bf16_t>(w.U, d, w.sU, nullptr, 0, w.UT + (long long)l * d * Mp, Mp, w.sUT, M, d, K, s));
         {
-            GemmNT p{w.U, w.W1Tb + ow, M, dh, d, d, d, w.sU, w.sW};
-            EpiBiasGelu epi{theta + ob1, P, w.H + (long long)l * Mdh, w.sH, w.A, w.sA, dh};
+            GemmNT p{Ul, w.W1Tb + ow, M, dh, d, d, d, w.sU, w.sW};
+            EpiBiasGelu epi{theta + ob1, P, w.H + (long long)l * Mdh, w.sH, Al, w.sA, dh};
             TRY((launch_gemm_nt<QSR_GEMM_BIG>(p, epi, K, s)));
         }
-        TRY(launch_cvt_transpose<bf16_t>(w.A, dh, w.sA, nullptr, 0, w.AT + (long long)l * dh * Mp, Mp, w.sAT, M, dh, K, s));
         {
-            GemmNT p{w.A, w.W2Tb + ow, M, d, dh, dh, dh, w.sA, w.sW};
+            GemmNT p{Al, w.W2Tb + ow, M, d, dh, dh, dh, w.sA, w.sW};
             EpiBiasResidual epi{theta + ob2, P, Xl, Xn, w.sX, d};
             TRY((launch_gemm_nt<QSR_GEMM_BIG>(p, epi, K, s)));
         }
@@ -502,11 +491,10 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
         float *DXc = w.DX + (long long)cur * Md, *DXn = w.DX + (long long)(cur ^ 1) * Md;
         // b2 and W2:  db2 = colsum(dx);  dW2 = a^T dx
         TRY(colsum<float>(DXc, w.sDX, w.PART, w.sPART, g + ob2, P, M, d, K, s));
-        TRY(launch_cvt_transpose<bf16_t>(w.DXb, d, w.sDXb, nullptr, 0, w.DXT, Mp, w.sDXT, M, d, K, s));
         {
-            GemmNT p{w.AT + (long long)l * dh * Mp, w.DXT, dh, d, (int)Mp, Mp, Mp, w.sAT, w.sDXT};
+            GemmNT p{w.A + (long long)l * Mdh, w.DXb, dh, d, M, dh, d, w.sA, w.sDXb};
             EpiScaleF32 epi{g + oW2, d, P, 1.0f};
-            TRY((launch_gemm_nt<QSR_GEMM_WGRAD>(p, epi, K, s)));
+            TRY((launch_gemm_tn<QSR_GEMM_WGRAD>(p, epi, K, s)));
         }
         // dh = (dx W2^T) * gelu'(h)
         {
@@ -516,11 +504,10 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
         }
         // b1 and W1:  db1 = colsum(dh);  dW1 = u^T dh
         TRY(colsum<bf16_t>(w.DH, w.sDH, w.PART, w.sPART, g + ob1, P, M, dh, K, s));
-        TRY(launch_cvt_transpose<bf16_t>(w.DH, dh, w.sDH, nullptr, 0, w.DHT, Mp, w.sDHT, M, dh, K, s));
         {
-            GemmNT p{w.UT + (long long)l * d * Mp, w.DHT, d, dh, (int)Mp, Mp, Mp, w.sUT, w.sDHT};
+            GemmNT p{w.U + (long long)l * Md, w.DH, d, dh, M, d, dh, w.sU, w.sDH};
             EpiScaleF32 epi{g + oW1, dh, P, 1.0f};
-            TRY((launch_gemm_nt<QSR_GEMM_WGRAD>(p, epi, K, s)));
+            TRY((launch_gemm_tn<QSR_GEMM_WGRAD>(p, epi, K, s)));
         }
         // du = dh W1^T, then LayerNorm backward + residual: dx_l
         {

@@ -266,8 +266,6 @@ static int init_impl(qsr_ctx *c, const float *theta0)
     HIP_TRY(launch_fill_zero(c->state0, n, c->stream));
     if (c->state1) HIP_TRY(launch_fill_zero(c->state1, n, c->stream));
     HIP_TRY(launch_fill_zero(c->d_loss, cfg.K, c->stream));
-    if (cfg.model == QSR_MODEL_RESMLP)   // the zero padding of the transposed activations lives here
-        HIP_TRY(launch_fill_zero((float *)c->workspace, (long long)(c->workspace_bytes / 4), c->stream));
     HIP_TRY(launch_sched_init(c->d_state, c->sp, c->stream));
     HIP_TRY(hipStreamSynchronize(c->stream));
     return QSR_OK;
