@@ -41,13 +41,15 @@ struct GemmNT {
     int M, N, K;
     long long lda, ldb;
     long long sA, sB;      // per-batch strides (elements)
+    float *colsum_B;       // TN form only, optional: colsum_B[z*s_colsum + n] = sum_k B[z][k][n]
+    long long s_colsum;
 };
 
 template <int BM, int BN, int BK, int WM, int WN, class Epi>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_bf16_kernel(GemmNT p, Epi epi)
 {
     static_assert(BK == 64, "rows are 8 pieces of 16 B");
-    constexpr int NT = WM * WN * 64, NW = WM * WN;
+    constexpr int NW = WM * WN;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     constexpr int A_CHUNKS = BM / 8, B_CHUNKS = BN / 8;      // 1 KiB chunks (8 rows) per slab
     constexpr int A_PER_WAVE = A_CHUNKS / NW, B_PER_WAVE = B_CHUNKS / NW;
@@ -175,6 +177,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_bf16_kernel(GemmNT p, Ep
 // such reads give the 8 k values of an MFMA operand, and the four groups of a wavefront cover
 // 32 features x 16 tokens in exactly the instruction's operand layout.  K (tokens) may be
 // ragged: rows beyond it are zero-filled.  M and N must be multiples of 8.
+// By-product: the workgroups of the first M-tile also add up the columns of the B slabs as they
+// pass through LDS (sum over tokens, fixed order), which yields the bias gradient that goes
+// with each weight gradient without another pass over the activations.
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 
 template <int BM, int BN, int BK, int WM, int WN, class Epi>
@@ -249,12 +254,26 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_tn_bf16_kernel(GemmNT p, Ep
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
     const int nk = (p.K + BK - 1) / BK;
+    // column sums of B: thread = (column pair, token group); groups are combined at the end
+    constexpr int CS_PAIRS = BN / 2, CS_GROUPS = NT / CS_PAIRS, CS_TOK = BK / CS_GROUPS;
+    static_assert(NT % CS_PAIRS == 0 && BK % CS_GROUPS == 0, "column-sum layout");
+    const bool do_colsum = p.colsum_B != nullptr && blockIdx.y == 0;
+    const int cs_pair = tid % CS_PAIRS, cs_grp = tid / CS_PAIRS;
+    float csum0 = 0.f, csum1 = 0.f;
     load_global(0);
     store_lds(0);
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
         const int cur = kt & 1;
         if (kt + 1 < nk) load_global((kt + 1) * BK);
+        if (do_colsum) {
+#pragma unroll
+            for (int k = 0; k < CS_TOK; ++k) {
+                const uint32_t two = *(const uint32_t *)(&Bs[cur][(cs_grp * CS_TOK + k) * LDB + 2 * cs_pair]);
+                csum0 += __uint_as_float(two << 16);            // bf16 -> fp32 is a 16-bit shift
+                csum1 += __uint_as_float(two & 0xffff0000u);
+            }
+        }
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
             bf16x8 fa[TM], fb[TN];
@@ -270,6 +289,18 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_tn_bf16_kernel(GemmNT p, Ep
         }
         if (kt + 1 < nk) store_lds(cur ^ 1);
         __syncthreads();
+    }
+    if (do_colsum) {                                   // all slabs are consumed: LDS is free
+        float *red = (float *)gemm_smem;               // [CS_GROUPS][BN]
+        red[cs_grp * BN + 2 * cs_pair] = csum0;
+        red[cs_grp * BN + 2 * cs_pair + 1] = csum1;
+        __syncthreads();
+        if (tid < BN && n0 + tid < p.N) {
+            float t = 0.f;
+#pragma unroll
+            for (int q = 0; q < CS_GROUPS; ++q) t += red[q * BN + tid];
+            p.colsum_B[(long long)z * p.s_colsum + n0 + tid] = t;
+        }
     }
 
 #pragma unroll

@@ -144,7 +144,9 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
-// one wavefront per token row: statistics in fp32, output u = gamma*xhat + beta in bf16
+// One wavefront per token row, the row held in registers as VPL float4 per lane (d <= 256 VPL,
+// d a multiple of 4): statistics in fp32, output u = gamma*xhat + beta in bf16 (64-bit stores).
+template <int VPL>
 __global__ __launch_bounds__(256) void ln_fwd_kernel(const float *__restrict__ X, long long sX,
                                                      const float *__restrict__ theta, long long sTh,
                                                      long long off_gamma, bf16_t *__restrict__ U,
@@ -156,22 +158,45 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const float *__restrict__ X
     if (row >= M) return;
     const float *x = X + (long long)z * sX + (long long)row * d;
     const float *gam = theta + (long long)z * sTh + off_gamma, *bet = gam + d;
+    float4 xv[VPL];
     float s = 0.f;
-    for (int j = lane; j < d; j += 64) s += x[j];
+#pragma unroll
+    for (int c = 0; c < VPL; ++c) {
+        const int j = (lane + c * 64) * 4;
+        xv[c] = j < d ? *(const float4 *)(x + j) : make_float4(0.f, 0.f, 0.f, 0.f);
+        s += (xv[c].x + xv[c].y) + (xv[c].z + xv[c].w);
+    }
     const float mean = wave_sum(s) / (float)d;
     float q = 0.f;
-    for (int j = lane; j < d; j += 64) { float c = x[j] - mean; q = fmaf(c, c, q); }
+#pragma unroll
+    for (int c = 0; c < VPL; ++c) {
+        const int j = (lane + c * 64) * 4;
+        if (j < d) {
+            float a = xv[c].x - mean, b = xv[c].y - mean, e = xv[c].z - mean, f = xv[c].w - mean;
+            q = fmaf(a, a, q); q = fmaf(b, b, q); q = fmaf(e, e, q); q = fmaf(f, f, q);
+        }
+    }
     const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + LN_EPS);
     bf16_t *u = U + (long long)z * sU + (long long)row * d;
-    for (int j = lane; j < d; j += 64) u[j] = (bf16_t)fmaf(gam[j], (x[j] - mean) * rstd, bet[j]);
+#pragma unroll
+    for (int c = 0; c < VPL; ++c) {
+        const int j = (lane + c * 64) * 4;
+        if (j < d) {
+            const float4 gv = *(const float4 *)(gam + j), bv = *(const float4 *)(bet + j);
+            bf16x4 o = {(bf16_t)fmaf(gv.x, (xv[c].x - mean) * rstd, bv.x), (bf16_t)fmaf(gv.y, (xv[c].y - mean) * rstd, bv.y),
+                        (bf16_t)fmaf(gv.z, (xv[c].z - mean) * rstd, bv.z), (bf16_t)fmaf(gv.w, (xv[c].w - mean) * rstd, bv.w)};
+            *(bf16x4 *)(u + j) = o;
+        }
+    }
     if (lane == 0) { MU[(long long)z * sStat + row] = mean; RSTD[(long long)z * sStat + row] = rstd; }
 }
 
-// Backward of LayerNorm plus the residual path, one wavefront per LN_ROWS_PER_WAVE token rows:
+// Backward of LayerNorm plus the residual path, one wavefront per LN_ROWS_PER_WAVE token rows,
+// VPL float4 per lane:
 //   dn = du*gamma; dx_out = dx_in + rstd*(dn - mean(dn) - xhat*mean(dn*xhat))
 // and per-wavefront partial sums of dgamma = sum_m du*xhat, dbeta = sum_m du (reduced by
-// colsum_final_kernel).  DPL = columns per lane.
-template <int DPL>
+// colsum_final_kernel).
+template <int VPL>
 __global__ __launch_bounds__(256) void ln_bwd_kernel(const float *__restrict__ DU, long long sDU,
                                                      const float *__restrict__ X, long long sX,
                                                      const float *__restrict__ MU,
@@ -187,45 +212,61 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const float *__restrict__ D
     const int wr = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
     if (wr >= wave_rows) return;
     const float *gam = theta + (long long)z * sTh + off_gamma;
-    float g[DPL], dg[DPL], db[DPL];
+    float g[VPL][4], dg[VPL][4], db[VPL][4];
 #pragma unroll
-    for (int c = 0; c < DPL; ++c) {
-        int j = lane + c * 64;
-        g[c] = j < d ? gam[j] : 0.f;
-        dg[c] = 0.f; db[c] = 0.f;
+    for (int c = 0; c < VPL; ++c) {
+        const int j = (lane + c * 64) * 4;
+        const float4 gv = j < d ? *(const float4 *)(gam + j) : make_float4(0.f, 0.f, 0.f, 0.f);
+        g[c][0] = gv.x; g[c][1] = gv.y; g[c][2] = gv.z; g[c][3] = gv.w;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { dg[c][e] = 0.f; db[c][e] = 0.f; }
     }
     const int r_end = min(M, (wr + 1) * LN_ROWS_PER_WAVE);
     for (int row = wr * LN_ROWS_PER_WAVE; row < r_end; ++row) {
         const long long o = (long long)row * d;
         const float mean = MU[(long long)z * sStat + row], rstd = RSTD[(long long)z * sStat + row];
-        float xh[DPL], dn[DPL];
+        float xh[VPL][4], dn[VPL][4];
         float s1 = 0.f, s2 = 0.f;
 #pragma unroll
-        for (int c = 0; c < DPL; ++c) {
-            int j = lane + c * 64;
-            float du = 0.f; xh[c] = 0.f;
-            if (j < d) { du = DU[(long long)z * sDU + o + j]; xh[c] = (X[(long long)z * sX + o + j] - mean) * rstd; }
-            dn[c] = du * g[c];
-            s1 += dn[c]; s2 = fmaf(dn[c], xh[c], s2);
-            dg[c] = fmaf(du, xh[c], dg[c]); db[c] += du;
+        for (int c = 0; c < VPL; ++c) {
+            const int j = (lane + c * 64) * 4;
+            float4 duv = make_float4(0.f, 0.f, 0.f, 0.f), xv = make_float4(mean, mean, mean, mean);
+            if (j < d) { duv = *(const float4 *)(DU + (long long)z * sDU + o + j); xv = *(const float4 *)(X + (long long)z * sX + o + j); }
+            const float du[4] = {duv.x, duv.y, duv.z, duv.w}, xx[4] = {xv.x, xv.y, xv.z, xv.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                xh[c][e] = (xx[e] - mean) * rstd;
+                dn[c][e] = du[e] * g[c][e];
+                s1 += dn[c][e]; s2 = fmaf(dn[c][e], xh[c][e], s2);
+                dg[c][e] = fmaf(du[e], xh[c][e], dg[c][e]); db[c][e] += du[e];
+            }
         }
         const float m1 = wave_sum(s1) / (float)d, m2 = wave_sum(s2) / (float)d;
 #pragma unroll
-        for (int c = 0; c < DPL; ++c) {
-            int j = lane + c * 64;
+        for (int c = 0; c < VPL; ++c) {
+            const int j = (lane + c * 64) * 4;
             if (j < d) {
-                float v = DXin[(long long)z * sDX + o + j] + rstd * (dn[c] - m1 - xh[c] * m2);
-                DXout[(long long)z * sDX + o + j] = v;
-                DXb[(long long)z * sDXb + o + j] = (bf16_t)v;
+                const float4 di = *(const float4 *)(DXin + (long long)z * sDX + o + j);
+                float4 v;
+                v.x = di.x + rstd * (dn[c][0] - m1 - xh[c][0] * m2);
+                v.y = di.y + rstd * (dn[c][1] - m1 - xh[c][1] * m2);
+                v.z = di.z + rstd * (dn[c][2] - m1 - xh[c][2] * m2);
+                v.w = di.w + rstd * (dn[c][3] - m1 - xh[c][3] * m2);
+                *(float4 *)(DXout + (long long)z * sDX + o + j) = v;
+                bf16x4 b = {(bf16_t)v.x, (bf16_t)v.y, (bf16_t)v.z, (bf16_t)v.w};
+                *(bf16x4 *)(DXb + (long long)z * sDXb + o + j) = b;
             }
         }
     }
     float *pg = PART + (long long)z * sPART + (long long)wr * d;
     float *pb = PART + (long long)z * sPART + ((long long)wave_rows + wr) * d;
 #pragma unroll
-    for (int c = 0; c < DPL; ++c) {
-        int j = lane + c * 64;
-        if (j < d) { pg[j] = dg[c]; pb[j] = db[c]; }
+    for (int c = 0; c < VPL; ++c) {
+        const int j = (lane + c * 64) * 4;
+        if (j < d) {
+            *(float4 *)(pg + j) = make_float4(dg[c][0], dg[c][1], dg[c][2], dg[c][3]);
+            *(float4 *)(pb + j) = make_float4(db[c][0], db[c][1], db[c][2], db[c][3]);
+        }
     }
 }
 
@@ -455,9 +496,15 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
         const float *Xl = w.X + (long long)l * Md;
         float *Xn = w.X + (long long)(l + 1) * Md;
         bf16_t *Ul = w.U + (long long)l * Md, *Al = w.A + (long long)l * Mdh;
-        ln_fwd_kernel<<<dim3((unsigned)((M + 3) / 4), (unsigned)K), 256, 0, s>>>(
-            Xl, w.sX, theta, P, og, Ul, w.sU, w.MU + (long long)l * M, w.RSTD + (long long)l * M, w.sStat, M, d);
-        TRY(hipGetLastError());
+        {
+            dim3 grid((unsigned)((M + 3) / 4), (unsigned)K);
+#define LN_FWD(VPL) ln_fwd_kernel<VPL><<<grid, 256, 0, s>>>(Xl, w.sX, theta, P, og, Ul, w.sU, w.MU + (long long)l * M, \
+                        w.RSTD + (long long)l * M, w.sStat, M, d)
+            const int vpl = (d + 255) / 256;
+            if (vpl <= 1) LN_FWD(1); else if (vpl <= 2) LN_FWD(2); else if (vpl <= 3) LN_FWD(3); else LN_FWD(4);
+#undef LN_FWD
+            TRY(hipGetLastError());
+        }
         {
             GemmNT p{Ul, w.W1Tb + ow, M, dh, d, d, d, w.sU, w.sW};
             EpiBiasGelu epi{theta + ob1, P, w.H + (long long)l * Mdh, w.sH, Al, w.sA, dh};
@@ -489,10 +536,9 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
                         oW2 = ob1 + dh, ob2 = oW2 + (long long)dh * d;
         const long long ow = (long long)l * d * dh;
         float *DXc = w.DX + (long long)cur * Md, *DXn = w.DX + (long long)(cur ^ 1) * Md;
-        // b2 and W2:  db2 = colsum(dx);  dW2 = a^T dx
-        TRY(colsum<float>(DXc, w.sDX, w.PART, w.sPART, g + ob2, P, M, d, K, s));
+        // W2 and b2:  dW2 = a^T dx, db2 = column sums of dx (by-product of the same GEMM)
         {
-            GemmNT p{w.A + (long long)l * Mdh, w.DXb, dh, d, M, dh, d, w.sA, w.sDXb};
+            GemmNT p{w.A + (long long)l * Mdh, w.DXb, dh, d, M, dh, d, w.sA, w.sDXb, g + ob2, P};
             EpiScaleF32 epi{g + oW2, d, P, 1.0f};
             TRY((launch_gemm_tn<QSR_GEMM_WGRAD>(p, epi, K, s)));
         }
@@ -502,10 +548,9 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
             EpiGeluBwd epi{w.H + (long long)l * Mdh, w.sH, w.DH, w.sDH, dh};
             TRY((launch_gemm_nt<QSR_GEMM_BIG>(p, epi, K, s)));
         }
-        // b1 and W1:  db1 = colsum(dh);  dW1 = u^T dh
-        TRY(colsum<bf16_t>(w.DH, w.sDH, w.PART, w.sPART, g + ob1, P, M, dh, K, s));
+        // W1 and b1:  dW1 = u^T dh, db1 = column sums of dh
         {
-            GemmNT p{w.U + (long long)l * Md, w.DH, d, dh, M, d, dh, w.sU, w.sDH};
+            GemmNT p{w.U + (long long)l * Md, w.DH, d, dh, M, d, dh, w.sU, w.sDH, g + ob1, P};
             EpiScaleF32 epi{g + oW1, dh, P, 1.0f};
             TRY((launch_gemm_tn<QSR_GEMM_WGRAD>(p, epi, K, s)));
         }
@@ -519,11 +564,10 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
             dim3 grid((unsigned)((wave_rows + 3) / 4), (unsigned)K);
             const float *Xl = w.X + (long long)l * Md;
             const float *mu = w.MU + (long long)l * M, *rs = w.RSTD + (long long)l * M;
-#define LN_BWD(DPL) ln_bwd_kernel<DPL><<<grid, 256, 0, s>>>(w.DU, w.sDU, Xl, w.sX, mu, rs, w.sStat, theta, P, og, \
+#define LN_BWD(VPL) ln_bwd_kernel<VPL><<<grid, 256, 0, s>>>(w.DU, w.sDU, Xl, w.sX, mu, rs, w.sStat, theta, P, og, \
                         DXc, DXn, w.sDX, w.DXb, w.sDXb, w.PART, w.sPART, wave_rows, M, d)
-            const int dpl = (d + 63) / 64;
-            if (dpl <= 2) LN_BWD(2); else if (dpl <= 4) LN_BWD(4); else if (dpl <= 8) LN_BWD(8);
-            else if (dpl <= 12) LN_BWD(12); else LN_BWD(16);
+            const int vpl = (d + 255) / 256;
+            if (vpl <= 1) LN_BWD(1); else if (vpl <= 2) LN_BWD(2); else if (vpl <= 3) LN_BWD(3); else LN_BWD(4);
 #undef LN_BWD
             TRY(hipGetLastError());
             colsum_final_kernel<<<dim3((unsigned)((d + 63) / 64), (unsigned)K), 256, 0, s>>>(
