@@ -27,14 +27,18 @@ __device__ __forceinline__ void add_comp(float &s, float &c, float r)
 // predicated on k < K), then K stores.  From a sweep on MI355X (K = 16 and 32, P = 60e6):
 // one-wavefront workgroups making one trip each gave 5.7 TB/s (K = 16) and 5.5 TB/s (K = 32),
 // 8-20 % above 256-thread blocks in a capped grid and above the chunked variant below.
-template <int KMAX>
-__global__ __launch_bounds__(AVG_THREADS) void average_rows_full_kernel(
+// THREADS: 64 for the stand-alone entry point (fastest); the predicated in-run launch, which is
+// skipped on the device in all but a handful of iterations, uses 256 so that a skipped launch
+// has four times fewer workgroups to retire (0.013 ms instead of 0.05 ms at P = 60e6) at the
+// price of 3 % on the launches that do average.
+template <int KMAX, int THREADS>
+__global__ __launch_bounds__(THREADS) void average_rows_full_kernel(
     float *__restrict__ buf, int K, long long P4, const DevState *__restrict__ st)
 {
     if (st != nullptr && st->do_sync == 0) return;
     const float fK = (float)K;
-    const long long stride = (long long)gridDim.x * AVG_THREADS;
-    for (long long i = (long long)blockIdx.x * AVG_THREADS + threadIdx.x; i < P4; i += stride) {
+    const long long stride = (long long)gridDim.x * THREADS;
+    for (long long i = (long long)blockIdx.x * THREADS + threadIdx.x; i < P4; i += stride) {
         float4 *col = (float4 *)buf + i;
         float4 r[KMAX];
 #pragma unroll
@@ -114,12 +118,16 @@ hipError_t launch_average_rows(float *buf, int K, long long P, const DevState *s
     if ((P & 3) == 0) {
         const long long P4 = P / 4;
         const int grid = avg_grid(P4, AVG_THREADS);
-        if (K <= 8)
-            average_rows_full_kernel<8><<<grid, AVG_THREADS, 0, s>>>(buf, K, P4, st);
-        else if (K <= 32)
-            average_rows_full_kernel<32><<<grid, AVG_THREADS, 0, s>>>(buf, K, P4, st);
-        else
+        const int grid256 = avg_grid(P4, 256);
+        if (K <= 8) {
+            if (st) average_rows_full_kernel<8, 256><<<grid256, 256, 0, s>>>(buf, K, P4, st);
+            else average_rows_full_kernel<8, AVG_THREADS><<<grid, AVG_THREADS, 0, s>>>(buf, K, P4, st);
+        } else if (K <= 32) {
+            if (st) average_rows_full_kernel<32, 256><<<grid256, 256, 0, s>>>(buf, K, P4, st);
+            else average_rows_full_kernel<32, AVG_THREADS><<<grid, AVG_THREADS, 0, s>>>(buf, K, P4, st);
+        } else {
             average_rows_vec4_kernel<<<grid, AVG_THREADS, 0, s>>>(buf, K, P4, st);
+        }
     } else {
         average_rows_scalar_kernel<<<avg_grid(P, AVG_THREADS), AVG_THREADS, 0, s>>>(buf, K, P, st);
     }

@@ -8,17 +8,17 @@
 // [col l%32], and accumulator element i is D[(i/4)*8 + (l/32)*4 + i%4][l%32].
 //
 // Tiling: a workgroup of WM x WN wavefronts computes a BM x BN tile; K is walked in slabs of
-// BK = 64 staged through two LDS buffers.  The slabs are copied global -> LDS directly
+// BK = 64 (or 32) staged through two LDS buffers.  The slabs are copied global -> LDS directly
 // (global_load_lds_dwordx4: no register staging, no LDS store instructions), slab j+1 in
 // flight while slab j is multiplied.  That instruction writes 64 lanes x 16 B to 1 KiB of
 // consecutive LDS, so rows are stored unpadded (8 pieces of 16 B) and bank conflicts are
-// avoided by an XOR swizzle instead: slot s of row r holds piece s ^ ((r >> 1) & 7), which
-// spreads the 128-bit fragment reads of 16 consecutive rows over all 64 banks (measured: no
-// conflicts).  Timed on MI355X at 12608 x 768 x 3072, batch 8: register-staged copy 0.58 ms,
+// avoided by an XOR swizzle instead: slot s of row r holds piece s ^ ((r >> 1) & 7) (BK = 32:
+// s ^ ((r >> 2) & 3)), which spreads the 128-bit fragment reads of 16 consecutive rows over all
+// 64 banks (measured: no conflicts).  Timed on MI355X at 12608 x 768 x 3072, batch 8: register-staged copy 0.58 ms,
 // direct copy 0.49 ms, plus the XCD-aware tile order 0.47 ms (1.01 PFLOP/s).
 // M and N may be ragged: out-of-range rows are clamped to the last valid row on load (they
 // only feed accumulator rows that are never stored) and the epilogue is bounds-checked.
-// K must be a multiple of 64 and lda/ldb multiples of 8 elements (16-byte rows).
+// K must be a multiple of BK and lda/ldb multiples of 8 elements (16-byte rows).
 //
 // The two operands are handed to the instruction in swapped roles (the B rows as its "A", the A
 // rows as its "B"), so that it produces the transposed tile: lane l then owns, for token row
@@ -48,10 +48,13 @@ struct GemmNT {
 template <int BM, int BN, int BK, int WM, int WN, class Epi>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_bf16_kernel(GemmNT p, Epi epi)
 {
-    static_assert(BK == 64, "rows are 8 pieces of 16 B");
+    static_assert(BK == 64 || BK == 32, "rows are 8 or 4 pieces of 16 B");
+    constexpr int PPR = BK / 8;             // 16-byte pieces per row
+    constexpr int RPC = 64 / PPR;           // rows per 1 KiB chunk
+    constexpr int SWZ = BK == 64 ? 1 : 2;   // slot = piece ^ ((row >> SWZ) & (PPR - 1))
     constexpr int NW = WM * WN;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
-    constexpr int A_CHUNKS = BM / 8, B_CHUNKS = BN / 8;      // 1 KiB chunks (8 rows) per slab
+    constexpr int A_CHUNKS = BM / RPC, B_CHUNKS = BN / RPC;   // 1 KiB chunks per slab
     constexpr int A_PER_WAVE = A_CHUNKS / NW, B_PER_WAVE = B_CHUNKS / NW;
     static_assert(A_CHUNKS % NW == 0 && B_CHUNKS % NW == 0, "chunks / waves");
     constexpr int STAGES = 2;
@@ -75,20 +78,20 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_bf16_kernel(GemmNT p, Ep
     const bf16_t *B = p.B + (long long)z * p.sB;
 
     // per-lane global source of each chunk this wave copies: LDS slot (row, s) of a chunk holds
-    // the global piece s ^ ((row >> 1) & 7) of that row
-    const int lrow = lane >> 3, lslot = lane & 7;
+    // the global piece s ^ ((row >> SWZ) & (PPR - 1)) of that row
+    const int lrow = lane / PPR, lslot = lane % PPR;
     const bf16_t *srcA[A_PER_WAVE], *srcB[B_PER_WAVE];
 #pragma unroll
     for (int i = 0; i < A_PER_WAVE; ++i) {
-        int row = (wave * A_PER_WAVE + i) * 8 + lrow;
-        int piece = lslot ^ ((row >> 1) & 7);
+        int row = (wave * A_PER_WAVE + i) * RPC + lrow;
+        int piece = lslot ^ ((row >> SWZ) & (PPR - 1));
         int gm = min(m0 + row, p.M - 1);
         srcA[i] = A + (long long)gm * p.lda + piece * 8;
     }
 #pragma unroll
     for (int i = 0; i < B_PER_WAVE; ++i) {
-        int row = (wave * B_PER_WAVE + i) * 8 + lrow;
-        int piece = lslot ^ ((row >> 1) & 7);
+        int row = (wave * B_PER_WAVE + i) * RPC + lrow;
+        int piece = lslot ^ ((row >> SWZ) & (PPR - 1));
         int gn = min(n0 + row, p.N - 1);
         srcB[i] = B + (long long)gn * p.ldb + piece * 8;
     }
@@ -130,12 +133,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_bf16_kernel(GemmNT p, Ep
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 int row = wm * TM * 32 + i * 32 + (lane & 31);
-                fa[i] = *(const bf16x8 *)(sa + row * BK + ((piece ^ ((row >> 1) & 7)) * 8));
+                fa[i] = *(const bf16x8 *)(sa + row * BK + ((piece ^ ((row >> SWZ) & (PPR - 1))) * 8));
             }
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 int row = wn * TN * 32 + j * 32 + (lane & 31);
-                fb[j] = *(const bf16x8 *)(sb + row * BK + ((piece ^ ((row >> 1) & 7)) * 8));
+                fb[j] = *(const bf16x8 *)(sb + row * BK + ((piece ^ ((row >> SWZ) & (PPR - 1))) * 8));
             }
 #pragma unroll
             for (int i = 0; i < TM; ++i)

@@ -450,8 +450,10 @@ struct EpiGeluBwd {              // dh = acc * gelu'(h)
 // Tile shapes (BM, BN, BK, wavefronts in M, wavefronts in N), from timing the three GEMM shapes of
 // the benchmark size (tokens x width x hidden = 12608 x 768 x 3072, batch 8) on MI355X:
 // 256x256x64 tiles with 8 wavefronts were fastest where the token axis is M (fwd, dgrad: 4800 or
-// 1200 workgroups); the weight-gradient GEMMs have only 3072 x 768 outputs per worker, where
-// 256x256 tiles would leave 288 workgroups for 256 CUs, so they use 128x128x64 (1152 workgroups).
+// 1200 workgroups), also for the two GEMMs with the heavy GELU epilogues (128x256x32 tiles, which
+// fit three workgroups per CU so that epilogues could overlap main loops, were 10 % slower);
+// the weight-gradient GEMMs have only 3072 x 768 outputs per worker, where 256x256 tiles would
+// leave 288 workgroups for 256 CUs, so they use 128x128x64 (1152 workgroups).
 #define QSR_GEMM_BIG 256, 256, 64, 2, 4
 #define QSR_GEMM_WGRAD 128, 128, 64, 2, 2
 
