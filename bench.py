@@ -19,6 +19,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
+MFMA_BF16_PEAK_TFLOPS = 2500.0 # MI355X dense bf16 matrix cores, vendor figure
 BYTES_PER_UPDATE = {"adamw": 28, "sgdm": 20}   # algorithmic HBM bytes per replica-parameter
 BYTES_PER_AVERAGE = 8
 
@@ -128,7 +129,20 @@ def main():
     upd_bytes = BYTES_PER_UPDATE[w["opt"]] * K * P
     roofline = None
     kernels = {}
-    if cnt[1] > 0:
+    if w["model"] == "resmlp" and cnt[0] > 0:
+        # the dense contraction dominates: 6 GEMMs of 2*M*d*dh flop per block and worker; the
+        # duration is that of the whole gradient stage (GEMMs and their HBM-bound helpers)
+        flops = 6 * w["n_blocks"] * K * 2.0 * w["B_loc"] * w["d_in"] * w["d_hidden"]
+        g_ms = ms[0] / cnt[0]
+        ach = flops / (g_ms * 1e-3) / 1e12
+        roofline = {"kernel": "gradient stage: gemm_nt_bf16_kernel / gemm_tn_bf16_kernel + helpers",
+                    "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "avg_ms": g_ms,
+                    "launches": cnt[0], "flops_per_launch": flops}
+        kernels["gradient_ms_avg"] = g_ms
+        kernels["update_ms_avg"] = ms[1] / cnt[1]
+        kernels["update_GBs"] = upd_bytes / (ms[1] / cnt[1] * 1e-3) / 1e9
+    elif cnt[1] > 0:
         upd_ms = ms[1] / cnt[1]
         ach = upd_bytes / (upd_ms * 1e-3) / 1e9
         roofline = {"kernel": "update_%s_kernel" % w["opt"], "bound": "hbm", "achieved": ach,
@@ -163,12 +177,13 @@ def main():
         "metric": "replica-param updates/s", "value": K * P * steps / dt, "unit": "updates/s",
         "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": dt * 1e3 / steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "bf16" if w["model"] == "resmlp" else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "K": K, "P": P, "T": T, "optimizer": w["opt"],
                    "model": w["model"], "H_base": w["H_base"], "alpha": w["alpha"],
                    "lr": w["lr"], "eta_max": w["eta_max"]},
         "sync_rounds": rounds,
-        "hbm_GBs_update": roofline["achieved"] if roofline else None,
+        "hbm_GBs_update": (kernels.get("update_GBs") if w["model"] == "resmlp"
+                           else (roofline["achieved"] if roofline else None)),
         "kernels": kernels,
         "roofline": roofline,
     }

@@ -332,7 +332,12 @@ inline hipError_t launch_gemm_nt(const GemmNT &p, const Epi &epi, int batch, hip
     constexpr size_t smem = 2 * (size_t)(BM + BN) * BK * sizeof(bf16_t);
     static_assert(smem <= 160 * 1024, "tile does not fit the 160 KB LDS");
     auto kern = gemm_nt_bf16_kernel<BM, BN, BK, WM, WN, Epi>;
-    if (smem > 64 * 1024) { hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); if (e != hipSuccess) return e; }
+    static bool lds_limit_raised = false;     // per instantiation; contexts are not thread-safe
+    if (smem > 64 * 1024 && !lds_limit_raised) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        lds_limit_raised = true;
+    }
     kern<<<grid, WM * WN * 64, smem, s>>>(p, epi);
     return hipGetLastError();
 }
@@ -344,9 +349,11 @@ inline hipError_t launch_gemm_tn(const GemmNT &p, const Epi &epi, int batch, hip
     constexpr size_t smem = 2 * (size_t)BK * (BM + 32 + BN + 32) * sizeof(bf16_t);
     static_assert(smem <= 160 * 1024, "tile does not fit the 160 KB LDS");
     auto kern = gemm_tn_bf16_kernel<BM, BN, BK, WM, WN, Epi>;
-    if (smem > 64 * 1024) {
+    static bool lds_limit_raised = false;     // per instantiation; contexts are not thread-safe
+    if (smem > 64 * 1024 && !lds_limit_raised) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
+        lds_limit_raised = true;
     }
     kern<<<grid, WM * WN * 64, smem, s>>>(p, epi);
     return hipGetLastError();

@@ -22,7 +22,6 @@ static inline size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 constexpr float LN_EPS = 1e-5f;
 constexpr int LN_ROWS_PER_WAVE = 16;
-constexpr int CS_ROWS = 64;              // rows per partial column sum
 
 struct ResWs {
     // per-replica strides are the element counts of one replica's array
@@ -38,7 +37,7 @@ struct ResWs {
     float *DU;     long long sDU;      // [M][d]
     bf16_t *W1b, *W1Tb, *W2b, *W2Tb; long long sW; // [L][d*dh] each
     bf16_t *WTt;                       // [d][d], shared: teacher map transposed
-    float *PART;   long long sPART;    // column-sum partials
+    float *PART;   long long sPART;    // [2][wave_rows][d] partial dgamma, dbeta
     float *LPART;  long long sLPART;   // loss partials
 };
 
@@ -68,10 +67,7 @@ static ResWs carve(const ModelDims &dm, void *ws, size_t *total)
     w.W2b = (bf16_t *)take(w.sW, 2, K);  w.W2Tb = (bf16_t *)take(w.sW, 2, K);
     w.WTt = (bf16_t *)take(d * d, 2, 1);
     const long long wave_rows = (M + LN_ROWS_PER_WAVE - 1) / LN_ROWS_PER_WAVE;
-    const long long cs_chunks = (M + CS_ROWS - 1) / CS_ROWS;
-    long long part = 2 * wave_rows * d;
-    if (cs_chunks * dh > part) part = cs_chunks * dh;
-    w.sPART = part;           w.PART = (float *)take(w.sPART, 4, K);
+    w.sPART = 2 * wave_rows * d; w.PART = (float *)take(w.sPART, 4, K);
     w.sLPART = (M * d + 1023) / 1024; w.LPART = (float *)take(w.sLPART, 4, K);
     if (total) *total = off;
     return w;
@@ -271,35 +267,22 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const float *__restrict__ D
 }
 
 // ---------------------------------------------------------------------------------------------
-// column sums (bias gradients; final stage of the LayerNorm parameter gradients)
+// column sums: final stage of the LayerNorm parameter gradients
 // ---------------------------------------------------------------------------------------------
-template <class T>
-__global__ __launch_bounds__(256) void colsum_partial_kernel(const T *__restrict__ A, long long sA,
-                                                             float *__restrict__ PART, long long sPART,
-                                                             int rows, int cols)
-{
-    const int z = blockIdx.z;
-    const int j = blockIdx.x * 256 + threadIdx.x;
-    if (j >= cols) return;
-    const int r0 = blockIdx.y * CS_ROWS, r1 = min(rows, r0 + CS_ROWS);
-    const T *a = A + (long long)z * sA;
-    float acc = 0.f;
-    for (int r = r0; r < r1; ++r) acc += (float)a[(long long)r * cols + j];
-    PART[(long long)z * sPART + (long long)blockIdx.y * cols + j] = acc;
-}
-
 // out[z][j] = sum_c PART[z][c][j].  A workgroup owns 64 columns; its 4 wavefronts each sum a
 // contiguous quarter of the chunks in ascending order and the four partial sums are added in
 // wavefront order (fixed order: deterministic).
 __global__ __launch_bounds__(256) void colsum_final_kernel(const float *__restrict__ PART, long long sPART,
-                                                           long long part_off, float *__restrict__ out,
-                                                           long long sOut, int chunks, int cols)
+                                                           float *__restrict__ out, long long sOut,
+                                                           int chunks, int cols)
 {
+    // blockIdx.z selects the partial array (0: dgamma, 1: dbeta); the results are adjacent
     __shared__ float red[4][64];
     const int z = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int j = blockIdx.x * 64 + lane;
-    const float *p = PART + (long long)z * sPART + part_off;
+    const float *p = PART + (long long)z * sPART + (long long)blockIdx.z * chunks * cols;
+    out += (long long)blockIdx.z * cols;
     const int per = (chunks + 3) / 4;
     const int c0 = wave * per, c1 = min(chunks, c0 + per);
     float acc = 0.f;
@@ -309,20 +292,6 @@ __global__ __launch_bounds__(256) void colsum_final_kernel(const float *__restri
     __syncthreads();
     if (wave == 0 && j < cols)
         out[(long long)z * sOut + j] = ((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane];
-}
-
-template <class T>
-static hipError_t colsum(const T *A, long long sA, float *PART, long long sPART, float *out, long long sOut,
-                         int rows, int cols, int batch, hipStream_t s)
-{
-    const int chunks = (rows + CS_ROWS - 1) / CS_ROWS;
-    colsum_partial_kernel<T><<<dim3((unsigned)((cols + 255) / 256), (unsigned)chunks, (unsigned)batch), 256, 0, s>>>(
-        A, sA, PART, sPART, rows, cols);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    colsum_final_kernel<<<dim3((unsigned)((cols + 63) / 64), (unsigned)batch), 256, 0, s>>>(
-        PART, sPART, 0, out, sOut, chunks, cols);
-    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -572,11 +541,8 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
             if (vpl <= 1) LN_BWD(1); else if (vpl <= 2) LN_BWD(2); else if (vpl <= 3) LN_BWD(3); else LN_BWD(4);
 #undef LN_BWD
             TRY(hipGetLastError());
-            colsum_final_kernel<<<dim3((unsigned)((d + 63) / 64), (unsigned)K), 256, 0, s>>>(
-                w.PART, w.sPART, 0, g + og, P, wave_rows, d);
-            TRY(hipGetLastError());
-            colsum_final_kernel<<<dim3((unsigned)((d + 63) / 64), (unsigned)K), 256, 0, s>>>(
-                w.PART, w.sPART, (long long)wave_rows * d, g + og + d, P, wave_rows, d);
+            colsum_final_kernel<<<dim3((unsigned)((d + 63) / 64), (unsigned)K, 2), 256, 0, s>>>(
+                w.PART, w.sPART, g + og, P, wave_rows, d);
             TRY(hipGetLastError());
         }
         cur ^= 1;
