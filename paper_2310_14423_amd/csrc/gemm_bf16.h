@@ -22,9 +22,8 @@
 //
 // The two operands are handed to the instruction in swapped roles (the B rows as its "A", the A
 // rows as its "B"), so that it produces the transposed tile: lane l then owns, for token row
-// m = l%32, four consecutive output columns n.  The epilogue functor is called as
-// epi(z, m, n, v[4]) for C[z][m][n..n+3] (N must be a multiple of 4), which lets it use 64-bit
-// bf16x4 and 128-bit fp32x4 accesses on row-major outputs.
+// m = l%32, four consecutive output columns n, which is what the epilogue's LDS staging writes
+// with 128-bit stores (see epilogue_via_lds).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -44,6 +43,43 @@ struct GemmNT {
     float *colsum_B;       // TN form only, optional: colsum_B[z*s_colsum + n] = sum_k B[z][k][n]
     long long s_colsum;
 };
+
+// Epilogue.  The MFMA leaves lane l with 4 consecutive columns of row l%32, i.e. one store
+// instruction would touch 32 different rows.  Each wavefront therefore passes its tile, 32 rows
+// at a time, through a private LDS area (the slab buffers are free by then) and re-reads it
+// so that 16 consecutive lanes hold one row's consecutive columns: the functor is then called
+// as epi(z, m, n, v[4]) for C[z][m][n..n+3] with whole 128- or 256-byte row segments per
+// instruction (N must be a multiple of 4).  Rows are padded by 16 B: conflict-free both ways.
+template <int TM, int TN, class Epi>
+__device__ __forceinline__ void epilogue_via_lds(f32x16 (&acc)[TM][TN], float *stage, int lane,
+                                                 int row0, int col0, int M, int N, int z, const Epi &epi)
+{
+    constexpr int W = TN * 32, LD = W + 4;             // floats per staged row
+    constexpr int LPR = W / 4;                         // lanes per row on the way out
+    constexpr int RPI = 64 / LPR;                      // rows per read instruction
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int eg = 0; eg < 4; ++eg)
+                *(float4 *)(stage + (lane & 31) * LD + j * 32 + eg * 8 + (lane >> 5) * 4) =
+                    make_float4(acc[i][j][eg * 4 + 0], acc[i][j][eg * 4 + 1], acc[i][j][eg * 4 + 2],
+                                acc[i][j][eg * 4 + 3]);
+        __builtin_amdgcn_wave_barrier();               // LDS executes a wavefront's accesses in order
+#pragma unroll
+        for (int it = 0; it < 32 / RPI; ++it) {
+            const int r = it * RPI + lane / LPR, c = (lane % LPR) * 4;
+            const float4 t = *(const float4 *)(stage + r * LD + c);
+            const int row = row0 + i * 32 + r, col = col0 + c;
+            if (row < M && col < N) {
+                const float v[4] = {t.x, t.y, t.z, t.w};
+                epi(z, row, col, v);
+            }
+        }
+        __builtin_amdgcn_wave_barrier();               // LDS executes a wavefront's accesses in order
+    }
+}
 
 template <int BM, int BN, int BK, int WM, int WN, class Epi>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_bf16_kernel(GemmNT p, Epi epi)
@@ -169,22 +205,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_bf16_kernel(GemmNT p, Ep
         mfmas((KS - 1) & 1);
     }
 
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int row = m0 + wm * TM * 32 + i * 32 + (lane & 31);
-        if (row >= p.M) continue;
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int eg = 0; eg < 4; ++eg) {
-                const int col = n0 + wn * TN * 32 + j * 32 + eg * 8 + (lane >> 5) * 4;
-                if (col < p.N) {
-                    const float v[4] = {acc[i][j][eg * 4 + 0], acc[i][j][eg * 4 + 1], acc[i][j][eg * 4 + 2],
-                                        acc[i][j][eg * 4 + 3]};
-                    epi(z, row, col, v);
-                }
-            }
-    }
+    __syncthreads();                                   // every wavefront is done with the slabs
+    epilogue_via_lds<TM, TN>(acc, (float *)gemm_smem + wave * (32 * (TN * 32 + 4)), lane,
+                             m0 + wm * TM * 32, n0 + wn * TN * 32, p.M, p.N, z, epi);
 }
 
 // "TN" form for the weight gradients: both operands are stored with the reduction axis as the
@@ -327,22 +350,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_tn_bf16_kernel(GemmNT p, Ep
         }
     }
 
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int row = m0 + wm * TM * 32 + i * 32 + (lane & 31);
-        if (row >= p.M) continue;
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int eg = 0; eg < 4; ++eg) {
-                const int col = n0 + wn * TN * 32 + j * 32 + eg * 8 + (lane >> 5) * 4;
-                if (col < p.N) {
-                    const float v[4] = {acc[i][j][eg * 4 + 0], acc[i][j][eg * 4 + 1], acc[i][j][eg * 4 + 2],
-                                        acc[i][j][eg * 4 + 3]};
-                    epi(z, row, col, v);
-                }
-            }
-    }
+    __syncthreads();                                   // every wavefront is done with the slabs
+    epilogue_via_lds<TM, TN>(acc, (float *)gemm_smem + wave * (32 * (TN * 32 + 4)), lane,
+                             m0 + wm * TM * 32, n0 + wn * TN * 32, p.M, p.N, z, epi);
 }
 
 template <int BM, int BN, int BK, int WM, int WN, class Epi>
