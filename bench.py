@@ -26,7 +26,7 @@ BYTES_PER_AVERAGE = 8
 # HBM bytes per launch of the update kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE (scaled by a
 # kernel of known size; profiles/flat60m_hbm_traffic_pmc.md).  Valid only for the kernel source
 # the counters were taken on: keyed by the first 16 hex digits of its SHA-256.
-PMC_TRAFFIC = {"flat60m": {"source": "update.hip", "sha256_16": "a1633381720059d5", "bytes": 26.873e9}}
+PMC_TRAFFIC = {"flat60m": {"source": "update.hip", "sha256_16": "a1633381720059d5", "bytes": 26.870e9}}
 
 
 def measured_traffic(workload):

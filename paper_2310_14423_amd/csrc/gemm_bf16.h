@@ -47,9 +47,14 @@ struct GemmNT {
 // Epilogue.  The MFMA leaves lane l with 4 consecutive columns of row l%32, i.e. one store
 // instruction would touch 32 different rows.  Each wavefront therefore passes its tile, 32 rows
 // at a time, through a private LDS area (the slab buffers are free by then) and re-reads it
-// so that 16 consecutive lanes hold one row's consecutive columns: the functor is then called
-// as epi(z, m, n, v[4]) for C[z][m][n..n+3] with whole 128- or 256-byte row segments per
-// instruction (N must be a multiple of 4).  Rows are padded by 16 B: conflict-free both ways.
+// so that 16 consecutive lanes hold one row's consecutive columns: whole 128- or 256-byte row
+// segments per global instruction (N must be a multiple of 4).  Rows are padded by 16 B:
+// conflict-free both ways.  The functor has two parts, so that what it reads from global memory
+// is requested before the LDS round trip and arrives during it:
+//     Aux  epi.pre(z, m, n)            -- loads for C[z][m][n..n+3] (may be empty)
+//     void epi(z, m, n, v[4], aux)     -- consumes the accumulators and stores
+struct NoAux {};
+
 template <int TM, int TN, class Epi>
 __device__ __forceinline__ void epilogue_via_lds(f32x16 (&acc)[TM][TN], float *stage, int lane,
                                                  int row0, int col0, int M, int N, int z, const Epi &epi)
@@ -57,8 +62,16 @@ __device__ __forceinline__ void epilogue_via_lds(f32x16 (&acc)[TM][TN], float *s
     constexpr int W = TN * 32, LD = W + 4;             // floats per staged row
     constexpr int LPR = W / 4;                         // lanes per row on the way out
     constexpr int RPI = 64 / LPR;                      // rows per read instruction
+    constexpr int ITERS = 32 / RPI;
+    const int c = (lane % LPR) * 4, col = col0 + c;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
+        typename Epi::Aux aux[ITERS];
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            const int row = row0 + i * 32 + it * RPI + lane / LPR;
+            if (row < M && col < N) aux[it] = epi.pre(z, row, col);
+        }
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -68,16 +81,16 @@ __device__ __forceinline__ void epilogue_via_lds(f32x16 (&acc)[TM][TN], float *s
                                 acc[i][j][eg * 4 + 3]);
         __builtin_amdgcn_wave_barrier();               // LDS executes a wavefront's accesses in order
 #pragma unroll
-        for (int it = 0; it < 32 / RPI; ++it) {
-            const int r = it * RPI + lane / LPR, c = (lane % LPR) * 4;
+        for (int it = 0; it < ITERS; ++it) {
+            const int r = it * RPI + lane / LPR;
             const float4 t = *(const float4 *)(stage + r * LD + c);
-            const int row = row0 + i * 32 + r, col = col0 + c;
+            const int row = row0 + i * 32 + r;
             if (row < M && col < N) {
                 const float v[4] = {t.x, t.y, t.z, t.w};
-                epi(z, row, col, v);
+                epi(z, row, col, v, aux[it]);
             }
         }
-        __builtin_amdgcn_wave_barrier();               // LDS executes a wavefront's accesses in order
+        __builtin_amdgcn_wave_barrier();
     }
 }
 

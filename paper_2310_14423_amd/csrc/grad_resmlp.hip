@@ -375,7 +375,9 @@ __device__ __forceinline__ bf16x4 pack4(float a, float b, float c, float d)
 
 struct EpiScaleF32 {             // C = scale * acc
     float *C; long long ldc, sC; float scale;
-    __device__ void operator()(int z, int m, int n, const float (&v)[4]) const
+    typedef NoAux Aux;
+    __device__ Aux pre(int, int, int) const { return Aux{}; }
+    __device__ void operator()(int z, int m, int n, const float (&v)[4], const Aux &) const
     {
         *(float4 *)(C + (long long)z * sC + (long long)m * ldc + n) =
             make_float4(v[0] * scale, v[1] * scale, v[2] * scale, v[3] * scale);
@@ -383,7 +385,9 @@ struct EpiScaleF32 {             // C = scale * acc
 };
 struct EpiBiasGelu {             // h = acc + b1; H = bf16(h); A = bf16(gelu(h))
     const float *bias; long long sBias; bf16_t *H; long long sH; bf16_t *A; long long sA; long long ld;
-    __device__ void operator()(int z, int m, int n, const float (&v)[4]) const
+    typedef NoAux Aux;
+    __device__ Aux pre(int, int, int) const { return Aux{}; }
+    __device__ void operator()(int z, int m, int n, const float (&v)[4], const Aux &) const
     {
         const float4 b = *(const float4 *)(bias + (long long)z * sBias + n);
         const float h[4] = {v[0] + b.x, v[1] + b.y, v[2] + b.z, v[3] + b.w};
@@ -397,20 +401,27 @@ struct EpiBiasGelu {             // h = acc + b1; H = bf16(h); A = bf16(gelu(h))
 };
 struct EpiBiasResidual {         // x_out = x_in + acc + b2
     const float *bias; long long sBias; const float *Xin; float *Xout; long long sX; long long ld;
-    __device__ void operator()(int z, int m, int n, const float (&v)[4]) const
+    typedef float4 Aux;
+    __device__ Aux pre(int z, int m, int n) const
+    {
+        return *(const float4 *)(Xin + (long long)z * sX + (long long)m * ld + n);
+    }
+    __device__ void operator()(int z, int m, int n, const float (&v)[4], const Aux &x) const
     {
         const long long o = (long long)z * sX + (long long)m * ld + n;
         const float4 b = *(const float4 *)(bias + (long long)z * sBias + n);
-        const float4 x = *(const float4 *)(Xin + o);
         *(float4 *)(Xout + o) = make_float4(x.x + v[0] + b.x, x.y + v[1] + b.y, x.z + v[2] + b.z, x.w + v[3] + b.w);
     }
 };
 struct EpiGeluBwd {              // dh = acc * gelu'(h)
     const bf16_t *H; long long sH; bf16_t *DH; long long sDH; long long ld;
-    __device__ void operator()(int z, int m, int n, const float (&v)[4]) const
+    typedef bf16x4 Aux;
+    __device__ Aux pre(int z, int m, int n) const
     {
-        const long long o = (long long)m * ld + n;
-        const bf16x4 hb = *(const bf16x4 *)(H + (long long)z * sH + o);
+        return *(const bf16x4 *)(H + (long long)z * sH + (long long)m * ld + n);
+    }
+    __device__ void operator()(int z, int m, int n, const float (&v)[4], const Aux &hb) const
+    {
         float r[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -419,7 +430,7 @@ struct EpiGeluBwd {              // dh = acc * gelu'(h)
             gelu_parts(h, c, pdf);
             r[i] = v[i] * fmaf(h, pdf, c);
         }
-        *(bf16x4 *)(DH + (long long)z * sDH + o) = pack4(r[0], r[1], r[2], r[3]);
+        *(bf16x4 *)(DH + (long long)z * sDH + (long long)m * ld + n) = pack4(r[0], r[1], r[2], r[3]);
     }
 };
 
