@@ -7,7 +7,8 @@ the K-axis replica averaging and the next H from the quadratic rule.  The defaul
 the optimizer-only 60 M-parameter, 16-replica Local AdamW run (T = 5000, 8 rounds): with the
 default --steps the timed region is exactly one complete run, all averaging rounds included.
 
-Prints ONE JSON line (see README for the fields).
+After the headline run, the four other workloads are run briefly and reported under
+"per_workload" (--headline-only skips them).  Prints ONE JSON line.
 """
 import argparse
 import json
@@ -71,40 +72,33 @@ def cpu_baseline(w, seconds_target=15.0):
                       "every step, double precision, %.1f s wall" % (w["K"], P, w["P"], steps, dt)}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=None)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="flat60m", choices=["flat60m", "flat350m", "lsq", "mlp", "resmlp"])
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-kernel-timing", action="store_true",
-                    help="skip the per-kernel HIP events (the roofline object is then null)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (K simulated workers on one MI355X); "
-              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
-        sys.exit(2)
-
-    import numpy as np
+def run_workload(name, steps, warmup, kernel_timing=True):
+    """Runs `steps` iterations of one workload (after `warmup` untimed ones and a restart at
+    t = 0) and returns the fields of the JSON line that depend on the workload."""
     import torch
     import workloads
     import paper_2310_14423_amd as qsr
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
-    w = workloads.get(args.workload)
+    w = workloads.get(name)
     K, P, T = w["K"], w["P"], w["T"]
-    steps = args.steps if args.steps is not None else T
+    if steps is None:
+        steps = T
     ctx = qsr.Context(w, theta0=workloads.theta0(w), model_const=workloads.model_const(w))
 
-    ctx.step(min(args.warmup, T))
+    ctx.step(min(warmup, T))
     ctx.restart()                              # the timed region starts a run at t = 0
-    ctx.timing(not args.no_kernel_timing)
+    ctx.timing(kernel_timing)
     ms = [0.0] * 4
     cnt = [0] * 4
     rounds = 0
+
+    def collect():
+        nonlocal ms, cnt, rounds
+        if kernel_timing:
+            m, c = ctx.read_timing()
+            ms = [a + b for a, b in zip(ms, m)]; cnt = [a + b for a, b in zip(cnt, c)]
+        rounds += ctx.get_H()[1]
+
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     left = steps
@@ -113,22 +107,30 @@ def main():
         ctx.step(n)
         left -= n
         if left > 0 or n == T:                 # a run is complete: collect, start the next one
-            m, c = ctx.read_timing() if not args.no_kernel_timing else ([0] * 4, [0] * 4)
-            ms = [a + b for a, b in zip(ms, m)]; cnt = [a + b for a, b in zip(cnt, c)]
-            rounds += ctx.get_H()[1]
+            collect()
             if left > 0:
                 ctx.restart()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     if steps % T != 0:
-        m, c = ctx.read_timing() if not args.no_kernel_timing else ([0] * 4, [0] * 4)
-        ms = [a + b for a, b in zip(ms, m)]; cnt = [a + b for a, b in zip(cnt, c)]
-        rounds += ctx.get_H()[1]
+        collect()
     ctx.timing(False)
 
     upd_bytes = BYTES_PER_UPDATE[w["opt"]] * K * P
     roofline = None
     kernels = {}
+    if cnt[0] > 0:
+        kernels["gradient_ms_avg"] = ms[0] / cnt[0]
+    if cnt[1] > 0:
+        kernels["update_ms_avg"] = ms[1] / cnt[1]
+        kernels["update_GBs"] = upd_bytes / (ms[1] / cnt[1] * 1e-3) / 1e9
+    if cnt[2] > 0:
+        avg_ms = ms[2] / cnt[2]
+        kernels["average_in_run_ms_avg"] = avg_ms
+        kernels["average_in_run_GBs"] = BYTES_PER_AVERAGE * K * P / (avg_ms * 1e-3) / 1e9
+        kernels["average_in_run_launches"] = cnt[2]
+    if cnt[3] > 0:
+        kernels["average_skipped_ms_avg"] = ms[3] / cnt[3]
     if w["model"] == "resmlp" and cnt[0] > 0:
         # the dense contraction dominates: 6 GEMMs of 2*M*d*dh flop per block and worker; the
         # duration is that of the whole gradient stage (GEMMs and their HBM-bound helpers)
@@ -139,27 +141,13 @@ def main():
                     "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "avg_ms": g_ms,
                     "launches": cnt[0], "flops_per_launch": flops}
-        kernels["gradient_ms_avg"] = g_ms
-        kernels["update_ms_avg"] = ms[1] / cnt[1]
-        kernels["update_GBs"] = upd_bytes / (ms[1] / cnt[1] * 1e-3) / 1e9
     elif cnt[1] > 0:
-        upd_ms = ms[1] / cnt[1]
-        ach = upd_bytes / (upd_ms * 1e-3) / 1e9
+        ach = kernels["update_GBs"]
         roofline = {"kernel": "update_%s_kernel" % w["opt"], "bound": "hbm", "achieved": ach,
                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
-                    "traffic": measured_traffic(args.workload),
-                    "avg_ms": upd_ms, "launches": cnt[1],
+                    "traffic": measured_traffic(name),
+                    "avg_ms": kernels["update_ms_avg"], "launches": cnt[1],
                     "bytes_per_launch": upd_bytes}
-        kernels["update_ms_avg"] = upd_ms
-        if cnt[0] > 0:
-            kernels["gradient_ms_avg"] = ms[0] / cnt[0]
-        if cnt[2] > 0:
-            avg_ms = ms[2] / cnt[2]
-            kernels["average_in_run_ms_avg"] = avg_ms
-            kernels["average_in_run_GBs"] = BYTES_PER_AVERAGE * K * P / (avg_ms * 1e-3) / 1e9
-            kernels["average_in_run_launches"] = cnt[2]
-        if cnt[3] > 0:
-            kernels["average_skipped_ms_avg"] = ms[3] / cnt[3]
 
     # the averaging kernel runs only a handful of times per run: time it in a loop of its own
     reps = 20
@@ -174,22 +162,68 @@ def main():
     kernels["average_standalone_GBs"] = BYTES_PER_AVERAGE * K * P / (a_ms * 1e-3) / 1e9
 
     out = {
-        "metric": "replica-param updates/s", "value": K * P * steps / dt, "unit": "updates/s",
-        "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": dt * 1e3 / steps,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if w["model"] == "resmlp" else "f32", "data": "synthetic",
-        "config": {"workload": args.workload, "K": K, "P": P, "T": T, "optimizer": w["opt"],
+        "value": K * P * steps / dt, "steps": steps, "ms_per_step": dt * 1e3 / steps,
+        "dtype": "bf16" if w["model"] == "resmlp" else "f32",
+        "config": {"workload": name, "K": K, "P": P, "T": T, "optimizer": w["opt"],
                    "model": w["model"], "H_base": w["H_base"], "alpha": w["alpha"],
                    "lr": w["lr"], "eta_max": w["eta_max"]},
         "sync_rounds": rounds,
-        "hbm_GBs_update": (kernels.get("update_GBs") if w["model"] == "resmlp"
-                           else (roofline["achieved"] if roofline else None)),
+        "hbm_GBs_update": kernels.get("update_GBs"),
         "kernels": kernels,
         "roofline": roofline,
     }
     ctx.close()
     del ctx
     torch.cuda.empty_cache()
+    return out, w
+
+
+# short runs of the other workloads, reported next to the headline one
+OTHER_WORKLOADS = {"lsq": dict(steps=None, warmup=5), "mlp": dict(steps=None, warmup=5),
+                   "resmlp": dict(steps=10, warmup=2), "flat350m": dict(steps=100, warmup=2)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="flat60m", choices=["flat60m", "flat350m", "lsq", "mlp", "resmlp"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true",
+                    help="skip the per-kernel HIP events (the roofline object is then null)")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="do not add the short runs of the four other workloads (per_workload)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (K simulated workers on one MI355X); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+
+    res, w = run_workload(args.workload, args.steps, args.warmup, not args.no_kernel_timing)
+    out = {"metric": "replica-param updates/s", "value": res["value"], "unit": "updates/s",
+           "n_gpus": 1, "steps": res["steps"], "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": res["dtype"], "data": "synthetic", "config": res["config"],
+           "sync_rounds": res["sync_rounds"], "hbm_GBs_update": res["hbm_GBs_update"],
+           "kernels": res["kernels"], "roofline": res["roofline"]}
+    if not args.headline_only:
+        per = {}
+        for name, kw in OTHER_WORKLOADS.items():
+            if name == args.workload:
+                continue
+            try:
+                r, _ = run_workload(name, kw["steps"], kw["warmup"])
+                per[name] = {k: r[k] for k in ("value", "steps", "ms_per_step", "dtype", "sync_rounds",
+                                               "hbm_GBs_update", "kernels", "roofline")}
+            except Exception as e:                    # e.g. not enough free HBM for the largest one
+                per[name] = {"error": "%s: %s" % (type(e).__name__, e)}
+        out["per_workload"] = per
     out["cpu_baseline"] = None if args.no_cpu_baseline else cpu_baseline(w)
     print(json.dumps(out))
 
