@@ -385,6 +385,68 @@ def test_parallel_opt(opt):
     ctx.close()
 
 
+@pytest.mark.parametrize("case", [
+    dict(T=1, H_base=1, alpha=0.0),                    # a single iteration, a single round
+    dict(T=7, H_base=50, alpha=0.0),                   # H_base beyond the run: one truncated round
+    dict(T=30, H_base=2, alpha=100.0),                 # (alpha/eta)^2 >> T from the start: H = T
+    dict(T=25, H_base=3, alpha=0.0, power=0),          # constant H, last round cut to 1
+    dict(T=40, H_base=2, alpha=0.3, T_warm=40),        # the whole run is warm-up
+    dict(T=64, H_base=1, alpha=0.0),                   # averaging after every iteration
+])
+def test_degenerate_schedules(case):
+    case = dict(case)
+    w = _ext_workload("sgdm", 3, 37, case.pop("T"), mu=0.9, lam=1e-3, eta_max=0.1, **case)
+    rng = np.random.default_rng(5)
+    th0 = rng.standard_normal(37).astype(np.float32)
+    import torch
+    ctx = gpu_ctx(w, theta0=th0)
+    orc = oracle_run(w, theta0=th0)
+    for t in range(w["T"]):
+        g = rng.standard_normal((3, 37)).astype(np.float32)
+        ctx.grads.copy_(torch.from_numpy(g))
+        ctx.step()
+        orc.step(1, ext_g=g[None].astype(np.float64))
+    gt, gH = ctx.read_sync_log()
+    assert list(gt) == list(orc.sync_log) and list(gH) == list(orc.H_log) and gt[-1] == w["T"]
+    assert_params_close(ctx.params.cpu().numpy(), orc.theta, what=str(case))
+    ctx.close()
+
+
+def test_learning_rate_table_with_zero_tail():
+    """A caller-supplied schedule that reaches exactly 0: the rule switches to H = T - t."""
+    eta = np.concatenate([np.linspace(0.2, 0.01, 30), np.zeros(10)])
+    w = _ext_workload("adamw", 2, 16, 40, H_base=2, alpha=0.05, beta1=0.9, beta2=0.99, eps=1e-8, lam=0.01)
+    import torch
+    ctx = gpu_ctx(w, theta0=np.ones(16, np.float32), eta_table=eta)
+    orc = oracle_run(w, theta0=np.ones(16, np.float32), eta=eta)
+    assert np.array_equal(ctx.eta_table(), eta)
+    rng = np.random.default_rng(8)
+    for t in range(40):
+        g = rng.standard_normal((2, 16)).astype(np.float32)
+        ctx.grads.copy_(torch.from_numpy(g))
+        ctx.step(); orc.step(1, ext_g=g[None].astype(np.float64))
+    gt, gH = ctx.read_sync_log()
+    assert list(gt) == list(orc.sync_log) and list(gH) == list(orc.H_log)
+    assert_params_close(ctx.params.cpu().numpy(), orc.theta, what="zero-tail table")
+    ctx.close()
+
+
+def test_nan_gradient_propagates_without_trapping():
+    """A non-finite gradient entry poisons that parameter (and, after averaging, that column of
+    every worker) and nothing else; the schedule is unaffected."""
+    import torch
+    w = _ext_workload("adamw", 2, 8, 6, H_base=3, alpha=0.0, beta1=0.9, beta2=0.99, eps=1e-8, lam=0.0)
+    ctx = gpu_ctx(w, theta0=np.zeros(8, np.float32))
+    g = np.ones((2, 8), np.float32); g[1, 5] = np.nan
+    for t in range(6):
+        ctx.grads.copy_(torch.from_numpy(g if t == 0 else np.ones((2, 8), np.float32)))
+        ctx.step()
+    p = ctx.params.cpu().numpy()
+    assert np.isnan(p[:, 5]).all() and np.isfinite(np.delete(p, 5, axis=1)).all()
+    assert list(ctx.read_sync_log()[0]) == [3, 6]
+    ctx.close()
+
+
 def test_protocol_errors():
     import paper_2310_14423_amd as qsr
     w = _ext_workload("sgdm", 2, 8, 2, mu=0.5, lam=0.0)
