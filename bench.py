@@ -131,6 +131,9 @@ def run_workload(name, steps, warmup, kernel_timing=True):
         kernels["average_in_run_launches"] = cnt[2]
     if cnt[3] > 0:
         kernels["average_skipped_ms_avg"] = ms[3] / cnt[3]
+    # share of the iteration time spent in the averaging that stands in for the All-Reduce (the
+    # quantity the paper's App. F estimates from wall-clock differences), skipped launches included
+    kernels["averaging_share_of_time"] = (ms[2] + ms[3]) * 1e-3 / dt if kernel_timing else None
     if w["model"] == "resmlp" and cnt[0] > 0:
         # the dense contraction dominates: 6 GEMMs of 2*M*d*dh flop per block and worker; the
         # duration is that of the whole gradient stage (GEMMs and their HBM-bound helpers)

@@ -41,7 +41,15 @@ enum {
 };
 
 enum { QSR_OPT_SGDM = 0, QSR_OPT_ADAMW = 1 };
-enum { QSR_LR_COSINE = 0, QSR_LR_STEP = 1, QSR_LR_TABLE = 2 };
+enum {
+    QSR_LR_COSINE = 0,  /* cosine decay eta_max -> eta_min (Sec. 4 "Training Setup")              */
+    QSR_LR_STEP = 1,    /* eta_max divided by step_factor at each milestone                       */
+    QSR_LR_TABLE = 2,   /* caller-supplied table                                                  */
+    QSR_LR_LINEAR = 3,  /* linear decay eta_max -> eta_min (Sec. 4.1 "Other learning rate
+                           schedules")                                                            */
+    QSR_LR_POW2COS = 4  /* the step schedule the paper derives from the cosine one:
+                           2^round(log2(eta_cos(t))) (Sec. 4.1)                                   */
+};
 enum {
     QSR_MODEL_EXTERNAL = 0, /* caller writes `grads` before each qsr_local_step          */
     QSR_MODEL_NOISE = 1,    /* g = grad_sigma * N(0,1), optimizer-only workloads          */
@@ -68,7 +76,9 @@ typedef struct {
     int32_t parallel;     /* 1 = Parallel OPT (Alg. 1): the K local gradients are averaged every
                              step before OPT, so all workers take the same update; every step
                              counts as a round.  Needs H_base = 1, power = 0.  0 = Local OPT  */
-    int32_t reserved;     /* must be 0                                                     */
+    int32_t average_state;/* 0: optimizer state stays local at a synchronization, as in Alg. 2, which
+                             averages the model parameters only; 1: the state buffers (momentum /
+                             m, v) are averaged with them                                   */
     int64_t P;            /* parameters per worker, >= 1                                   */
     int64_t T;            /* total iterations, eta_t is defined for t in 0..T-1, >= 1      */
     int64_t T_warm;       /* linear warm-up 0 -> eta_max over the first T_warm iterations  */
@@ -79,7 +89,7 @@ typedef struct {
     double momentum;      /* SGD heavy-ball coefficient                                    */
     double beta1, beta2, eps; /* AdamW                                                     */
     double weight_decay;  /* SGD: coupled (added to the gradient); AdamW: decoupled        */
-    double eta_max, eta_min;  /* QSR_LR_COSINE / QSR_LR_STEP peak; cosine floor            */
+    double eta_max, eta_min;  /* peak; floor of the cosine / linear / pow2cos decays            */
     double step_factor;   /* QSR_LR_STEP: eta = eta_max / step_factor^(#milestones <= t)   */
     double alpha;         /* growth coefficient of Eq. (2); 0 gives constant H = H_base    */
     double grad_sigma;    /* QSR_MODEL_NOISE: standard deviation of the gradient           */
@@ -139,6 +149,14 @@ int qsr_eta_table(qsr_ctx *ctx, double *eta_out, int64_t cap);
 /* Synchronises and copies the K per-worker losses of the last local step (models LINREG,
  * MLP2, RESMLP) to the host array loss_out [K]. */
 int qsr_read_loss(qsr_ctx *ctx, float *loss_out);
+
+/* Checkpoint / resume of the scheduler.  qsr_get_state synchronises and returns
+ * state[0..3] = (t, s, h, H).  qsr_set_state installs such a tuple (asynchronously) in a context
+ * of the same configuration whose parameter and optimizer-state buffers the caller has restored;
+ * 0 <= t <= T, 0 <= h < H <= T - t + h required (H = 0 allowed only at t == T).  The log entries
+ * of rounds finished before the restored state read as 0. */
+int qsr_get_state(qsr_ctx *ctx, int64_t state[4]);
+int qsr_set_state(qsr_ctx *ctx, const int64_t state[4]);
 
 /* Puts the scheduler back to t = s = h = 0 (H^(0) recomputed, log cleared) without touching
  * parameters or optimizer state.  Asynchronous. */

@@ -63,6 +63,29 @@ void qsro_lr_cosine(int64_t T, int64_t T_warm, double eta_max, double eta_min,
     }
 }
 
+/* Linear decay (Sec. 4.1): eta_t = eta_max - (eta_max - eta_min) * (t-T_warm)/(T-T_warm) after
+ * the same linear warm-up. */
+void qsro_lr_linear(int64_t T, int64_t T_warm, double eta_max, double eta_min, double *eta)
+{
+    for (int64_t t = 0; t < T; ++t) {
+        if (t < T_warm) {
+            eta[t] = eta_max * (double)t / (double)T_warm;
+        } else {
+            double frac = (double)(t - T_warm) / (double)(T - T_warm);
+            eta[t] = eta_max - (eta_max - eta_min) * frac;
+        }
+    }
+}
+
+/* The step schedule the paper derives from the cosine one (Sec. 4.1):
+ * eta_step(t) = 2^round(log2(eta_cos(t))). */
+void qsro_lr_pow2cos(int64_t T, int64_t T_warm, double eta_max, double eta_min, double *eta)
+{
+    qsro_lr_cosine(T, T_warm, eta_max, eta_min, eta);
+    for (int64_t t = T_warm; t < T; ++t)
+        if (eta[t] > 0.0) eta[t] = exp2(round(log2(eta[t])));
+}
+
 /* eta_t = eta_max / factor^j, j = number of milestones m with m <= t
  * (after the same linear warm-up). */
 void qsro_lr_step(int64_t T, int64_t T_warm, double eta_max, int32_t n_ms,
@@ -460,6 +483,10 @@ int qsro_run(const qsro_config *c, const double *eta, qsro_state *st, double *th
         st->h += 1;
         if (st->h == st->H) {
             qsro_average(theta, K, n);
+            if (c->average_state) {
+                qsro_average(st0, K, n);
+                if (c->opt == 1) qsro_average(st1, K, n);
+            }
             if (sync_log && st->s < log_cap) sync_log[st->s] = st->t;
             st->s += 1;
             st->h = 0;

@@ -16,6 +16,9 @@ typedef struct {
                              variants of Sec. 2 / App. F; 0 = constant H_base    */
     int32_t parallel;     /* 1 = Parallel OPT (Alg. 1): gradients are averaged
                              every step and all workers take the same update  */
+    int32_t average_state;/* 1 = the optimizer state is averaged at a sync too
+                             (Alg. 2 averages the parameters only: 0)           */
+    int32_t pad_;
     int64_t n;            /* tracked parameters per worker (= P, or a sample) */
     int64_t T, T_warm;
     int64_t t_local_start;/* post-local schedule: rounds that start before this

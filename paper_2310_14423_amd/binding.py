@@ -10,12 +10,12 @@ _LIB = os.path.join(_HERE, "libqsr.so")
 _lib = None
 
 EXPORTS = ["qsr_validate", "qsr_workspace_bytes", "qsr_init", "qsr_local_step", "qsr_maybe_sync",
-           "qsr_get_H", "qsr_read_sync_log", "qsr_eta_table", "qsr_read_loss", "qsr_restart",
+           "qsr_get_H", "qsr_get_state", "qsr_set_state", "qsr_read_sync_log", "qsr_eta_table", "qsr_read_loss", "qsr_restart",
            "qsr_timing", "qsr_read_timing", "qsr_destroy", "qsr_average_rows", "qsr_strerror",
            "qsr_last_hip_error"]
 
 OPTS = {"sgdm": 0, "adamw": 1}
-LRS = {"cosine": 0, "step": 1, "table": 2}
+LRS = {"cosine": 0, "step": 1, "table": 2, "linear": 3, "pow2cos": 4}
 MODELS = {"external": 0, "noise": 1, "linreg": 2, "mlp2": 3, "resmlp": 4}
 
 
@@ -32,7 +32,7 @@ class Config(C.Structure):
     _fields_ = [
         ("K", C.c_int32), ("opt", C.c_int32), ("model", C.c_int32), ("lr_kind", C.c_int32),
         ("H_base", C.c_int32), ("n_milestones", C.c_int32), ("n_blocks", C.c_int32),
-        ("power", C.c_int32), ("parallel", C.c_int32), ("reserved", C.c_int32),
+        ("power", C.c_int32), ("parallel", C.c_int32), ("average_state", C.c_int32),
         ("P", C.c_int64), ("T", C.c_int64), ("T_warm", C.c_int64), ("t_local_start", C.c_int64),
         ("B_loc", C.c_int64),
         ("d_in", C.c_int64), ("d_hidden", C.c_int64), ("d_out", C.c_int64),
@@ -76,6 +76,7 @@ def make_config(w, stream=0, eta_table=None):
     c.H_base = w["H_base"]; c.alpha = w["alpha"]
     c.power = w.get("power", 2); c.parallel = int(w.get("parallel", False))
     c.t_local_start = w.get("t_local_start", 0)
+    c.average_state = int(w.get("average_state", False))
     c.P = w["P"]; c.T = w["T"]; c.T_warm = w.get("T_warm", 0)
     c.B_loc = w.get("B_loc", 0); c.d_in = w.get("d_in", 0); c.d_hidden = w.get("d_hidden", 0)
     c.d_out = w.get("d_out", 0); c.n_blocks = w.get("n_blocks", 0)
@@ -190,6 +191,15 @@ class Context:
         out = np.empty(self.w["K"], dtype=np.float32)
         _check(lib().qsr_read_loss(self._ctx, out.ctypes.data_as(C.c_void_p)), "qsr_read_loss")
         return out
+
+    def get_state(self):
+        st = (C.c_int64 * 4)()
+        _check(lib().qsr_get_state(self._ctx, st), "qsr_get_state")
+        return tuple(st)
+
+    def set_state(self, state):
+        st = (C.c_int64 * 4)(*state)
+        _check(lib().qsr_set_state(self._ctx, st), "qsr_set_state")
 
     def restart(self):
         _check(lib().qsr_restart(self._ctx), "qsr_restart")

@@ -80,9 +80,9 @@ extern "C" int qsr_validate(const qsr_config *c, const char **why)
     else if (c->T_warm < 0 || c->T_warm > c->T) w = "T_warm";
     else if (c->opt != QSR_OPT_SGDM && c->opt != QSR_OPT_ADAMW) w = "opt";
     else if (c->model < QSR_MODEL_EXTERNAL || c->model > QSR_MODEL_RESMLP) w = "model";
-    else if (c->lr_kind < QSR_LR_COSINE || c->lr_kind > QSR_LR_TABLE) w = "lr_kind";
+    else if (c->lr_kind < QSR_LR_COSINE || c->lr_kind > QSR_LR_POW2COS) w = "lr_kind";
     else if (c->H_base < 1) w = "H_base";
-    else if (c->reserved != 0) w = "reserved";
+    else if (c->average_state != 0 && c->average_state != 1) w = "average_state";
     else if (c->power < 0 || c->power > 8) w = "power";
     else if (c->parallel != 0 && c->parallel != 1) w = "parallel";
     else if (c->parallel == 1 && (c->H_base != 1 || c->power != 0 || c->t_local_start != 0))
@@ -96,7 +96,9 @@ extern "C" int qsr_validate(const qsr_config *c, const char **why)
         w = "beta1/beta2";
     else if (c->opt == QSR_OPT_ADAMW && !(std::isfinite(c->eps) && c->eps > 0.0)) w = "eps";
     else if (c->lr_kind != QSR_LR_TABLE && !(std::isfinite(c->eta_max) && c->eta_max > 0.0)) w = "eta_max";
-    else if (c->lr_kind == QSR_LR_COSINE && !(finite_ge0(c->eta_min) && c->eta_min <= c->eta_max)) w = "eta_min";
+    else if ((c->lr_kind == QSR_LR_COSINE || c->lr_kind == QSR_LR_LINEAR || c->lr_kind == QSR_LR_POW2COS) &&
+             !(finite_ge0(c->eta_min) && c->eta_min <= c->eta_max))
+        w = "eta_min";
     else if (c->lr_kind == QSR_LR_STEP &&
              (c->n_milestones < 0 || (c->n_milestones > 0 && !c->milestones) ||
               !(std::isfinite(c->step_factor) && c->step_factor > 0.0)))
@@ -181,9 +183,13 @@ static void build_eta(const qsr_config *c, std::vector<double> &eta)
             e = c->eta_table[t];
         } else if (t < Tw) {
             e = c->eta_max * (double)t / (double)Tw;
-        } else if (c->lr_kind == QSR_LR_COSINE) {
+        } else if (c->lr_kind == QSR_LR_COSINE || c->lr_kind == QSR_LR_POW2COS) {
             double frac = (double)(t - Tw) / (double)(T - Tw);
             e = c->eta_min + 0.5 * (c->eta_max - c->eta_min) * (1.0 + std::cos(pi * frac));
+            if (c->lr_kind == QSR_LR_POW2COS && e > 0.0) e = std::exp2(std::round(std::log2(e)));
+        } else if (c->lr_kind == QSR_LR_LINEAR) {
+            double frac = (double)(t - Tw) / (double)(T - Tw);
+            e = c->eta_max - (c->eta_max - c->eta_min) * frac;
         } else {
             double div = 1.0;
             for (int i = 0; i < c->n_milestones; ++i)
@@ -418,6 +424,10 @@ extern "C" int qsr_maybe_sync(qsr_ctx *c)
         HIP_TRY(launch_average_rows(c->params, c->cfg.K, c->cfg.P, c->d_state, c->stream));
         int rc = br.close(c->t_host);
         if (rc != QSR_OK) return rc;
+        if (c->cfg.average_state) {          // same device-side decision, taken before it is cleared
+            HIP_TRY(launch_average_rows(c->state0, c->cfg.K, c->cfg.P, c->d_state, c->stream));
+            if (c->state1) HIP_TRY(launch_average_rows(c->state1, c->cfg.K, c->cfg.P, c->d_state, c->stream));
+        }
     }
     HIP_TRY(launch_sched_next_round(c->d_state, c->sp, c->stream));
     c->need_sync_call = false;
@@ -467,6 +477,27 @@ extern "C" int qsr_read_loss(qsr_ctx *c, float *loss_out)
     if (!c || !loss_out) return QSR_EINVAL;
     HIP_TRY(hipStreamSynchronize(c->stream));
     HIP_TRY(hipMemcpy(loss_out, c->d_loss, (size_t)c->cfg.K * sizeof(float), hipMemcpyDeviceToHost));
+    return QSR_OK;
+}
+
+extern "C" int qsr_get_state(qsr_ctx *c, int64_t state[4])
+{
+    if (!c || !state) return QSR_EINVAL;
+    int rc = fetch_state(c);
+    if (rc != QSR_OK) return rc;
+    state[0] = c->h_state->t; state[1] = c->h_state->s; state[2] = c->h_state->h; state[3] = c->h_state->H;
+    return QSR_OK;
+}
+
+extern "C" int qsr_set_state(qsr_ctx *c, const int64_t state[4])
+{
+    if (!c || !state) return QSR_EINVAL;
+    const long long t = state[0], s = state[1], h = state[2], H = state[3], T = c->cfg.T;
+    if (t < 0 || t > T || s < 0 || s > t || h < 0 || h > t) return QSR_EINVAL;
+    if (t == T ? (H != 0 || h != 0) : (H < 1 || h >= H || H - h > T - t)) return QSR_EINVAL;
+    if (c->need_sync_call) return QSR_ESTATE;
+    HIP_TRY(launch_sched_set(c->d_state, c->sp, t, s, h, H, c->stream));
+    c->t_host = t;
     return QSR_OK;
 }
 

@@ -55,6 +55,8 @@ enum : uint32_t { STREAM_GRAD = 0, STREAM_X = 1, STREAM_NOISE = 2, STREAM_LABEL 
 // ---- launchers (each returns the hipError_t of its launch) --------------------------------
 hipError_t launch_sched_init(DevState *st, SchedParams sp, hipStream_t s);
 hipError_t launch_sched_tick(DevState *st, hipStream_t s);
+hipError_t launch_sched_set(DevState *st, SchedParams sp, long long t, long long s_, long long h, long long H,
+                            hipStream_t s);
 hipError_t launch_sched_next_round(DevState *st, SchedParams sp, hipStream_t s);
 
 hipError_t launch_update_sgdm(float *theta, const float *g, float *buf, long long n,

@@ -44,6 +44,16 @@ __global__ void sched_init_kernel(DevState *st, SchedParams sp)
     st->do_sync = 0; st->pad = 0;
 }
 
+// resume: install a saved (t, s, h, H); log entries of earlier rounds are cleared
+__global__ void sched_set_kernel(DevState *st, SchedParams sp, long long t, long long s, long long h,
+                                 long long H)
+{
+    for (long long i = threadIdx.x; i < s; i += blockDim.x) { sp.log_t[i] = 0; sp.log_H[i] = 0; }
+    if (threadIdx.x != 0) return;
+    st->t = t; st->s = s; st->h = h; st->H = H;
+    st->do_sync = 0; st->pad = 0;
+}
+
 // end of a local step (Alg. 2's inner loop counter)
 __global__ void sched_tick_kernel(DevState *st)
 {
@@ -71,6 +81,12 @@ __global__ void sched_next_round_kernel(DevState *st, SchedParams sp)
 hipError_t launch_sched_init(DevState *st, SchedParams sp, hipStream_t s)
 {
     sched_init_kernel<<<1, 64, 0, s>>>(st, sp);
+    return hipGetLastError();
+}
+hipError_t launch_sched_set(DevState *st, SchedParams sp, long long t, long long s_, long long h, long long H,
+                            hipStream_t s)
+{
+    sched_set_kernel<<<1, 256, 0, s>>>(st, sp, t, s_, h, H);
     return hipGetLastError();
 }
 hipError_t launch_sched_tick(DevState *st, hipStream_t s)

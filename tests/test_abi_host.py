@@ -39,10 +39,10 @@ def test_named_workloads_validate(name):
 
 @pytest.mark.parametrize("field,value,why", [
     ("K", 0, "K"), ("P", 0, "P"), ("T", 0, "T"), ("T_warm", -1, "T_warm"), ("T_warm", 6000, "T_warm"),
-    ("opt", 2, "opt"), ("model", 5, "model"), ("lr_kind", 3, "lr_kind"), ("H_base", 0, "H_base"),
+    ("opt", 2, "opt"), ("model", 5, "model"), ("lr_kind", 5, "lr_kind"), ("H_base", 0, "H_base"),
     ("alpha", -0.1, "alpha"), ("alpha", float("nan"), "alpha"), ("eta_max", 0.0, "eta_max"),
     ("eta_min", 1.0, "eta_min"), ("beta2", 1.0, "beta1/beta2"), ("eps", 0.0, "eps"),
-    ("weight_decay", -1.0, "weight_decay"), ("grad_sigma", -1.0, "grad_sigma"), ("reserved", 1, "reserved"),
+    ("weight_decay", -1.0, "weight_decay"), ("grad_sigma", -1.0, "grad_sigma"), ("average_state", 2, "average_state"),
     ("power", -1, "power"), ("power", 9, "power"), ("parallel", 2, "parallel"),
     ("parallel", 1, "parallel needs H_base = 1, power = 0"), ("t_local_start", -5, "t_local_start"),
 ])
@@ -74,6 +74,7 @@ def test_null_arguments():
     assert L.qsr_local_step(None) == -1 and L.qsr_maybe_sync(None) == -1
     assert L.qsr_get_H(None, None, None, None) == -1
     assert L.qsr_destroy(None) == -1
+    assert L.qsr_get_state(None, None) == -1 and L.qsr_set_state(None, None) == -1
     assert L.qsr_average_rows(None, 2, C.c_int64(8), None) == -1
     cfg, _ = make_config(workloads.get("flat60m"))
     out = C.c_void_p()

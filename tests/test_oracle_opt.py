@@ -247,3 +247,23 @@ def test_post_local_and_constant_and_power_schedules():
             if abs(v - round(v)) > 1e-6:
                 assert Hs == want
             t += Hs
+
+
+def test_state_averaging_option():
+    """Alg. 2 averages the parameters only; with the option on, the optimizer state is averaged
+    at each synchronization too (and otherwise nothing changes)."""
+    rng = np.random.default_rng(13)
+    K, n = 3, 4
+    eta = np.full(6, 0.05)
+    g = rng.standard_normal((6, K, n))
+    a = oracle.Run(K=K, n=n, eta=eta, opt="adamw", lam=0.01, H_base=3, alpha=0.0, average_state=True)
+    b = oracle.Run(K=K, n=n, eta=eta, opt="adamw", lam=0.01, H_base=3, alpha=0.0)
+    a.step(2, ext_g=g[:2]); b.step(2, ext_g=g[:2])
+    assert np.array_equal(a.theta, b.theta) and np.array_equal(a.st0, b.st0)      # before the first sync
+    a.step(1, ext_g=g[2:3]); b.step(1, ext_g=g[2:3])
+    assert np.array_equal(a.theta, b.theta)                                       # parameters agree at the sync
+    for st_a, st_b in ((a.st0, b.st0), (a.st1, b.st1)):
+        assert np.allclose(st_a, np.tile(st_b.mean(axis=0), (K, 1)), rtol=1e-15)
+        assert not np.allclose(st_b[0], st_b[1])
+    a.step(3, ext_g=g[3:]); b.step(3, ext_g=g[3:])
+    assert not np.allclose(a.theta, b.theta)                                      # and the runs differ afterwards

@@ -30,29 +30,20 @@ def _rows():
 
 
 def _table(r):
-    """Learning-rate table for one golden row.  The cosine comes from the oracle; the
-    derived schedules (not on the hot path) are written out here."""
+    """Learning-rate table for one golden row, from the oracle's schedule functions."""
     spe = N_IMAGENET // r["B"]
     T = r["epochs"] * spe
     Tw = r["Tw"]
-    cos = oracle.lr_cosine(T, Tw, r["eta_max"], r["eta_min"])
     if r["sched"] == "cosine":
-        return cos, Tw
-    t = np.arange(T, dtype=np.float64)
+        return oracle.lr_cosine(T, Tw, r["eta_max"], r["eta_min"]), Tw
     if r["sched"] == "linear":
-        eta = np.where(t < Tw, r["eta_max"] * t / Tw, r["eta_max"] * (T - t) / (T - Tw))
-        return eta, Tw
+        return oracle.lr_linear(T, Tw, r["eta_max"], r["eta_min"]), Tw
     if r["sched"] == "pow2cos":
-        eta = cos.copy()
-        pos = cos > 0
-        eta[pos] = 2.0 ** np.round(np.log2(cos[pos]))
-        return eta, Tw
+        return oracle.lr_pow2cos(T, Tw, r["eta_max"], r["eta_min"]), Tw
     if r["sched"] == "smith":
-        ep = t / spe
-        halvings = np.where(ep < 150, 0, np.floor((ep - 150) / 30) + 1)
-        eta = r["eta_max"] / 2.0 ** halvings
-        eta = np.where(t < Tw, r["eta_max"] * t / Tw, eta)
-        return eta, Tw
+        # App. F: the peak until epoch 150 of 300, then halved every 30 epochs
+        ms = [e * spe for e in (150, 180, 210, 240, 270)]
+        return oracle.lr_step(T, Tw, r["eta_max"], ms, 2.0), Tw
     raise ValueError(r["sched"])
 
 
@@ -120,6 +111,20 @@ def test_cosine_closed_form_points():
     assert eta[-1] > 0.01 and eta[-1] == pytest.approx(
         0.01 + 0.245 * (1 + math.cos(math.pi * 899 / 900)), rel=1e-12)
     assert np.all(np.diff(eta[Tw:]) < 0)
+
+
+def test_linear_and_pow2cos_closed_form_points():
+    eta = oracle.lr_linear(1000, 100, 0.5, 0.1)
+    assert eta[0] == 0.0 and eta[100] == 0.5
+    assert eta[550] == pytest.approx(0.3, rel=1e-15) and eta[999] == pytest.approx(0.1 + 0.4 / 900, rel=1e-12)
+    cos = oracle.lr_cosine(1000, 100, 0.5, 0.0)
+    p2 = oracle.lr_pow2cos(1000, 100, 0.5, 0.0)
+    assert np.array_equal(p2[:100], cos[:100])                    # warm-up untouched
+    assert p2[100] == 0.5 and p2[550] == 0.25                     # cos: 0.5, 0.25
+    lg = np.log2(p2[100:])
+    assert np.all(lg == np.round(lg))                             # exact powers of two
+    assert np.all(np.abs(np.log2(cos[100:]) - lg) <= 0.5 + 1e-12)  # nearest in log scale
+    assert np.all(np.diff(p2[100:]) <= 0)
 
 
 def test_step_schedule_values():

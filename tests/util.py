@@ -11,6 +11,10 @@ def eta_of(w):
         return oracle.lr_cosine(w["T"], w.get("T_warm", 0), w["eta_max"], w.get("eta_min", 0.0))
     if w["lr"] == "step":
         return oracle.lr_step(w["T"], w.get("T_warm", 0), w["eta_max"], list(w["milestones"]), w["factor"])
+    if w["lr"] == "linear":
+        return oracle.lr_linear(w["T"], w.get("T_warm", 0), w["eta_max"], w.get("eta_min", 0.0))
+    if w["lr"] == "pow2cos":
+        return oracle.lr_pow2cos(w["T"], w.get("T_warm", 0), w["eta_max"], w.get("eta_min", 0.0))
     raise ValueError(w["lr"])
 
 
@@ -28,7 +32,7 @@ def oracle_run(w, p_idx=None, n_threads=8, theta0=None, eta=None):
                       d_out=w.get("d_out", 0), n_blocks=w.get("n_blocks", 0),
                       model_const=workloads.model_const(w), p_idx=p_idx, theta0=th0,
                       n_threads=n_threads, power=w.get("power", 2), parallel=w.get("parallel", False),
-                      t_local_start=w.get("t_local_start", 0))
+                      t_local_start=w.get("t_local_start", 0), average_state=w.get("average_state", False))
 
 
 def gpu_ctx(w, theta0=None, eta_table=None):
