@@ -84,6 +84,9 @@ typedef struct {
     int64_t T_warm;       /* linear warm-up 0 -> eta_max over the first T_warm iterations  */
     int64_t t_local_start;/* post-local schedule (Sec. 1): rounds that start before this
                              iteration use H = 1; 0 = off                                  */
+    int64_t t_swap_start; /* Local OPT + SWAP (App. G): a round that starts at or after this
+                             iteration runs to the end of training, with one final averaging;
+                             0 = off                                                        */
     int64_t B_loc;        /* local batch: samples (RESMLP: tokens) per worker per step     */
     int64_t d_in, d_hidden, d_out;
     double momentum;      /* SGD heavy-ball coefficient                                    */

@@ -137,9 +137,12 @@ int64_t qsro_get_H(const double *eta, int64_t T, int64_t T_warm, int64_t t,
 
 /* The rule of a configured run: power rule (gamma = 0: constant H_base), preceded by the
  * post-local phase of Lin et al. (Sec. 1, Sec. 4 "Comparison with other synchronization
- * strategies"): H = 1 for rounds that start before t_local_start. */
+ * strategies"): H = 1 for rounds that start before t_local_start; and followed, if asked, by
+ * the modified SWAP phase of App. G: from t_swap_start on, local steps only and one final
+ * averaging. */
 static int64_t run_get_H(const qsro_config *c, const double *eta, int64_t t)
 {
+    if (c->t_swap_start > 0 && t >= c->t_swap_start) return c->T - t;
     if (t < c->t_local_start) return 1;
     if (c->power == 0) {
         int64_t rem = c->T - t;

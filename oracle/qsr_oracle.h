@@ -23,6 +23,8 @@ typedef struct {
     int64_t T, T_warm;
     int64_t t_local_start;/* post-local schedule: rounds that start before this
                              iteration have H = 1; 0 = off                     */
+    int64_t t_swap_start; /* Local OPT + SWAP (App. G): a round that starts at or
+                             after this iteration lasts until T; 0 = off        */
     int64_t B_loc;        /* samples (model 4: tokens) per worker per step    */
     int64_t d_in, d_hidden, d_out;
     double mu, beta1, beta2, eps, lambda;

@@ -85,9 +85,10 @@ extern "C" int qsr_validate(const qsr_config *c, const char **why)
     else if (c->average_state != 0 && c->average_state != 1) w = "average_state";
     else if (c->power < 0 || c->power > 8) w = "power";
     else if (c->parallel != 0 && c->parallel != 1) w = "parallel";
-    else if (c->parallel == 1 && (c->H_base != 1 || c->power != 0 || c->t_local_start != 0))
+    else if (c->parallel == 1 && (c->H_base != 1 || c->power != 0 || c->t_local_start != 0 || c->t_swap_start != 0))
         w = "parallel needs H_base = 1, power = 0";
     else if (c->t_local_start < 0 || c->t_local_start > c->T) w = "t_local_start";
+    else if (c->t_swap_start < 0 || c->t_swap_start > c->T) w = "t_swap_start";
     else if (!finite_ge0(c->alpha)) w = "alpha";
     else if (!finite_ge0(c->weight_decay)) w = "weight_decay";
     else if (c->opt == QSR_OPT_SGDM && !(finite_ge0(c->momentum) && c->momentum < 1.0)) w = "momentum";
@@ -265,6 +266,7 @@ static int init_impl(qsr_ctx *c, const float *theta0)
 
     c->sp.T = cfg.T; c->sp.T_warm = cfg.T_warm; c->sp.H_base = cfg.H_base; c->sp.alpha = cfg.alpha;
     c->sp.power = cfg.power; c->sp.t_local_start = cfg.t_local_start;
+    c->sp.t_swap_start = cfg.t_swap_start;
     c->sp.eta = c->d_eta; c->sp.log_t = c->d_log_t; c->sp.log_H = c->d_log_H;
 
     const long long n = (long long)cfg.K * cfg.P;

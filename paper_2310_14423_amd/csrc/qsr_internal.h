@@ -29,6 +29,7 @@ struct SchedParams {
     long long T, T_warm;
     long long H_base;
     long long t_local_start; // post-local phase: H = 1 for rounds starting before it
+    long long t_swap_start;  // SWAP phase: a round starting at or after it runs to T; 0 = off
     int power;               // exponent of the rule; 0 = constant H_base
     double alpha;
     const double *eta;      // [T] device

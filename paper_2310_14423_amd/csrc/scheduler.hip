@@ -14,12 +14,14 @@ namespace qsr {
 // operations), so that the integer result is reproducible bit for bit.  The same routine
 // serves the schedules the paper compares with: a general integer power gamma (1: H ~ 1/eta,
 // 3: the cubic rule of App. F) by repeated multiplication, constant H (gamma = 0), and the
-// post-local schedule (H = 1 for rounds that start before a switching iteration).
+// post-local schedule (H = 1 for rounds that start before a switching iteration) and the
+// modified SWAP schedule of App. G (one last round from a switching iteration to T).
 #pragma clang fp contract(off)
 __device__ long long get_H(const SchedParams &sp, long long t)
 {
     long long rem = sp.T - t;
     if (rem <= 0) return 0;
+    if (sp.t_swap_start > 0 && t >= sp.t_swap_start) return rem;
     if (t < sp.t_local_start) return 1;
     if (sp.power == 0) return sp.H_base < rem ? sp.H_base : rem;
     long long te = t < sp.T_warm ? sp.T_warm : t;

@@ -44,7 +44,7 @@ def test_named_workloads_validate(name):
     ("eta_min", 1.0, "eta_min"), ("beta2", 1.0, "beta1/beta2"), ("eps", 0.0, "eps"),
     ("weight_decay", -1.0, "weight_decay"), ("grad_sigma", -1.0, "grad_sigma"), ("average_state", 2, "average_state"),
     ("power", -1, "power"), ("power", 9, "power"), ("parallel", 2, "parallel"),
-    ("parallel", 1, "parallel needs H_base = 1, power = 0"), ("t_local_start", -5, "t_local_start"),
+    ("parallel", 1, "parallel needs H_base = 1, power = 0"), ("t_local_start", -5, "t_local_start"), ("t_swap_start", 9999, "t_swap_start"),
 ])
 def test_bad_configurations_are_rejected(field, value, why):
     cfg, keep = make_config(workloads.get("flat60m"))

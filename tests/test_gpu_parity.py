@@ -354,10 +354,11 @@ def test_resmlp_short_run():
 
 @pytest.mark.parametrize("kw", [dict(power=3, alpha=0.012, H_base=4), dict(power=1, alpha=0.03, H_base=4),
                                 dict(power=0, H_base=7), dict(power=0, H_base=8, t_local_start=700),
-                                dict(power=2, alpha=0.0175, H_base=4, t_local_start=300)])
+                                dict(power=2, alpha=0.0175, H_base=4, t_local_start=300),
+                                dict(power=0, H_base=4, t_swap_start=1500)])
 def test_other_synchronization_schedules_are_bit_exact(kw):
     """The schedules the paper compares QSR with (H ~ 1/eta, the cubic rule, constant H,
-    post-local): integer sequences against the oracle for a whole run."""
+    post-local, Local OPT + SWAP): integer sequences against the oracle for a whole run."""
     w = dict(workloads.get("flat60m"), P=8, K=2, T=2000, eta_max=0.008, **kw)
     ctx = gpu_ctx(w, theta0=np.zeros(8, np.float32))
     orc = oracle_run(w, theta0=np.zeros(8, np.float32))

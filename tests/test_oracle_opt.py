@@ -234,6 +234,10 @@ def test_post_local_and_constant_and_power_schedules():
     r = oracle.Run(K=1, n=1, eta=eta, H_base=8, alpha=0.0, power=0, t_local_start=20)
     r.step(T, ext_g=g)
     assert list(r.H_log) == [1] * 20 + [8] * 5
+    # Local OPT + SWAP (App. G): constant 4 until t = 30, then local steps only and one last averaging
+    r = oracle.Run(K=1, n=1, eta=eta, H_base=4, alpha=0.0, power=0, t_swap_start=30)
+    r.step(T, ext_g=g)
+    assert list(r.H_log) == [4] * 8 + [28] and list(r.sync_log)[-2:] == [32, 60]
     # H ~ 1/eta and the cubic rule follow the power form of Eq. (2)
     for gamma, coef in ((1, 0.9), (3, 0.12)):
         r = oracle.Run(K=1, n=1, eta=eta, H_base=2, alpha=coef, power=gamma)
