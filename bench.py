@@ -43,7 +43,7 @@ def measured_traffic(workload):
     return ent["bytes"] if h == ent["sha256_16"] else None
 
 
-def cpu_baseline(w, seconds_target=15.0):
+def cpu_baseline(w, cpu_seconds_target=20.0):
     """The CPU oracle, as it stands, on a bounded sample of the same workload."""
     import numpy as np
     import oracle
@@ -64,7 +64,8 @@ def cpu_baseline(w, seconds_target=15.0):
         return time.perf_counter() - t0
 
     t1 = run(2)
-    steps = int(max(2, min(200, seconds_target / max(t1 / 2, 1e-3))))
+    # about 20 s of CPU work in total: wall time per step times the threads it keeps busy
+    steps = int(max(2, min(200, cpu_seconds_target / max(t1 / 2 * threads, 1e-3))))
     dt = run(steps)
     return {"value": w["K"] * P * steps / dt, "unit": "replica-param updates/s", "cores": threads,
             "kind": "oracle",
