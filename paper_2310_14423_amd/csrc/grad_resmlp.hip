@@ -379,8 +379,8 @@ struct EpiScaleF32 {             // C = scale * acc
     __device__ Aux pre(int, int, int) const { return Aux{}; }
     __device__ void operator()(int z, int m, int n, const float (&v)[4], const Aux &) const
     {
-        *(float4 *)(C + (long long)z * sC + (long long)m * ldc + n) =
-            make_float4(v[0] * scale, v[1] * scale, v[2] * scale, v[3] * scale);
+        st_nt4((float4 *)(C + (long long)z * sC + (long long)m * ldc + n),
+               make_float4(v[0] * scale, v[1] * scale, v[2] * scale, v[3] * scale));
     }
 };
 struct EpiBiasGelu {             // h = acc + b1; H = bf16(h); A = bf16(gelu(h))
@@ -395,8 +395,8 @@ struct EpiBiasGelu {             // h = acc + b1; H = bf16(h); A = bf16(gelu(h))
 #pragma unroll
         for (int i = 0; i < 4; ++i) { float c, pdf; gelu_parts(h[i], c, pdf); a[i] = h[i] * c; }
         const long long o = (long long)m * ld + n;
-        *(bf16x4 *)(H + (long long)z * sH + o) = pack4(h[0], h[1], h[2], h[3]);
-        *(bf16x4 *)(A + (long long)z * sA + o) = pack4(a[0], a[1], a[2], a[3]);
+        __builtin_nontemporal_store(pack4(h[0], h[1], h[2], h[3]), (bf16x4 *)(H + (long long)z * sH + o));
+        __builtin_nontemporal_store(pack4(a[0], a[1], a[2], a[3]), (bf16x4 *)(A + (long long)z * sA + o));
     }
 };
 struct EpiBiasResidual {         // x_out = x_in + acc + b2
@@ -410,7 +410,7 @@ struct EpiBiasResidual {         // x_out = x_in + acc + b2
     {
         const long long o = (long long)z * sX + (long long)m * ld + n;
         const float4 b = *(const float4 *)(bias + (long long)z * sBias + n);
-        *(float4 *)(Xout + o) = make_float4(x.x + v[0] + b.x, x.y + v[1] + b.y, x.z + v[2] + b.z, x.w + v[3] + b.w);
+        st_nt4((float4 *)(Xout + o), make_float4(x.x + v[0] + b.x, x.y + v[1] + b.y, x.z + v[2] + b.z, x.w + v[3] + b.w));
     }
 };
 struct EpiGeluBwd {              // dh = acc * gelu'(h)
@@ -430,7 +430,7 @@ struct EpiGeluBwd {              // dh = acc * gelu'(h)
             gelu_parts(h, c, pdf);
             r[i] = v[i] * fmaf(h, pdf, c);
         }
-        *(bf16x4 *)(DH + (long long)z * sDH + (long long)m * ld + n) = pack4(r[0], r[1], r[2], r[3]);
+        __builtin_nontemporal_store(pack4(r[0], r[1], r[2], r[3]), (bf16x4 *)(DH + (long long)z * sDH + (long long)m * ld + n));
     }
 };
 
