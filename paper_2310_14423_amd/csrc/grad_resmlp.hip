@@ -14,6 +14,7 @@
 // they are ("TN" form, LDS transpose reads), so no transposed activation copies exist.
 // Per-block parameter packing: gamma[d], beta[d], W1[d][dh], b1[dh], W2[dh][d], b2[d].
 #include "gemm_bf16.h"
+#include "gemm_pp.h"
 #include "qsr_internal.h"
 
 namespace qsr {
@@ -444,6 +445,18 @@ struct EpiGeluBwd {              // dh = acc * gelu'(h)
 #define QSR_GEMM_BIG 256, 256, 64, 2, 4
 #define QSR_GEMM_WGRAD 128, 128, 64, 2, 2
 
+// the persistent two-group kernels where the problem allows them, else the plain tiled ones
+template <class Epi>
+static hipError_t gemm_nt(const GemmNT &p, const Epi &epi, int batch, hipStream_t s)
+{
+    return launch_gemm_nt<QSR_GEMM_BIG>(p, epi, batch, s);
+}
+template <class Epi>
+static hipError_t gemm_tn(const GemmNT &p, const Epi &epi, int batch, hipStream_t s)
+{
+    return launch_gemm_tn<QSR_GEMM_WGRAD>(p, epi, batch, s);
+}
+
 #define TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return e_; } while (0)
 
 hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g, const float *teacher,
@@ -474,7 +487,7 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
     {
         GemmNT p{w.U, w.WTt, M, d, d, d, d, w.sU, 0};
         EpiScaleF32 epi{w.Y, d, w.sY, 1.0f / sqrtf((float)d)};
-        TRY((launch_gemm_nt<QSR_GEMM_BIG>(p, epi, K, s)));
+        TRY(gemm_nt(p, epi, K, s));
     }
 
     // forward
@@ -497,12 +510,12 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
         {
             GemmNT p{Ul, w.W1Tb + ow, M, dh, d, d, d, w.sU, w.sW};
             EpiBiasGelu epi{theta + ob1, P, w.H + (long long)l * Mdh, w.sH, Al, w.sA, dh};
-            TRY((launch_gemm_nt<QSR_GEMM_BIG>(p, epi, K, s)));
+            TRY(gemm_nt(p, epi, K, s));
         }
         {
             GemmNT p{Al, w.W2Tb + ow, M, d, dh, dh, dh, w.sA, w.sW};
             EpiBiasResidual epi{theta + ob2, P, Xl, Xn, w.sX, d};
-            TRY((launch_gemm_nt<QSR_GEMM_BIG>(p, epi, K, s)));
+            TRY(gemm_nt(p, epi, K, s));
         }
     }
 
@@ -529,25 +542,25 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
         {
             GemmNT p{w.A + (long long)l * Mdh, w.DXb, dh, d, M, dh, d, w.sA, w.sDXb, g + ob2, P};
             EpiScaleF32 epi{g + oW2, d, P, 1.0f};
-            TRY((launch_gemm_tn<QSR_GEMM_WGRAD>(p, epi, K, s)));
+            TRY(gemm_tn(p, epi, K, s));
         }
         // dh = (dx W2^T) * gelu'(h)
         {
             GemmNT p{w.DXb, w.W2b + ow, M, dh, d, d, d, w.sDXb, w.sW};
             EpiGeluBwd epi{w.H + (long long)l * Mdh, w.sH, w.DH, w.sDH, dh};
-            TRY((launch_gemm_nt<QSR_GEMM_BIG>(p, epi, K, s)));
+            TRY(gemm_nt(p, epi, K, s));
         }
         // W1 and b1:  dW1 = u^T dh, db1 = column sums of dh
         {
             GemmNT p{w.U + (long long)l * Md, w.DH, d, dh, M, d, dh, w.sU, w.sDH, g + ob1, P};
             EpiScaleF32 epi{g + oW1, dh, P, 1.0f};
-            TRY((launch_gemm_tn<QSR_GEMM_WGRAD>(p, epi, K, s)));
+            TRY(gemm_tn(p, epi, K, s));
         }
         // du = dh W1^T, then LayerNorm backward + residual: dx_l
         {
             GemmNT p{w.DH, w.W1b + ow, M, d, dh, dh, dh, w.sDH, w.sW};
             EpiScaleF32 epi{w.DU, d, w.sDU, 1.0f};
-            TRY((launch_gemm_nt<QSR_GEMM_BIG>(p, epi, K, s)));
+            TRY(gemm_nt(p, epi, K, s));
         }
         {
             dim3 grid((unsigned)((wave_rows + 3) / 4), (unsigned)K);
