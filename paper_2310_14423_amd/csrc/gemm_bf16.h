@@ -42,6 +42,7 @@ struct GemmNT {
     long long sA, sB;      // per-batch strides (elements)
     float *colsum_B;       // TN form only, optional: colsum_B[z*s_colsum + n] = sum_k B[z][k][n]
     long long s_colsum;
+    const bf16_t *zeros;   // TN form of gemm_pp.h only: 64 bytes of zeros, read in place of k-rows beyond K
 };
 
 // Epilogue.  The MFMA leaves lane l with 4 consecutive columns of row l%32, i.e. one store

@@ -32,9 +32,10 @@
 // treats every LDS access of the epilogue as possibly aliasing the copies in flight and waits
 // for all outstanding vector memory operations (its own stores included) before each of them.
 //
-// K must be a multiple of 32 and at least 32; lda/ldb multiples of 8 elements; N a multiple of 4.
-// M and N may be ragged (NT: rows clamped on load, TN: K must not be ragged), the epilogue is
-// bounds-checked.
+// lda/ldb must be multiples of 8 elements and N a multiple of 4.  M and N may be ragged (operand
+// rows or columns clamped on load, the epilogue is bounds-checked).  NT: K a multiple of 32.
+// TN: M and N multiples of 8; K may be ragged if GemmNT::zeros is given (k-rows beyond K are read
+// from there).
 #pragma once
 #include <type_traits>
 
@@ -118,7 +119,7 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(GemmNT p, Epi epi, int Z)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;       // wm is also the ping-pong group
     const int nx = (p.N + BN - 1) / BN, ny = (p.M + BM - 1) / BM;
-    const int nk = p.K / BK;
+    const int nk = (p.K + BK - 1) / BK;            // TN: a ragged last slab is filled up with zero rows
     const int per_z = nx * ny, T = Z * per_z, Tc = (T + 7) / 8;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, slots = gridDim.x >> 3;
     const int c0 = xcd * Tc, c1 = min(T, c0 + Tc);
@@ -144,7 +145,8 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(GemmNT p, Epi epi, int Z)
     //     [column block][32 k][32 features], which the transpose reads take without conflicts.
     const unsigned lds_ring = (unsigned)(uintptr_t)(__attribute__((address_space(3))) void *)gemm_smem;
     const bf16_t *src[CPW];
-    long long src_step[CPW];                        // elements per slab
+    // elements per slab (uniform over the wavefront: a chunk index decides A or B)
+    const long long stepA = TNMODE ? (long long)BK * p.lda : BK, stepB = TNMODE ? (long long)BK * p.ldb : BK;
     auto set_src = [&](int i) {
         int z, m0, n0;
         decode(i, z, m0, n0);
@@ -160,28 +162,33 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(GemmNT p, Epi epi, int Z)
                 const int piece = (lane & 3) ^ ((row >> 2) & 3);
                 src[c] = isA ? A + (long long)min(m0 + row, p.M - 1) * p.lda + piece * 8
                              : B + (long long)min(n0 + row, p.N - 1) * p.ldb + piece * 8;
-                src_step[c] = BK;
             } else {
                 const int fblk = cc >> 1, t = (cc & 1) * 16 + (lane >> 2);   // column block, k-row inside the slab
                 const int f = fblk * 32 + (lane & 3) * 8;
                 src[c] = isA ? A + (long long)t * p.lda + min(m0 + f, p.M - 8)
                              : B + (long long)t * p.ldb + min(n0 + f, p.N - 8);
-                src_step[c] = (long long)BK * (isA ? p.lda : p.ldb);
             }
         }
     };
     int d_stage = 0;                                // stage the next copy goes to
+    int d_row = 0;                                  // TN: first k-row of the next slab to copy
     auto issue_slab = [&]() {                       // copies this wavefront's chunks of the next slab
 #pragma unroll
         for (int c = 0; c < CPW; ++c) {
             const int chunk = c * 8 + wave;
             if (CHUNKS % 8 == 0 || chunk < CHUNKS) {
                 const unsigned dst = __builtin_amdgcn_readfirstlane(lds_ring + d_stage * STAGE_BYTES + chunk * 1024);
-                asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" :: "s"(dst), "v"(src[c]) : "memory", "m0");
-                src[c] += src_step[c];
+                const bf16_t *g = src[c];
+                if (TNMODE) {
+                    const int cc = chunk < A_CHUNKS ? chunk : chunk - A_CHUNKS;
+                    if (d_row + (cc & 1) * 16 + (lane >> 2) >= p.K) g = p.zeros + (lane & 3) * 8;
+                }
+                asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" :: "s"(dst), "v"(g) : "memory", "m0");
+                src[c] += __builtin_amdgcn_readfirstlane(chunk) < A_CHUNKS ? stepA : stepB;
             }
         }
         d_stage = d_stage + 1 == NS ? 0 : d_stage + 1;
+        d_row += BK;
     };
     // wavefronts whose last chunk index lies beyond the slab issue one copy less per slab
     const bool short_wave = CHUNKS % 8 != 0 && (CPW - 1) * 8 + wave >= CHUNKS;
@@ -268,6 +275,7 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(GemmNT p, Epi epi, int Z)
     auto prime = [&](int tile) {
         set_src(tile);
         d_stage = 0;
+        d_row = 0;
 #pragma unroll
         for (int s = 0; s < NS - 1; ++s)
             if (s < S) issue_next();
@@ -277,7 +285,10 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(GemmNT p, Epi epi, int Z)
     };
 
     float *stage16 = stage_lds + wave * (16 * 64);
-    float csum0 = 0.f, csum1 = 0.f;                 // TN: column sums of B, thread = one column pair
+    // TN: column sums of B.  Half-wavefront = one 32-column block of the tile, lane = (k-row mod 4,
+    // column quad): 8 reads of 8 bytes cover the 32 k-rows of a slab.
+    float csum[4] = {0.f, 0.f, 0.f, 0.f};
+    const int cs_blk = wave * 2 + (lane >> 5), cs_kq = (lane >> 3) & 3, cs_quad = lane & 7;
     int c_stage = 0;
     if (CONT) prime(0);
     for (int ti = 0, q = 0; ti < n_my; ++ti) {
@@ -285,19 +296,27 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(GemmNT p, Epi epi, int Z)
         decode(ti, cz, cm0, cn0);
         if (!CONT) { prime(ti); c_stage = 0; q = 0; }
         zero_acc();
-        const bool do_colsum = TNMODE && p.colsum_B != nullptr && cm0 == 0 && tid < BN / 2;
+        const bool colsum_wg = TNMODE && p.colsum_B != nullptr && cm0 == 0;
+        const bool do_colsum = colsum_wg && cs_blk < BN / 32;
         for (int k = 0; k < nk; ++k, ++q) {
             load_frags(c_stage);
             if (do_colsum) {
                 // the workgroups of the first M-tile add up the k-rows of their B slabs as they pass
                 // through LDS (fixed order): the bias gradient that goes with the weight gradient
                 const bf16_t *sb = (const bf16_t *)(gemm_smem + c_stage * STAGE_BYTES) + BM * BK;
-                const bf16_t *colp = sb + (tid >> 4) * (32 * 32) + (tid & 15) * 2;
+                const bf16_t *colp = sb + cs_blk * (32 * 32) + cs_kq * 32 + cs_quad * 4;
 #pragma unroll
-                for (int t = 0; t < BK; ++t) {
-                    const uint32_t two = *(const uint32_t *)(colp + t * 32);
-                    csum0 += __uint_as_float(two << 16);            // bf16 -> fp32 is a 16-bit shift
-                    csum1 += __uint_as_float(two & 0xffff0000u);
+                for (int b = 0; b < 2; ++b) {                       // two batches: registers are scarce here
+                    uint2 four[4];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) four[t] = *(const uint2 *)(colp + (b * 4 + t) * (4 * 32));
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {                   // bf16 -> fp32 is a 16-bit shift
+                        csum[0] += __uint_as_float(four[t].x << 16);
+                        csum[1] += __uint_as_float(four[t].x & 0xffff0000u);
+                        csum[2] += __uint_as_float(four[t].y << 16);
+                        csum[3] += __uint_as_float(four[t].y & 0xffff0000u);
+                    }
                 }
             }
             c_stage = c_stage + 1 == NS ? 0 : c_stage + 1;
@@ -313,22 +332,26 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(GemmNT p, Epi epi, int Z)
             __builtin_amdgcn_s_setprio(0);
             barrier();
         }
-        if (CONT) {
+        if constexpr (CONT) {
             epilogue_via_lds16<TM>(acc, stage16, lane, cm0 + wm * (BM / 2), cn0 + wn * (BN / WN), p.M, p.N, cz, epi);
             __builtin_amdgcn_s_waitcnt(0x0f70);    // vmcnt(0): stores drained, only copies are counted from here on
         } else {
             if (wm == 0) barrier();                // both groups are through with the ring
+            constexpr int EPI_FLOATS = 8 * 32 * (TN * 32 + 4);
+            static_assert((EPI_FLOATS + (BN / 32) * 4 * 32) * 4 <= NS * STAGE_BYTES, "staging inside the ring");
+            float *cs_part = (float *)gemm_smem + EPI_FLOATS;       // [column block][k-row mod 4][32]
+            if (do_colsum)
+                *(float4 *)(cs_part + (cs_blk * 4 + cs_kq) * 32 + cs_quad * 4) = make_float4(csum[0], csum[1], csum[2], csum[3]);
+            csum[0] = csum[1] = csum[2] = csum[3] = 0.f;
             epilogue_via_lds<TM, TN>(acc, (float *)gemm_smem + wave * (32 * (TN * 32 + 4)), lane,
                                      cm0 + wm * (BM / 2), cn0 + wn * (BN / WN), p.M, p.N, cz, epi);
-            if (do_colsum) {
-                const int n = cn0 + 2 * tid;
-                float *o = p.colsum_B + (long long)cz * p.s_colsum;
-                if (n < p.N) o[n] = csum0;
-                if (n + 1 < p.N) o[n + 1] = csum1;
-            }
-            csum0 = csum1 = 0.f;
             __builtin_amdgcn_s_waitcnt(0x0070);    // vmcnt(0), lgkmcnt(0)
-            barrier();                             // every epilogue is out of the ring before it is primed again
+            barrier();                             // epilogues and partial column sums are written
+            if (colsum_wg && tid < BN && cn0 + tid < p.N) {
+                const float *q = cs_part + (tid >> 5) * (4 * 32) + (tid & 31);
+                p.colsum_B[(long long)cz * p.s_colsum + cn0 + tid] = (q[0] + q[32]) + (q[64] + q[96]);
+            }
+            barrier();                             // the ring is free to be primed again
         }
     }
     if (CONT && wm == 0) barrier();
@@ -337,9 +360,10 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(GemmNT p, Epi epi, int Z)
 // Whether launch_gemm_pp can take the problem (otherwise the kernels of gemm_bf16.h do).
 inline bool gemm_pp_supports(const GemmNT &p, bool tn)
 {
-    if (p.K < 32 || p.K % 32 != 0 || p.lda % 8 != 0 || p.ldb % 8 != 0 || p.N % 4 != 0) return false;
-    if (tn && (p.M % 8 != 0 || p.N % 8 != 0 || p.M < 8 || p.N < 8)) return false;
-    return true;
+    if (p.K < 1 || p.lda % 8 != 0 || p.ldb % 8 != 0 || p.N % 4 != 0) return false;
+    if (!tn) return p.K % 32 == 0;
+    if (p.M % 8 != 0 || p.N % 8 != 0 || p.M < 8 || p.N < 8) return false;
+    return p.K % 32 == 0 || p.zeros != nullptr;
 }
 
 // compute units of the current device (one persistent workgroup each)

@@ -40,6 +40,7 @@ struct ResWs {
     bf16_t *WTt;                       // [d][d], shared: teacher map transposed
     float *PART;   long long sPART;    // [2][wave_rows][d] partial dgamma, dbeta
     float *LPART;  long long sLPART;   // loss partials
+    bf16_t *ZERO;                      // 256 bytes of zeros (stand-in rows of ragged GEMM slabs)
 };
 
 static ResWs carve(const ModelDims &dm, void *ws, size_t *total)
@@ -70,6 +71,7 @@ static ResWs carve(const ModelDims &dm, void *ws, size_t *total)
     const long long wave_rows = (M + LN_ROWS_PER_WAVE - 1) / LN_ROWS_PER_WAVE;
     w.sPART = 2 * wave_rows * d; w.PART = (float *)take(w.sPART, 4, K);
     w.sLPART = (M * d + 1023) / 1024; w.LPART = (float *)take(w.sLPART, 4, K);
+    w.ZERO = (bf16_t *)take(128, 2, 1);
     if (total) *total = off;
     return w;
 }
@@ -454,6 +456,7 @@ static hipError_t gemm_nt(const GemmNT &p, const Epi &epi, int batch, hipStream_
 template <class Epi>
 static hipError_t gemm_tn(const GemmNT &p, const Epi &epi, int batch, hipStream_t s)
 {
+    if (gemm_pp_supports(p, true)) return launch_gemm_pp<true>(p, epi, batch, s);
     return launch_gemm_tn<QSR_GEMM_WGRAD>(p, epi, batch, s);
 }
 
@@ -468,6 +471,7 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
     ResWs w = carve(dm, ws, nullptr);
     const long long Md = (long long)M * d, Mdh = (long long)M * dh;
 
+    TRY(launch_fill_zero((float *)w.ZERO, 64, s));
     // bf16 copies of the weights in both orientations (the master weights changed last step)
     for (int l = 0; l < L; ++l) {
         const long long oW1 = l * per_block + 2LL * d, oW2 = oW1 + (long long)d * dh + dh;
@@ -540,7 +544,7 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
         float *DXc = w.DX + (long long)cur * Md, *DXn = w.DX + (long long)(cur ^ 1) * Md;
         // W2 and b2:  dW2 = a^T dx, db2 = column sums of dx (by-product of the same GEMM)
         {
-            GemmNT p{w.A + (long long)l * Mdh, w.DXb, dh, d, M, dh, d, w.sA, w.sDXb, g + ob2, P};
+            GemmNT p{w.A + (long long)l * Mdh, w.DXb, dh, d, M, dh, d, w.sA, w.sDXb, g + ob2, P, w.ZERO};
             EpiScaleF32 epi{g + oW2, d, P, 1.0f};
             TRY(gemm_tn(p, epi, K, s));
         }
@@ -552,7 +556,7 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
         }
         // W1 and b1:  dW1 = u^T dh, db1 = column sums of dh
         {
-            GemmNT p{w.U + (long long)l * Md, w.DH, d, dh, M, d, dh, w.sU, w.sDH, g + ob1, P};
+            GemmNT p{w.U + (long long)l * Md, w.DH, d, dh, M, d, dh, w.sU, w.sDH, g + ob1, P, w.ZERO};
             EpiScaleF32 epi{g + oW1, dh, P, 1.0f};
             TRY(gemm_tn(p, epi, K, s));
         }
