@@ -285,10 +285,12 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(GemmNT p, Epi epi, int Z)
     };
 
     float *stage16 = stage_lds + wave * (16 * 64);
-    // TN: column sums of B.  Half-wavefront = one 32-column block of the tile, lane = (k-row mod 4,
-    // column quad): 8 reads of 8 bytes cover the 32 k-rows of a slab.
-    float csum[4] = {0.f, 0.f, 0.f, 0.f};
-    const int cs_blk = wave * 2 + (lane >> 5), cs_kq = (lane >> 3) & 3, cs_quad = lane & 7;
+    // TN: column sums of B, taken from the B fragments the first group already holds for its MFMAs:
+    // lane l of a fragment has 8 consecutive k of column l % 32, which one dot product with ones
+    // per register pair adds up (v_dot2c_f32_bf16), in the shadow of the multiply phase.
+    float csum[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) csum[j] = 0.f;
     int c_stage = 0;
     if (CONT) prime(0);
     for (int ti = 0, q = 0; ti < n_my; ++ti) {
@@ -297,28 +299,9 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(GemmNT p, Epi epi, int Z)
         if (!CONT) { prime(ti); c_stage = 0; q = 0; }
         zero_acc();
         const bool colsum_wg = TNMODE && p.colsum_B != nullptr && cm0 == 0;
-        const bool do_colsum = colsum_wg && cs_blk < BN / 32;
+        const bool do_colsum = colsum_wg && wm == 0;
         for (int k = 0; k < nk; ++k, ++q) {
             load_frags(c_stage);
-            if (do_colsum) {
-                // the workgroups of the first M-tile add up the k-rows of their B slabs as they pass
-                // through LDS (fixed order): the bias gradient that goes with the weight gradient
-                const bf16_t *sb = (const bf16_t *)(gemm_smem + c_stage * STAGE_BYTES) + BM * BK;
-                const bf16_t *colp = sb + cs_blk * (32 * 32) + cs_kq * 32 + cs_quad * 4;
-#pragma unroll
-                for (int b = 0; b < 2; ++b) {                       // two batches: registers are scarce here
-                    uint2 four[4];
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) four[t] = *(const uint2 *)(colp + (b * 4 + t) * (4 * 32));
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) {                   // bf16 -> fp32 is a 16-bit shift
-                        csum[0] += __uint_as_float(four[t].x << 16);
-                        csum[1] += __uint_as_float(four[t].x & 0xffff0000u);
-                        csum[2] += __uint_as_float(four[t].y << 16);
-                        csum[3] += __uint_as_float(four[t].y & 0xffff0000u);
-                    }
-                }
-            }
             c_stage = c_stage + 1 == NS ? 0 : c_stage + 1;
             if (q + NS - 1 < S) {
                 issue_next();
@@ -329,6 +312,21 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(GemmNT p, Epi epi, int Z)
             barrier();
             __builtin_amdgcn_s_setprio(1);
             mfmas();
+            if (do_colsum) {
+                // the workgroups of the first M-tile add up the k-rows of their B slabs (fixed
+                // order): the bias gradient that goes with the weight gradient
+                typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+                const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const bf16x2 two = {fb[ks][j][2 * e], fb[ks][j][2 * e + 1]};
+                            csum[j] = __builtin_amdgcn_fdot2_f32_bf16(two, ones, csum[j], false);
+                        }
+            }
             __builtin_amdgcn_s_setprio(0);
             barrier();
         }
@@ -338,19 +336,20 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(GemmNT p, Epi epi, int Z)
         } else {
             if (wm == 0) barrier();                // both groups are through with the ring
             constexpr int EPI_FLOATS = 8 * 32 * (TN * 32 + 4);
-            static_assert((EPI_FLOATS + (BN / 32) * 4 * 32) * 4 <= NS * STAGE_BYTES, "staging inside the ring");
-            float *cs_part = (float *)gemm_smem + EPI_FLOATS;       // [column block][k-row mod 4][32]
-            if (do_colsum)
-                *(float4 *)(cs_part + (cs_blk * 4 + cs_kq) * 32 + cs_quad * 4) = make_float4(csum[0], csum[1], csum[2], csum[3]);
-            csum[0] = csum[1] = csum[2] = csum[3] = 0.f;
+            static_assert((EPI_FLOATS + 2 * BN) * 4 <= NS * STAGE_BYTES, "staging inside the ring");
+            float *cs_part = (float *)gemm_smem + EPI_FLOATS;       // [k half of the fragment][column]
+            if (do_colsum) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j) cs_part[(lane >> 5) * BN + wn * (BN / WN) + j * 32 + (lane & 31)] = csum[j];
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) csum[j] = 0.f;
             epilogue_via_lds<TM, TN>(acc, (float *)gemm_smem + wave * (32 * (TN * 32 + 4)), lane,
                                      cm0 + wm * (BM / 2), cn0 + wn * (BN / WN), p.M, p.N, cz, epi);
             __builtin_amdgcn_s_waitcnt(0x0070);    // vmcnt(0), lgkmcnt(0)
             barrier();                             // epilogues and partial column sums are written
-            if (colsum_wg && tid < BN && cn0 + tid < p.N) {
-                const float *q = cs_part + (tid >> 5) * (4 * 32) + (tid & 31);
-                p.colsum_B[(long long)cz * p.s_colsum + cn0 + tid] = (q[0] + q[32]) + (q[64] + q[96]);
-            }
+            if (colsum_wg && tid < BN && cn0 + tid < p.N)
+                p.colsum_B[(long long)cz * p.s_colsum + cn0 + tid] = cs_part[tid] + cs_part[BN + tid];
             barrier();                             // the ring is free to be primed again
         }
     }
@@ -381,7 +380,7 @@ inline int gemm_pp_cu_count()
 template <bool TNMODE, class Epi>
 inline hipError_t launch_gemm_pp(const GemmNT &p, const Epi &epi, int batch, hipStream_t s)
 {
-    constexpr int NS = 4;
+    constexpr int NS = TNMODE ? 3 : 4;        // TN: 3 stages timed 4-6 % faster than 4
     constexpr int BM = TNMODE ? 192 : 256, BN = TNMODE ? 384 : 256;
     constexpr size_t smem = (size_t)NS * (BM + BN) * 32 * 2;
     constexpr size_t stage = TNMODE ? 16 : (size_t)8 * 16 * 64 * 4;

@@ -49,28 +49,34 @@ static ResWs carve(const ModelDims &dm, void *ws, size_t *total)
     char *p = (char *)ws;
     size_t off = 0;
     ResWs w;
+    // Per-worker arrays are laid out [K][stride].  The natural strides of the benchmark size are
+    // exact multiples of 512 KiB, which puts the 8 workers' arrays in phase with every power-of-two
+    // interleaving of the memory channels: XCDs that sweep one worker each, at the same relative
+    // offsets and the same time, would all sit on the same channels.  8448 extra bytes per worker
+    // take them out of phase.
+    auto padded = [&](long long n, size_t elt) { return (long long)(up256((size_t)n * elt) + 8448) / (long long)elt; };
     auto take = [&](long long per_replica, size_t elt, long long copies) {
         void *r = p + off;
         off += up256((size_t)per_replica * elt * (size_t)copies);
         return r;
     };
-    w.sX = (L + 1) * M * d;   w.X = (float *)take(w.sX, 4, K);
-    w.sStat = L * M;          w.MU = (float *)take(w.sStat, 4, K); w.RSTD = (float *)take(w.sStat, 4, K);
-    w.sH = L * M * dh;        w.H = (bf16_t *)take(w.sH, 2, K);
-    w.sU = L * M * d;         w.U = (bf16_t *)take(w.sU, 2, K);
-    w.sA = L * M * dh;        w.A = (bf16_t *)take(w.sA, 2, K);
-    w.sY = M * d;             w.Y = (float *)take(w.sY, 4, K);
-    w.sDX = 2 * M * d;        w.DX = (float *)take(w.sDX, 4, K);
-    w.sDXb = M * d;           w.DXb = (bf16_t *)take(w.sDXb, 2, K);
-    w.sDH = M * dh;           w.DH = (bf16_t *)take(w.sDH, 2, K);
-    w.sDU = M * d;            w.DU = (float *)take(w.sDU, 4, K);
-    w.sW = L * d * dh;
+    w.sX = padded((L + 1) * M * d, 4);   w.X = (float *)take(w.sX, 4, K);
+    w.sStat = padded(L * M, 4);          w.MU = (float *)take(w.sStat, 4, K); w.RSTD = (float *)take(w.sStat, 4, K);
+    w.sH = padded(L * M * dh, 2);        w.H = (bf16_t *)take(w.sH, 2, K);
+    w.sU = padded(L * M * d, 2);         w.U = (bf16_t *)take(w.sU, 2, K);
+    w.sA = padded(L * M * dh, 2);        w.A = (bf16_t *)take(w.sA, 2, K);
+    w.sY = padded(M * d, 4);             w.Y = (float *)take(w.sY, 4, K);
+    w.sDX = padded(2 * M * d, 4);        w.DX = (float *)take(w.sDX, 4, K);
+    w.sDXb = padded(M * d, 2);           w.DXb = (bf16_t *)take(w.sDXb, 2, K);
+    w.sDH = padded(M * dh, 2);           w.DH = (bf16_t *)take(w.sDH, 2, K);
+    w.sDU = padded(M * d, 4);            w.DU = (float *)take(w.sDU, 4, K);
+    w.sW = padded(L * d * dh, 2);
     w.W1b = (bf16_t *)take(w.sW, 2, K);  w.W1Tb = (bf16_t *)take(w.sW, 2, K);
     w.W2b = (bf16_t *)take(w.sW, 2, K);  w.W2Tb = (bf16_t *)take(w.sW, 2, K);
     w.WTt = (bf16_t *)take(d * d, 2, 1);
     const long long wave_rows = (M + LN_ROWS_PER_WAVE - 1) / LN_ROWS_PER_WAVE;
-    w.sPART = 2 * wave_rows * d; w.PART = (float *)take(w.sPART, 4, K);
-    w.sLPART = (M * d + 1023) / 1024; w.LPART = (float *)take(w.sLPART, 4, K);
+    w.sPART = padded(2 * wave_rows * d, 4); w.PART = (float *)take(w.sPART, 4, K);
+    w.sLPART = padded((M * d + 1023) / 1024, 4); w.LPART = (float *)take(w.sLPART, 4, K);
     w.ZERO = (bf16_t *)take(128, 2, 1);
     if (total) *total = off;
     return w;
