@@ -393,6 +393,7 @@ inline hipError_t launch_gemm_nt(const GemmNT &p, const Epi &epi, int batch, hip
     dim3 grid((tiles + 7) / 8 * 8, 1, 1);
     constexpr size_t smem = 2 * (size_t)(BM + BN) * BK * sizeof(bf16_t);
     static_assert(smem <= 160 * 1024, "tile does not fit the 160 KB LDS");
+    static_assert((size_t)WM * WN * 32 * (BN / WN + 4) * sizeof(float) <= smem, "epilogue staging does not fit the slab buffers");
     auto kern = gemm_nt_bf16_kernel<BM, BN, BK, WM, WN, Epi>;
     static bool lds_limit_raised = false;     // per instantiation; contexts are not thread-safe
     if (smem > 64 * 1024 && !lds_limit_raised) {
@@ -410,6 +411,7 @@ inline hipError_t launch_gemm_tn(const GemmNT &p, const Epi &epi, int batch, hip
     dim3 grid((unsigned)((p.N + BN - 1) / BN), (unsigned)((p.M + BM - 1) / BM), (unsigned)batch);
     constexpr size_t smem = 2 * (size_t)BK * (BM + 32 + BN + 32) * sizeof(bf16_t);
     static_assert(smem <= 160 * 1024, "tile does not fit the 160 KB LDS");
+    static_assert((size_t)WM * WN * 32 * (BN / WN + 4) * sizeof(float) <= smem, "epilogue staging does not fit the slab buffers");
     auto kern = gemm_tn_bf16_kernel<BM, BN, BK, WM, WN, Epi>;
     static bool lds_limit_raised = false;     // per instantiation; contexts are not thread-safe
     if (smem > 64 * 1024 && !lds_limit_raised) {

@@ -443,17 +443,21 @@ struct EpiGeluBwd {              // dh = acc * gelu'(h)
     }
 };
 
-// Tile shapes (BM, BN, BK, wavefronts in M, wavefronts in N), from timing the three GEMM shapes of
-// the benchmark size (tokens x width x hidden = 12608 x 768 x 3072, batch 8) on MI355X:
-// 256x256x64 tiles with 8 wavefronts were fastest where the token axis is M (fwd, dgrad: 4800 or
-// 1200 workgroups), also for the two GEMMs with the heavy GELU epilogues (128x256x32 tiles, which
-// fit three workgroups per CU so that epilogues could overlap main loops, were 10 % slower);
-// the weight-gradient GEMMs have only 3072 x 768 outputs per worker, where 256x256 tiles would
-// leave 288 workgroups for 256 CUs, so they use 128x128x64 (1152 workgroups).
+// Tile shapes (BM, BN, BK, wavefronts in M, wavefronts in N), from timing the GEMM shapes of the
+// benchmark size (tokens x width x hidden = 12608 x 768 x 3072, batch 8) on MI355X:
+// 256x256x64 tiles with 8 wavefronts are fastest where the token axis is M (fwd, dgrad: 4800 or
+// 1200 workgroups), also for the two GEMMs with the heavy GELU epilogues (128x256x32 tiles, two
+// workgroups per CU so that one's epilogue could overlap the other's main loop, timed the same to
+// 4 % slower: they fetch 1.5 times the bytes from L2, which is what bounds the main loop).
+// The weight gradients (768 x 3072 outputs per worker, reduction over the tokens) go to the
+// persistent two-group kernel of gemm_pp.h, whose 192x384 tiles make exactly 256 workgroups for 8
+// workers; 128x128x64 tiles of the plain kernel remain as the fall-back.
 #define QSR_GEMM_BIG 256, 256, 64, 2, 4
 #define QSR_GEMM_WGRAD 128, 128, 64, 2, 2
 
-// the persistent two-group kernels where the problem allows them, else the plain tiled ones
+// NT: the plain tiled kernel (the persistent one timed the same to slower here: a workgroup that
+// goes on to its next tile must first see its epilogue's stores complete, where a fresh workgroup
+// starts at once).  TN: the persistent two-group kernel where the problem allows it.
 template <class Epi>
 static hipError_t gemm_nt(const GemmNT &p, const Epi &epi, int batch, hipStream_t s)
 {

@@ -336,6 +336,26 @@ def test_resmlp_mid_size_gradient():
     ctx.close()
 
 
+def test_resmlp_weight_gradient_many_tiles():
+    """Full-width layer (768 x 3072) with 9 workers: 288 weight-gradient tiles of 192 x 384 for 256
+    persistent workgroups, so some of them walk two tiles; the token count (200) leaves a ragged
+    last reduction slab."""
+    dims = dict(d_in=768, d_hidden=3072, n_blocks=1, B_loc=200, K=9)
+    w = workloads.get("resmlp", T=4, T_warm=1, **dims)
+    ctx = gpu_ctx(w)
+    orc = oracle_run(w, n_threads=4)
+    th0 = workloads.theta0(w).astype(np.float64)
+    ctx.local_step()
+    g = ctx.grads.cpu().numpy()
+    loss = ctx.read_loss()
+    for k in (0, 4, 8):
+        want, wl = orc.grad(k, 0, th0)
+        assert loss[k] == pytest.approx(wl, rel=1e-2)
+        for name, sl in _resmlp_groups(w):
+            assert_params_close(g[k, sl], want[sl], rtol=RTOL_BF16, what="resmlp wide grad %s k=%d" % (name, k))
+    ctx.close()
+
+
 def test_resmlp_short_run():
     """Local AdamW + QSR on the residual-MLP workload at reduced size: warm-up rule, two rounds."""
     w = workloads.get("resmlp", d_in=64, d_hidden=128, n_blocks=2, B_loc=100, K=2, T=40, T_warm=4,
