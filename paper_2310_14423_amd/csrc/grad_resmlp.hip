@@ -466,7 +466,7 @@ static hipError_t gemm_nt(const GemmNT &p, const Epi &epi, int batch, hipStream_
 template <class Epi>
 static hipError_t gemm_tn(const GemmNT &p, const Epi &epi, int batch, hipStream_t s)
 {
-    if (gemm_pp_supports(p, true)) return launch_gemm_pp<true>(p, epi, batch, s);
+    if (gemm_pp_tn_supports(p)) return launch_gemm_pp_tn(p, epi, batch, s);
     return launch_gemm_tn<QSR_GEMM_WGRAD>(p, epi, batch, s);
 }
 
