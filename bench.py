@@ -141,7 +141,7 @@ def run_workload(name, steps, warmup, kernel_timing=True):
         flops = 6 * w["n_blocks"] * K * 2.0 * w["B_loc"] * w["d_in"] * w["d_hidden"]
         g_ms = ms[0] / cnt[0]
         ach = flops / (g_ms * 1e-3) / 1e12
-        roofline = {"kernel": "gradient stage: gemm_nt_bf16_kernel / gemm_tn_bf16_kernel + helpers",
+        roofline = {"kernel": "gradient stage: gemm_nt_bf16_kernel / gemm_pp_tn_kernel + helpers",
                     "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "avg_ms": g_ms,
                     "launches": cnt[0], "flops_per_launch": flops}
