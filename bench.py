@@ -27,7 +27,7 @@ BYTES_PER_AVERAGE = 8
 # HBM bytes per launch of the update kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE (scaled by a
 # kernel of known size; profiles/flat60m_hbm_traffic_pmc.md).  Valid only for the kernel source
 # the counters were taken on: keyed by the first 16 hex digits of its SHA-256.
-PMC_TRAFFIC = {"flat60m": {"source": "update.hip", "sha256_16": "a1633381720059d5", "bytes": 26.870e9}}
+PMC_TRAFFIC = {"flat60m": {"sources": ["update.hip", "opt_elem.h"], "sha256_16": "ee529a9dc78d2a72", "bytes": 26.873e9}}
 
 
 def measured_traffic(workload):
@@ -35,12 +35,13 @@ def measured_traffic(workload):
     ent = PMC_TRAFFIC.get(workload)
     if not ent:
         return None
-    src = os.path.join(ROOT, "paper_2310_14423_amd", "csrc", ent["source"])
+    h = hashlib.sha256()
     try:
-        h = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
+        for name in ent["sources"]:
+            h.update(open(os.path.join(ROOT, "paper_2310_14423_amd", "csrc", name), "rb").read())
     except OSError:
         return None
-    return ent["bytes"] if h == ent["sha256_16"] else None
+    return ent["bytes"] if h.hexdigest()[:16] == ent["sha256_16"] else None
 
 
 def cpu_baseline(w, cpu_seconds_target=20.0):
@@ -182,6 +183,34 @@ def run_workload(name, steps, warmup, kernel_timing=True):
     return out, w
 
 
+def fused_sync_probe(name):
+    """The optional fused form (update + averaging of a round's last step in one pass) on the same
+    buffers: a short run with a constant period of 4, so that every fourth step synchronizes.
+    Bytes per replica-parameter on such a step: AdamW 16 read + 8 (m, v) + 4 (mean) written = 28
+    instead of 28 (update) + 8 (averaging); SGD 20 instead of 20 + 8."""
+    import torch
+    import workloads
+    import paper_2310_14423_amd as qsr
+    w = workloads.get(name, fuse_sync=True, power=0, H_base=4, alpha=0.0)
+    K, P = w["K"], w["P"]
+    ctx = qsr.Context(w, theta0=workloads.theta0(w), model_const=workloads.model_const(w))
+    ctx.step(8)
+    ctx.timing(True)
+    ctx.read_timing()
+    ctx.step(40)
+    ms, cnt = ctx.read_timing()
+    ctx.timing(False)
+    ctx.close()
+    del ctx
+    torch.cuda.empty_cache()
+    if cnt[2] == 0:
+        return None
+    f_ms = ms[2] / cnt[2]
+    nbytes = BYTES_PER_UPDATE[w["opt"]] * K * P
+    return {"update_and_average_fused_ms_avg": f_ms, "launches": cnt[2], "bytes_per_launch": nbytes,
+            "GBs": nbytes / (f_ms * 1e-3) / 1e9, "skipped_launch_ms_avg": ms[3] / cnt[3] if cnt[3] else None}
+
+
 # short runs of the other workloads, reported next to the headline one
 OTHER_WORKLOADS = {"lsq": dict(steps=None, warmup=5), "mlp": dict(steps=None, warmup=5),
                    "resmlp": dict(steps=10, warmup=2), "flat350m": dict(steps=100, warmup=2)}
@@ -228,6 +257,8 @@ def main():
             except Exception as e:                    # e.g. not enough free HBM for the largest one
                 per[name] = {"error": "%s: %s" % (type(e).__name__, e)}
         out["per_workload"] = per
+        if w["model"] in ("noise", "external"):
+            out["fused_sync"] = fused_sync_probe(args.workload)
     out["cpu_baseline"] = None if args.no_cpu_baseline else cpu_baseline(w)
     print(json.dumps(out))
 

@@ -79,6 +79,11 @@ typedef struct {
     int32_t average_state;/* 0: optimizer state stays local at a synchronization, as in Alg. 2, which
                              averages the model parameters only; 1: the state buffers (momentum /
                              m, v) are averaged with them                                   */
+    int32_t fuse_sync;    /* 1: the local step that completes a round also averages (one pass over
+                             the buffers: 28 B per replica-parameter for AdamW on that step instead
+                             of 28 + 8); qsr_maybe_sync then only opens the next round.  Same
+                             results bit for bit.  Not with parallel or average_state.  0 = off */
+    int32_t reserved;     /* must be 0                                                    */
     int64_t P;            /* parameters per worker, >= 1                                   */
     int64_t T;            /* total iterations, eta_t is defined for t in 0..T-1, >= 1      */
     int64_t T_warm;       /* linear warm-up 0 -> eta_max over the first T_warm iterations  */
@@ -169,8 +174,10 @@ int qsr_restart(qsr_ctx *ctx);
  * gradient stage, update kernel and averaging kernel is bracketed by an event pair;
  * qsr_read_timing synchronises, adds up the pairs recorded since the last read and recycles
  * them.  ms[i] / count[i]: 0 = gradient stage, 1 = update kernel, 2 = averaging launches that
- * averaged, 3 = averaging launches that the device-side decision skipped.  Read before
- * qsr_restart: the split of 2 and 3 uses the log of the current run. */
+ * averaged, 3 = averaging launches that the device-side decision skipped.  With fuse_sync, 2
+ * and 3 are the fused update-and-average launches that acted / were skipped, and 1 also holds
+ * the plain update launches skipped on those steps.  Read before qsr_restart: the split of 2
+ * and 3 uses the log of the current run. */
 int qsr_timing(qsr_ctx *ctx, int enable);
 int qsr_read_timing(qsr_ctx *ctx, double ms[4], int64_t count[4]);
 

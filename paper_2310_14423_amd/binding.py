@@ -33,6 +33,7 @@ class Config(C.Structure):
         ("K", C.c_int32), ("opt", C.c_int32), ("model", C.c_int32), ("lr_kind", C.c_int32),
         ("H_base", C.c_int32), ("n_milestones", C.c_int32), ("n_blocks", C.c_int32),
         ("power", C.c_int32), ("parallel", C.c_int32), ("average_state", C.c_int32),
+        ("fuse_sync", C.c_int32), ("reserved", C.c_int32),
         ("P", C.c_int64), ("T", C.c_int64), ("T_warm", C.c_int64), ("t_local_start", C.c_int64),
         ("t_swap_start", C.c_int64), ("B_loc", C.c_int64),
         ("d_in", C.c_int64), ("d_hidden", C.c_int64), ("d_out", C.c_int64),
@@ -78,6 +79,7 @@ def make_config(w, stream=0, eta_table=None):
     c.t_local_start = w.get("t_local_start", 0)
     c.t_swap_start = w.get("t_swap_start", 0)
     c.average_state = int(w.get("average_state", False))
+    c.fuse_sync = int(w.get("fuse_sync", False))
     c.P = w["P"]; c.T = w["T"]; c.T_warm = w.get("T_warm", 0)
     c.B_loc = w.get("B_loc", 0); c.d_in = w.get("d_in", 0); c.d_hidden = w.get("d_hidden", 0)
     c.d_out = w.get("d_out", 0); c.n_blocks = w.get("n_blocks", 0)

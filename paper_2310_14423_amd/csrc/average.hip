@@ -7,21 +7,13 @@
 // error of each partial sum is carried in a second accumulator), so the mean is accurate to
 // about one rounding whatever K is, does not depend on the launch shape, all K rows receive the
 // same bits, and averaging K identical rows returns that row when K is a power of two.
+#include "opt_elem.h"
 #include "qsr_internal.h"
 
 namespace qsr {
 
 constexpr int AVG_THREADS = 64;
 constexpr int AVG_KU = 16;
-
-// s + c <- s + c + r, with the rounding error of s + r recovered exactly (two-sum)
-__device__ __forceinline__ void add_comp(float &s, float &c, float r)
-{
-    float t = s + r;
-    float bp = t - s;
-    c += (s - (t - bp)) + (r - bp);
-    s = t;
-}
 
 // K <= KMAX: all K row loads of a column are issued before the first addition (fully unrolled,
 // predicated on k < K), then K stores.  From a sweep on MI355X (K = 16 and 32, P = 60e6):

@@ -83,6 +83,9 @@ extern "C" int qsr_validate(const qsr_config *c, const char **why)
     else if (c->lr_kind < QSR_LR_COSINE || c->lr_kind > QSR_LR_POW2COS) w = "lr_kind";
     else if (c->H_base < 1) w = "H_base";
     else if (c->average_state != 0 && c->average_state != 1) w = "average_state";
+    else if (c->fuse_sync != 0 && c->fuse_sync != 1) w = "fuse_sync";
+    else if (c->fuse_sync == 1 && (c->parallel == 1 || c->average_state == 1)) w = "fuse_sync with parallel or average_state";
+    else if (c->reserved != 0) w = "reserved";
     else if (c->power < 0 || c->power > 8) w = "power";
     else if (c->parallel != 0 && c->parallel != 1) w = "parallel";
     else if (c->parallel == 1 && (c->H_base != 1 || c->power != 0 || c->t_local_start != 0 || c->t_swap_start != 0))
@@ -400,14 +403,28 @@ extern "C" int qsr_local_step(qsr_ctx *c)
     {                                                   // OPT for all K workers at once
         Bracket br(c, 1);
         if (br.rc != QSR_OK) return br.rc;
+        const bool fused = cfg.fuse_sync != 0;
         if (cfg.opt == QSR_OPT_SGDM)
             HIP_TRY(launch_update_sgdm(c->params, c->grads, c->state0, n, c->d_state, c->d_scal,
-                                       (float)cfg.momentum, (float)cfg.weight_decay, c->stream));
+                                       (float)cfg.momentum, (float)cfg.weight_decay, fused, c->stream));
         else
             HIP_TRY(launch_update_adamw(c->params, c->grads, c->state0, c->state1, n, c->d_state,
                                         c->d_scal, (float)(1.0 - cfg.beta1), (float)(1.0 - cfg.beta2),
-                                        (float)cfg.eps, c->stream));
+                                        (float)cfg.eps, fused, c->stream));
         int rc = br.close(c->t_host);
+        if (rc != QSR_OK) return rc;
+    }
+    if (cfg.fuse_sync) {                                // the round's last step: OPT and All-Reduce in one pass
+        Bracket br(c, 2);                               // timed like an averaging launch: it ran iff the log says so
+        if (br.rc != QSR_OK) return br.rc;
+        if (cfg.opt == QSR_OPT_SGDM)
+            HIP_TRY(launch_update_sgdm_sync(c->params, c->grads, c->state0, cfg.K, cfg.P, c->d_state, c->d_scal,
+                                            (float)cfg.momentum, (float)cfg.weight_decay, c->stream));
+        else
+            HIP_TRY(launch_update_adamw_sync(c->params, c->grads, c->state0, c->state1, cfg.K, cfg.P, c->d_state,
+                                             c->d_scal, (float)(1.0 - cfg.beta1), (float)(1.0 - cfg.beta2),
+                                             (float)cfg.eps, c->stream));
+        int rc = br.close(c->t_host + 1);
         if (rc != QSR_OK) return rc;
     }
     HIP_TRY(launch_sched_tick(c->d_state, c->stream));
@@ -420,7 +437,8 @@ extern "C" int qsr_maybe_sync(qsr_ctx *c)
 {
     if (!c) return QSR_EINVAL;
     if (!c->need_sync_call) return QSR_ESTATE;
-    if (!c->cfg.parallel) {      // Parallel OPT keeps the workers identical: nothing to average
+    if (!c->cfg.parallel && !c->cfg.fuse_sync) {   // Parallel OPT keeps the workers identical, the fused
+                                                   // form has averaged in qsr_local_step already
         Bracket br(c, 2);
         if (br.rc != QSR_OK) return br.rc;
         HIP_TRY(launch_average_rows(c->params, c->cfg.K, c->cfg.P, c->d_state, c->stream));

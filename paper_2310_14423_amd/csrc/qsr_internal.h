@@ -60,12 +60,20 @@ hipError_t launch_sched_set(DevState *st, SchedParams sp, long long t, long long
                             hipStream_t s);
 hipError_t launch_sched_next_round(DevState *st, SchedParams sp, hipStream_t s);
 
+// fused_sync: leave the step that completes a round to launch_update_*_sync
 hipError_t launch_update_sgdm(float *theta, const float *g, float *buf, long long n,
                               const DevState *st, const StepScalars *sc, float mu, float lambda,
-                              hipStream_t s);
+                              bool fused_sync, hipStream_t s);
 hipError_t launch_update_adamw(float *theta, const float *g, float *m, float *v, long long n,
                                const DevState *st, const StepScalars *sc, float c1, float c2,
-                               float eps, hipStream_t s);
+                               float eps, bool fused_sync, hipStream_t s);
+// update + averaging in one pass over the [K][P] buffers, only on the step that completes a round
+hipError_t launch_update_sgdm_sync(float *theta, const float *g, float *buf, int K, long long P,
+                                   const DevState *st, const StepScalars *sc, float mu, float lambda,
+                                   hipStream_t s);
+hipError_t launch_update_adamw_sync(float *theta, const float *g, float *m, float *v, int K, long long P,
+                                    const DevState *st, const StepScalars *sc, float c1, float c2,
+                                    float eps, hipStream_t s);
 
 // mean over the K rows of buf [K][P], written to all rows; skipped on the device when
 // st != nullptr and st->do_sync == 0

@@ -7,6 +7,7 @@
 // a single trip (no grid-stride loop) over 2 x 64 float4 per array reached 5.85 TB/s, against
 // 5.0-5.1 TB/s for 256-thread blocks in a capped persistent grid and 5.77 TB/s for a plain
 // copy kernel; non-temporal loads and stores were each worth 3-5 %.
+#include "opt_elem.h"
 #include "qsr_internal.h"
 
 namespace qsr {
@@ -17,28 +18,14 @@ constexpr int UPD_UNROLL = 2;      // float4 per array per thread per trip
 __device__ __forceinline__ float4 ldg_nt(const float4 *p) { return ld_nt4(p); }
 __device__ __forceinline__ void stg_nt(float4 *p, float4 v) { st_nt4(p, v); }
 
-// AdamW (decoupled weight decay, bias-corrected), in the order
-//   m <- m + (1-b1)(g - m) ; v <- v + (1-b2)(g^2 - v)
-//   theta <- theta - [ eta*lambda*theta + (eta/bc1) * m / (sqrt(v)/sqrt(bc2) + eps) ]
-// The moment updates are written as one rounding on top of the old moment, and the decay and
-// the Adam step are added before they are subtracted from theta, so that each state variable
-// takes one rounding per step (keeps thousands of fp32 steps within 1e-5 of exact arithmetic).
-__device__ __forceinline__ void adamw_elem(float &th, float g, float &m, float &v, float etalam,
-                                           float stepsz, float rsq_bc2, float c1, float c2,
-                                           float eps)
-{
-    m = fmaf(c1, g - m, m);
-    v = fmaf(c2, fmaf(g, g, -v), v);
-    float denom = fmaf(sqrtf(v), rsq_bc2, eps);
-    float upd = (stepsz * m) / denom;
-    th = th - fmaf(etalam, th, upd);
-}
-
+// `fused_sync`: the context folds the averaging into the last local step of a round (see the
+// *_sync kernels below), so the plain update leaves that step alone.
 __global__ __launch_bounds__(UPD_THREADS) void update_adamw_kernel(
     float4 *__restrict__ theta, const float4 *__restrict__ g, float4 *__restrict__ m,
     float4 *__restrict__ v, long long n4, long long n, const DevState *__restrict__ st,
-    const StepScalars *__restrict__ sc, float c1, float c2, float eps)
+    const StepScalars *__restrict__ sc, float c1, float c2, float eps, int fused_sync)
 {
+    if (fused_sync && st->h + 1 == st->H) return;
     const StepScalars s = sc[st->t];
     const long long stride = (long long)gridDim.x * UPD_THREADS * UPD_UNROLL;
     long long base = (long long)blockIdx.x * UPD_THREADS * UPD_UNROLL + threadIdx.x;
@@ -72,21 +59,12 @@ __global__ __launch_bounds__(UPD_THREADS) void update_adamw_kernel(
     }
 }
 
-// SGD with heavy-ball momentum and coupled weight decay:
-//   g' = g + lambda*theta ; buf <- mu*buf + g' ; theta <- theta - eta*buf
-__device__ __forceinline__ void sgdm_elem(float &th, float g, float &buf, float eta, float mu,
-                                          float lambda)
-{
-    float gp = fmaf(lambda, th, g);
-    buf = fmaf(mu, buf, gp);
-    th = fmaf(-eta, buf, th);
-}
-
 __global__ __launch_bounds__(UPD_THREADS) void update_sgdm_kernel(
     float4 *__restrict__ theta, const float4 *__restrict__ g, float4 *__restrict__ buf,
     long long n4, long long n, const DevState *__restrict__ st,
-    const StepScalars *__restrict__ sc, float mu, float lambda)
+    const StepScalars *__restrict__ sc, float mu, float lambda, int fused_sync)
 {
+    if (fused_sync && st->h + 1 == st->H) return;
     const float eta = sc[st->t].x;
     const long long stride = (long long)gridDim.x * UPD_THREADS * UPD_UNROLL;
     long long base = (long long)blockIdx.x * UPD_THREADS * UPD_UNROLL + threadIdx.x;
@@ -131,23 +109,179 @@ static int update_grid(long long n4)
     return (int)blocks;
 }
 
+// ---------------------------------------------------------------------------------------------
+// The last local step of a round and the averaging that follows it, in one pass (Alg. 2's OPT
+// line for h = H-1 and its All-Reduce line): a lane owns four consecutive parameters, walks the
+// K rows (ROWS of them in flight), updates each worker's state in place, adds the updated
+// parameters up with the same error-free summation and in the same order as the averaging
+// kernel, and writes the mean to all K rows.  AdamW then moves 16 B read + 8 B (m, v) + 4 B
+// (mean) written = 28 B per replica-parameter on such a step instead of 28 + 8; SGD 12 + 8 = 20
+// instead of 20 + 8.  Acts only when this step completes the round (decided on the device, like
+// the averaging); results are bit-identical to update followed by average.
+// ---------------------------------------------------------------------------------------------
+constexpr int SYNC_ROWS = 4;
+// 256 threads: these launches are skipped on the device in all but a handful of iterations, and a
+// skipped launch then has four times fewer workgroups to retire than with one-wavefront blocks
+constexpr int SYNC_THREADS = 256;
+
+__global__ __launch_bounds__(SYNC_THREADS) void update_adamw_sync_kernel(
+    float4 *__restrict__ theta, const float4 *__restrict__ g, float4 *__restrict__ m,
+    float4 *__restrict__ v, int K, long long P4, const DevState *__restrict__ st,
+    const StepScalars *__restrict__ sc, float c1, float c2, float eps)
+{
+    if (st->h + 1 != st->H) return;
+    const StepScalars s = sc[st->t];
+    const float fK = (float)K;
+    const long long stride = (long long)gridDim.x * SYNC_THREADS;
+    for (long long i = (long long)blockIdx.x * SYNC_THREADS + threadIdx.x; i < P4; i += stride) {
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f), cmp = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int k0 = 0; k0 < K; k0 += SYNC_ROWS) {
+            float4 a[SYNC_ROWS], b[SYNC_ROWS], c[SYNC_ROWS], d[SYNC_ROWS];
+#pragma unroll
+            for (int u = 0; u < SYNC_ROWS; ++u)
+                if (k0 + u < K) {
+                    const long long o = (long long)(k0 + u) * P4 + i;
+                    a[u] = ldg_nt(theta + o); b[u] = ldg_nt(g + o); c[u] = ldg_nt(m + o); d[u] = ldg_nt(v + o);
+                }
+#pragma unroll
+            for (int u = 0; u < SYNC_ROWS; ++u)
+                if (k0 + u < K) {
+                    const long long o = (long long)(k0 + u) * P4 + i;
+                    adamw_elem(a[u].x, b[u].x, c[u].x, d[u].x, s.x, s.y, s.z, c1, c2, eps);
+                    adamw_elem(a[u].y, b[u].y, c[u].y, d[u].y, s.x, s.y, s.z, c1, c2, eps);
+                    adamw_elem(a[u].z, b[u].z, c[u].z, d[u].z, s.x, s.y, s.z, c1, c2, eps);
+                    adamw_elem(a[u].w, b[u].w, c[u].w, d[u].w, s.x, s.y, s.z, c1, c2, eps);
+                    stg_nt(m + o, c[u]); stg_nt(v + o, d[u]);
+                    add_comp(acc.x, cmp.x, a[u].x); add_comp(acc.y, cmp.y, a[u].y);
+                    add_comp(acc.z, cmp.z, a[u].z); add_comp(acc.w, cmp.w, a[u].w);
+                }
+        }
+        const float4 mean = make_float4((acc.x + cmp.x) / fK, (acc.y + cmp.y) / fK,
+                                        (acc.z + cmp.z) / fK, (acc.w + cmp.w) / fK);
+        for (int k = 0; k < K; ++k) stg_nt(theta + (long long)k * P4 + i, mean);
+    }
+}
+
+__global__ __launch_bounds__(SYNC_THREADS) void update_sgdm_sync_kernel(
+    float4 *__restrict__ theta, const float4 *__restrict__ g, float4 *__restrict__ buf, int K,
+    long long P4, const DevState *__restrict__ st, const StepScalars *__restrict__ sc, float mu,
+    float lambda)
+{
+    if (st->h + 1 != st->H) return;
+    const float eta = sc[st->t].x;
+    const float fK = (float)K;
+    const long long stride = (long long)gridDim.x * SYNC_THREADS;
+    for (long long i = (long long)blockIdx.x * SYNC_THREADS + threadIdx.x; i < P4; i += stride) {
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f), cmp = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int k0 = 0; k0 < K; k0 += SYNC_ROWS) {
+            float4 a[SYNC_ROWS], b[SYNC_ROWS], c[SYNC_ROWS];
+#pragma unroll
+            for (int u = 0; u < SYNC_ROWS; ++u)
+                if (k0 + u < K) {
+                    const long long o = (long long)(k0 + u) * P4 + i;
+                    a[u] = ldg_nt(theta + o); b[u] = ldg_nt(g + o); c[u] = ldg_nt(buf + o);
+                }
+#pragma unroll
+            for (int u = 0; u < SYNC_ROWS; ++u)
+                if (k0 + u < K) {
+                    const long long o = (long long)(k0 + u) * P4 + i;
+                    sgdm_elem(a[u].x, b[u].x, c[u].x, eta, mu, lambda);
+                    sgdm_elem(a[u].y, b[u].y, c[u].y, eta, mu, lambda);
+                    sgdm_elem(a[u].z, b[u].z, c[u].z, eta, mu, lambda);
+                    sgdm_elem(a[u].w, b[u].w, c[u].w, eta, mu, lambda);
+                    stg_nt(buf + o, c[u]);
+                    add_comp(acc.x, cmp.x, a[u].x); add_comp(acc.y, cmp.y, a[u].y);
+                    add_comp(acc.z, cmp.z, a[u].z); add_comp(acc.w, cmp.w, a[u].w);
+                }
+        }
+        const float4 mean = make_float4((acc.x + cmp.x) / fK, (acc.y + cmp.y) / fK,
+                                        (acc.z + cmp.z) / fK, (acc.w + cmp.w) / fK);
+        for (int k = 0; k < K; ++k) stg_nt(theta + (long long)k * P4 + i, mean);
+    }
+}
+
+// rows whose length is not a multiple of 4 are not 16-byte aligned: one element per lane
+// (v == nullptr: SGD with momentum, m is its buffer, c1 = mu, c2 = lambda)
+__global__ __launch_bounds__(SYNC_THREADS) void update_sync_scalar_kernel(
+    float *__restrict__ theta, const float *__restrict__ g, float *__restrict__ m,
+    float *__restrict__ v, int K, long long P, const DevState *__restrict__ st,
+    const StepScalars *__restrict__ sc, float c1, float c2, float eps)
+{
+    if (st->h + 1 != st->H) return;
+    const StepScalars s = sc[st->t];
+    const float fK = (float)K;
+    const long long stride = (long long)gridDim.x * SYNC_THREADS;
+    for (long long i = (long long)blockIdx.x * SYNC_THREADS + threadIdx.x; i < P; i += stride) {
+        float acc = 0.f, cmp = 0.f;
+        for (int k = 0; k < K; ++k) {
+            const long long o = (long long)k * P + i;
+            float a = theta[o], c = m[o];
+            if (v != nullptr) {
+                float d = v[o];
+                adamw_elem(a, g[o], c, d, s.x, s.y, s.z, c1, c2, eps);
+                v[o] = d;
+            } else {
+                sgdm_elem(a, g[o], c, s.x, c1, c2);
+            }
+            m[o] = c;
+            add_comp(acc, cmp, a);
+        }
+        const float mean = (acc + cmp) / fK;
+        for (int k = 0; k < K; ++k) theta[(long long)k * P + i] = mean;
+    }
+}
+
+static int sync_grid(long long items)
+{
+    long long blocks = (items + SYNC_THREADS - 1) / SYNC_THREADS;
+    const long long cap = 0x7FFFFFFFll;
+    if (blocks > cap) blocks = cap;
+    if (blocks < 1) blocks = 1;
+    return (int)blocks;
+}
+
+hipError_t launch_update_adamw_sync(float *theta, const float *g, float *m, float *v, int K, long long P,
+                                    const DevState *st, const StepScalars *sc, float c1, float c2,
+                                    float eps, hipStream_t s)
+{
+    if ((P & 3) == 0)
+        update_adamw_sync_kernel<<<sync_grid(P / 4), SYNC_THREADS, 0, s>>>(
+            (float4 *)theta, (const float4 *)g, (float4 *)m, (float4 *)v, K, P / 4, st, sc, c1, c2, eps);
+    else
+        update_sync_scalar_kernel<<<sync_grid(P), SYNC_THREADS, 0, s>>>(theta, g, m, v, K, P, st, sc, c1, c2, eps);
+    return hipGetLastError();
+}
+
+hipError_t launch_update_sgdm_sync(float *theta, const float *g, float *buf, int K, long long P,
+                                   const DevState *st, const StepScalars *sc, float mu, float lambda,
+                                   hipStream_t s)
+{
+    if ((P & 3) == 0)
+        update_sgdm_sync_kernel<<<sync_grid(P / 4), SYNC_THREADS, 0, s>>>(
+            (float4 *)theta, (const float4 *)g, (float4 *)buf, K, P / 4, st, sc, mu, lambda);
+    else
+        update_sync_scalar_kernel<<<sync_grid(P), SYNC_THREADS, 0, s>>>(theta, g, buf, nullptr, K, P, st, sc, mu,
+                                                                       lambda, 0.f);
+    return hipGetLastError();
+}
+
 hipError_t launch_update_adamw(float *theta, const float *g, float *m, float *v, long long n,
                                const DevState *st, const StepScalars *sc, float c1, float c2,
-                               float eps, hipStream_t s)
+                               float eps, bool fused_sync, hipStream_t s)
 {
     long long n4 = n / 4;
     update_adamw_kernel<<<update_grid(n4), UPD_THREADS, 0, s>>>(
-        (float4 *)theta, (const float4 *)g, (float4 *)m, (float4 *)v, n4, n, st, sc, c1, c2, eps);
+        (float4 *)theta, (const float4 *)g, (float4 *)m, (float4 *)v, n4, n, st, sc, c1, c2, eps, fused_sync ? 1 : 0);
     return hipGetLastError();
 }
 
 hipError_t launch_update_sgdm(float *theta, const float *g, float *buf, long long n,
                               const DevState *st, const StepScalars *sc, float mu, float lambda,
-                              hipStream_t s)
+                              bool fused_sync, hipStream_t s)
 {
     long long n4 = n / 4;
     update_sgdm_kernel<<<update_grid(n4), UPD_THREADS, 0, s>>>(
-        (float4 *)theta, (const float4 *)g, (float4 *)buf, n4, n, st, sc, mu, lambda);
+        (float4 *)theta, (const float4 *)g, (float4 *)buf, n4, n, st, sc, mu, lambda, fused_sync ? 1 : 0);
     return hipGetLastError();
 }
 

@@ -510,6 +510,50 @@ def test_state_averaging_option(opt):
     ctx.close()
 
 
+@pytest.mark.parametrize("opt", ["adamw", "sgdm"])
+@pytest.mark.parametrize("K,P", [(16, 65536 + 4), (3, 4099), (5, 1 << 18), (1, 8)])
+def test_fused_update_and_averaging(opt, K, P):
+    """The last local step of a round and its averaging in one pass: same bits as the two kernels,
+    parameters and state, and within tolerance of the oracle; rows of 4099 elements take the
+    unaligned path."""
+    import torch
+    kw = dict(mu=0.9, lam=1e-3) if opt == "sgdm" else dict(beta1=0.9, beta2=0.99, eps=1e-8, lam=0.01)
+    T = 30
+    w = _ext_workload(opt, K, P, T, T_warm=3, H_base=2, alpha=0.08, **kw)
+    rng = np.random.default_rng(K + P)
+    th0 = rng.standard_normal(P).astype(np.float32)
+    plain = gpu_ctx(w, theta0=th0)
+    fused = gpu_ctx(dict(w, fuse_sync=True), theta0=th0)
+    orc = oracle_run(w, theta0=th0)
+    for t in range(T):
+        g = (rng.standard_normal((K, P)) * rng.choice([1e-2, 1.0])).astype(np.float32)
+        for c in (plain, fused):
+            c.grads.copy_(torch.from_numpy(g))
+            c.step()
+        orc.step(1, ext_g=g[None].astype(np.float64))
+    assert list(fused.read_sync_log()[0]) == list(orc.sync_log) and len(orc.sync_log) >= 4
+    assert list(fused.read_sync_log()[1]) == list(orc.H_log)
+    for name in ("params", "state0") + (("state1",) if opt == "adamw" else ()):
+        a, b = getattr(plain, name).cpu().numpy(), getattr(fused, name).cpu().numpy()
+        assert np.array_equal(a, b), name
+    assert_params_close(fused.params.cpu().numpy(), orc.theta, what="fused params")
+    p = fused.params.cpu().numpy()
+    assert all(np.array_equal(p[k], p[0]) for k in range(K))
+    plain.close(); fused.close()
+
+
+def test_fused_sync_on_noise_workload():
+    """flat60m at reduced size with the fused form: schedule and parameters as the oracle's."""
+    w = workloads.get("flat60m", K=4, P=20003, T=400, alpha=0.004, fuse_sync=True)
+    ctx = gpu_ctx(w)
+    orc = oracle_run(w)
+    ctx.step(400); orc.step(400)
+    st, Hs = ctx.read_sync_log()
+    assert list(st) == list(orc.sync_log) and list(Hs) == list(orc.H_log) and len(st) >= 3
+    assert_params_close(ctx.params.cpu().numpy(), orc.theta, what="fused noise params")
+    ctx.close()
+
+
 def test_checkpoint_and_resume():
     """Stop after 700 of 2000 iterations (inside a round), restore buffers and scheduler state in a
     fresh context, finish: bit-identical to the uninterrupted run, and the log continues."""
