@@ -42,7 +42,7 @@ class Config(C.Structure):
         ("d_in", C.c_int64), ("d_hidden", C.c_int64), ("d_out", C.c_int64),
         ("mu", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double),
         ("lam", C.c_double), ("alpha", C.c_double), ("grad_sigma", C.c_double),
-        ("data_sigma", C.c_double),
+        ("data_sigma", C.c_double), ("clip_norm", C.c_double),
         ("seed", C.c_uint64),
         ("model_const", C.c_void_p), ("p_idx", C.c_void_p),
     ]
@@ -59,7 +59,7 @@ def lib():
         _lib.qsro_get_H_power.restype = C.c_int64
         _lib.qsro_get_H.restype = C.c_int64
         _lib.qsro_schedule.restype = C.c_int64
-        for f in ("qsro_grad_linreg", "qsro_grad_mlp2", "qsro_grad_resmlp"):
+        for f in ("qsro_grad_linreg", "qsro_grad_mlp2", "qsro_grad_resmlp", "qsro_clip"):
             getattr(_lib, f).restype = C.c_double
     return _lib
 
@@ -150,6 +150,12 @@ def adamw_step(theta, m, v, g, eta, b1, b2, eps, lam, step):
                           C.c_double(lam), C.c_int64(step))
 
 
+def clip(g, max_norm):
+    """Clips one worker's gradient in place; returns its norm before clipping."""
+    assert g.dtype == np.float64 and g.flags.c_contiguous
+    return lib().qsro_clip(_p(g), C.c_int64(g.size), C.c_double(max_norm))
+
+
 def average(theta):
     K, n = theta.shape
     lib().qsro_average(_p(theta), C.c_int32(K), C.c_int64(n))
@@ -167,7 +173,7 @@ class Run:
                  eps=1e-8, lam=0.0, H_base=1, alpha=0.0, model="external", seed=0,
                  grad_sigma=0.0, data_sigma=0.0, B_loc=0, d_in=0, d_hidden=0, d_out=0,
                  n_blocks=0, model_const=None, p_idx=None, theta0=None, n_threads=1, power=2,
-                 parallel=False, t_local_start=0, average_state=False, t_swap_start=0):
+                 parallel=False, t_local_start=0, average_state=False, t_swap_start=0, clip_norm=0.0):
         self.eta = _f64(eta)
         self.K, self.n = int(K), int(n)
         self._const = None if model_const is None else np.ascontiguousarray(model_const, np.float32)
@@ -177,7 +183,7 @@ class Run:
                           t_local_start=t_local_start, t_swap_start=t_swap_start, n=n, T=len(self.eta),
                           T_warm=T_warm, B_loc=B_loc, d_in=d_in, d_hidden=d_hidden, d_out=d_out,
                           mu=mu, beta1=beta1, beta2=beta2, eps=eps, lam=lam, alpha=alpha,
-                          grad_sigma=grad_sigma, data_sigma=data_sigma, seed=seed,
+                          grad_sigma=grad_sigma, data_sigma=data_sigma, clip_norm=clip_norm, seed=seed,
                           model_const=_p(self._const), p_idx=_p(self._pidx))
         self.state = State(0, 0, 0, 0)
         self.theta = np.zeros((K, n), dtype=np.float64)

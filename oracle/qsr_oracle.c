@@ -432,13 +432,28 @@ double qsro_grad_mlp2(const qsro_config *c, int32_t k, int64_t t, const double *
  * sync_log[s] receive H^(s) and the iteration count at that moment.
  * loss_out, if not NULL, is [n_steps][K] (models 2-4).
  * Returns 0, or -1 on a step past T or a bad model id. */
+/* Gradient clipping by global norm, one worker's gradient (App. C, "gradient clipping": threshold
+ * 1 for parallel AdamW, 4 for Local AdamW with constant H in the linear / step-decay runs, off in
+ * the QSR runs):  g <- g * min(1, c / (||g||_2 + 1e-6)), the convention of the framework the
+ * paper trained with.  Returns the norm before clipping. */
+double qsro_clip(double *g, int64_t n, double max_norm)
+{
+    double ss = 0.0;
+    for (int64_t i = 0; i < n; ++i) ss += g[i] * g[i];
+    double norm = sqrt(ss);
+    double coef = max_norm / (norm + 1e-6);
+    if (coef < 1.0)
+        for (int64_t i = 0; i < n; ++i) g[i] *= coef;
+    return norm;
+}
+
 int qsro_run(const qsro_config *c, const double *eta, qsro_state *st, double *theta,
              double *st0, double *st1, int64_t n_steps, const double *ext_g,
              int64_t *H_log, int64_t *sync_log, int64_t log_cap, double *loss_out)
 {
     int32_t K = c->K;
     int64_t n = c->n;
-    double *gbuf = NULL, *gavg = NULL;
+    double *gbuf = NULL, *gavg = NULL, *gclip = NULL;
     if (c->model != 0) gbuf = (double *)malloc(sizeof(double) * (size_t)K * (size_t)n);
     int rc = 0;
     for (int64_t it = 0; it < n_steps; ++it) {
@@ -470,6 +485,12 @@ int qsro_run(const qsro_config *c, const double *eta, qsro_state *st, double *th
             qsro_average(gavg, K, n);
             gall = gavg;
         }
+        if (c->clip_norm > 0.0) {                  /* clipping sits between the gradient and OPT */
+            if (!gclip) gclip = (double *)malloc(sizeof(double) * (size_t)K * (size_t)n);
+            memcpy(gclip, gall, sizeof(double) * (size_t)K * (size_t)n);
+            for (int32_t k = 0; k < K; ++k) qsro_clip(gclip + (int64_t)k * n, n, c->clip_norm);
+            gall = gclip;
+        }
 #ifdef _OPENMP
 #pragma omp parallel for num_threads(c->n_threads > 0 ? c->n_threads : 1) schedule(static)
 #endif
@@ -498,5 +519,6 @@ int qsro_run(const qsro_config *c, const double *eta, qsro_state *st, double *th
     }
     free(gbuf);
     free(gavg);
+    free(gclip);
     return rc;
 }

@@ -31,6 +31,8 @@ typedef struct {
     double alpha;
     double grad_sigma;    /* model 1: std of the gradient noise               */
     double data_sigma;    /* model 2: observation noise; model 3: input noise */
+    double clip_norm;     /* > 0: each worker's gradient is clipped to this
+                             Euclidean norm before OPT (App. C); 0 = off      */
     uint64_t seed;
     const float *model_const; /* model 2: w* [d]; 3: class means [C][d_in];
                                  4: teacher map [d][d]                        */

@@ -271,3 +271,38 @@ def test_state_averaging_option():
         assert not np.allclose(st_b[0], st_b[1])
     a.step(3, ext_g=g[3:]); b.step(3, ext_g=g[3:])
     assert not np.allclose(a.theta, b.theta)                                      # and the runs differ afterwards
+
+
+def test_gradient_clipping_equals_the_library_routine():
+    """App. C's gradient clipping (by global norm, per worker): the oracle's clipped run is the
+    library's clip_grad_norm_ followed by the library's optimizer, in double precision; below
+    the threshold nothing changes, far above it the gradient has the threshold's norm."""
+    rng = np.random.default_rng(5)
+    n, T, K = 13, 25, 2
+    eta = oracle.lr_cosine(T, 3, 0.02, 0.0)
+    g = rng.standard_normal((T, K, n)) * rng.choice([0.05, 1.0, 20.0], size=(T, 1, 1))
+    th0 = rng.standard_normal(n)
+    run = oracle.Run(K=K, n=n, eta=eta, T_warm=3, opt="adamw", beta1=0.9, beta2=0.95, eps=1e-8, lam=0.1,
+                     H_base=T, alpha=0.0, theta0=th0, clip_norm=1.0)      # one round: workers stay apart
+    ps = [torch.tensor(th0, dtype=torch.float64, requires_grad=True) for _ in range(K)]
+    os_ = [torch.optim.AdamW([p], lr=1.0, betas=(0.9, 0.95), eps=1e-8, weight_decay=0.1) for p in ps]
+    for t in range(T - 1):
+        run.step(1, ext_g=g[t:t + 1])
+        for k in range(K):
+            os_[k].param_groups[0]["lr"] = float(eta[t])
+            ps[k].grad = torch.tensor(g[t, k])
+            torch.nn.utils.clip_grad_norm_([ps[k]], max_norm=1.0)
+            os_[k].step()
+            assert np.allclose(run.theta[k], ps[k].detach().numpy(), rtol=1e-11, atol=1e-13), (t, k)
+    # the routine itself
+    small = np.array([0.3, -0.4]); big = np.array([30.0, -40.0])
+    a = small.copy(); oracle.clip(a, 1.0)
+    assert np.array_equal(a, small)
+    b = big.copy(); norm = oracle.clip(b, 1.0)
+    assert norm == pytest.approx(50.0, rel=1e-15)
+    assert np.linalg.norm(b) == pytest.approx(1.0, rel=1e-6) and np.allclose(b / np.linalg.norm(b), big / 50.0)
+    # clipping changes the trajectory when gradients are large, and not otherwise
+    free = oracle.Run(K=K, n=n, eta=eta, T_warm=3, opt="sgdm", mu=0.9, H_base=T, theta0=th0)
+    clipped = oracle.Run(K=K, n=n, eta=eta, T_warm=3, opt="sgdm", mu=0.9, H_base=T, theta0=th0, clip_norm=1e9)
+    free.step(5, ext_g=g[:5]); clipped.step(5, ext_g=g[:5])
+    assert np.array_equal(free.theta, clipped.theta)
