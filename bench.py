@@ -27,7 +27,7 @@ BYTES_PER_AVERAGE = 8
 # HBM bytes per launch of the update kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE (scaled by a
 # kernel of known size; profiles/flat60m_hbm_traffic_pmc.md).  Valid only for the kernel source
 # the counters were taken on: keyed by the first 16 hex digits of its SHA-256.
-PMC_TRAFFIC = {"flat60m": {"sources": ["update.hip", "opt_elem.h"], "sha256_16": "ee529a9dc78d2a72", "bytes": 26.873e9}}
+PMC_TRAFFIC = {"flat60m": {"sources": ["update.hip", "opt_elem.h"], "sha256_16": "79a601e2bc8f7857", "bytes": 26.870e9}}
 
 
 def measured_traffic(workload):
@@ -211,6 +211,31 @@ def fused_sync_probe(name):
             "GBs": nbytes / (f_ms * 1e-3) / 1e9, "skipped_launch_ms_avg": ms[3] / cnt[3] if cnt[3] else None}
 
 
+def clip_probe(name):
+    """The optional gradient clipping on the same buffers: the norm pass reads the gradients once
+    more (4 B per replica-parameter), the factors are applied inside the update kernel; the update
+    bracket then covers 28 + 4 = 32 B (AdamW) per replica-parameter."""
+    import torch
+    import workloads
+    import paper_2310_14423_amd as qsr
+    w = workloads.get(name, clip_norm=1.0)
+    K, P = w["K"], w["P"]
+    ctx = qsr.Context(w, theta0=workloads.theta0(w), model_const=workloads.model_const(w))
+    ctx.step(5)
+    ctx.timing(True)
+    ctx.read_timing()
+    ctx.step(30)
+    ms, cnt = ctx.read_timing()
+    ctx.timing(False)
+    ctx.close()
+    del ctx
+    torch.cuda.empty_cache()
+    u_ms = ms[1] / cnt[1]
+    nbytes = (BYTES_PER_UPDATE[w["opt"]] + 4) * K * P
+    return {"norm_and_update_ms_avg": u_ms, "launches": cnt[1], "bytes_per_launch": nbytes,
+            "GBs": nbytes / (u_ms * 1e-3) / 1e9}
+
+
 # short runs of the other workloads, reported next to the headline one
 OTHER_WORKLOADS = {"lsq": dict(steps=None, warmup=5), "mlp": dict(steps=None, warmup=5),
                    "resmlp": dict(steps=10, warmup=2), "flat350m": dict(steps=100, warmup=2)}
@@ -259,6 +284,7 @@ def main():
         out["per_workload"] = per
         if w["model"] in ("noise", "external"):
             out["fused_sync"] = fused_sync_probe(args.workload)
+            out["gradient_clipping"] = clip_probe(args.workload)
     out["cpu_baseline"] = None if args.no_cpu_baseline else cpu_baseline(w)
     print(json.dumps(out))
 

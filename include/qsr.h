@@ -102,6 +102,9 @@ typedef struct {
     double alpha;         /* growth coefficient of Eq. (2); 0 gives constant H = H_base    */
     double grad_sigma;    /* QSR_MODEL_NOISE: standard deviation of the gradient           */
     double data_sigma;    /* LINREG: observation noise; MLP2: input noise                  */
+    double clip_norm;     /* > 0: gradient clipping by global norm, per worker, before OPT (App. C):
+                             g_k <- g_k * min(1, clip_norm / (||g_k||_2 + 1e-6)); with parallel = 1
+                             it acts on the averaged gradient.  0 = off                     */
     uint64_t seed;        /* Philox4x32-10 key of all per-iteration draws                  */
     const int64_t *milestones; /* (host) ascending iteration indices, QSR_LR_STEP          */
     const double *eta_table;   /* (host) T entries, QSR_LR_TABLE                           */

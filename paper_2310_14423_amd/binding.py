@@ -40,7 +40,7 @@ class Config(C.Structure):
         ("momentum", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double),
         ("weight_decay", C.c_double), ("eta_max", C.c_double), ("eta_min", C.c_double),
         ("step_factor", C.c_double), ("alpha", C.c_double), ("grad_sigma", C.c_double),
-        ("data_sigma", C.c_double),
+        ("data_sigma", C.c_double), ("clip_norm", C.c_double),
         ("seed", C.c_uint64),
         ("milestones", C.c_void_p), ("eta_table", C.c_void_p), ("stream", C.c_void_p),
     ]
@@ -80,6 +80,7 @@ def make_config(w, stream=0, eta_table=None):
     c.t_swap_start = w.get("t_swap_start", 0)
     c.average_state = int(w.get("average_state", False))
     c.fuse_sync = int(w.get("fuse_sync", False))
+    c.clip_norm = float(w.get("clip_norm", 0.0))
     c.P = w["P"]; c.T = w["T"]; c.T_warm = w.get("T_warm", 0)
     c.B_loc = w.get("B_loc", 0); c.d_in = w.get("d_in", 0); c.d_hidden = w.get("d_hidden", 0)
     c.d_out = w.get("d_out", 0); c.n_blocks = w.get("n_blocks", 0)

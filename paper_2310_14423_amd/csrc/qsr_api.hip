@@ -42,6 +42,8 @@ struct qsr_ctx {
     StepScalars *d_scal;
     long long *d_log_t, *d_log_H;
     float *d_loss;
+    double *d_clip_part;     // gradient clipping: partial sums of squares, [K][blocks per row]
+    float *d_clip_coef;      // [K] factors, then [K] gradient norms
     // host mirrors
     std::vector<double> eta;
     DevState *h_state;       // pinned
@@ -86,6 +88,7 @@ extern "C" int qsr_validate(const qsr_config *c, const char **why)
     else if (c->fuse_sync != 0 && c->fuse_sync != 1) w = "fuse_sync";
     else if (c->fuse_sync == 1 && (c->parallel == 1 || c->average_state == 1)) w = "fuse_sync with parallel or average_state";
     else if (c->reserved != 0) w = "reserved";
+    else if (!finite_ge0(c->clip_norm)) w = "clip_norm";
     else if (c->power < 0 || c->power > 8) w = "power";
     else if (c->parallel != 0 && c->parallel != 1) w = "parallel";
     else if (c->parallel == 1 && (c->H_base != 1 || c->power != 0 || c->t_local_start != 0 || c->t_swap_start != 0))
@@ -238,6 +241,8 @@ static void free_ctx(qsr_ctx *c)
     if (c->d_log_t) (void)hipFree(c->d_log_t);
     if (c->d_log_H) (void)hipFree(c->d_log_H);
     if (c->d_loss) (void)hipFree(c->d_loss);
+    if (c->d_clip_part) (void)hipFree(c->d_clip_part);
+    if (c->d_clip_coef) (void)hipFree(c->d_clip_coef);
     if (c->h_state) (void)hipHostFree(c->h_state);
     delete c;
 }
@@ -257,6 +262,10 @@ static int init_impl(qsr_ctx *c, const float *theta0)
     HIP_TRY(hipMalloc((void **)&c->d_log_t, T * sizeof(long long)));
     HIP_TRY(hipMalloc((void **)&c->d_log_H, T * sizeof(long long)));
     HIP_TRY(hipMalloc((void **)&c->d_loss, (size_t)cfg.K * sizeof(float)));
+    if (cfg.clip_norm > 0.0) {
+        HIP_TRY(hipMalloc((void **)&c->d_clip_part, (size_t)cfg.K * clip_blocks_per_row(cfg.P) * sizeof(double)));
+        HIP_TRY(hipMalloc((void **)&c->d_clip_coef, 2 * (size_t)cfg.K * sizeof(float)));
+    }
     HIP_TRY(hipHostMalloc((void **)&c->h_state, sizeof(DevState), hipHostMallocDefault));
 
     std::vector<StepScalars> sc;
@@ -312,6 +321,7 @@ extern "C" int qsr_init(const qsr_config *cfg, float *params, float *grads, floa
     c->model_const = model_const; c->workspace = workspace; c->workspace_bytes = workspace_bytes;
     c->d_state = nullptr; c->d_eta = nullptr; c->d_scal = nullptr; c->d_log_t = nullptr;
     c->d_log_H = nullptr; c->d_loss = nullptr; c->h_state = nullptr;
+    c->d_clip_part = nullptr; c->d_clip_coef = nullptr;
     c->t_host = 0; c->need_sync_call = false; c->timing = false;
     c->dims = make_dims(cfg);
     rc = init_impl(c, theta0);
@@ -366,7 +376,6 @@ extern "C" int qsr_local_step(qsr_ctx *c)
     if (!c) return QSR_EINVAL;
     if (c->t_host >= c->cfg.T || c->need_sync_call) return QSR_ESTATE;
     const qsr_config &cfg = c->cfg;
-    const long long n = (long long)cfg.K * cfg.P;
 
     if (cfg.model != QSR_MODEL_EXTERNAL) {             // Eq. (1): every worker's local gradient
         Bracket br(c, 0);
@@ -404,13 +413,17 @@ extern "C" int qsr_local_step(qsr_ctx *c)
         Bracket br(c, 1);
         if (br.rc != QSR_OK) return br.rc;
         const bool fused = cfg.fuse_sync != 0;
+        if (cfg.clip_norm > 0.0)                        // App. C: per-worker factors min(1, c / (||g_k|| + 1e-6))
+            HIP_TRY(launch_clip_coef(c->grads, cfg.K, cfg.P, (float)cfg.clip_norm, c->d_clip_part,
+                                     c->d_clip_coef, c->d_clip_coef + cfg.K, c->stream));
         if (cfg.opt == QSR_OPT_SGDM)
-            HIP_TRY(launch_update_sgdm(c->params, c->grads, c->state0, n, c->d_state, c->d_scal,
-                                       (float)cfg.momentum, (float)cfg.weight_decay, fused, c->stream));
+            HIP_TRY(launch_update_sgdm(c->params, c->grads, c->state0, cfg.K, cfg.P, c->d_state, c->d_scal,
+                                       (float)cfg.momentum, (float)cfg.weight_decay, fused, c->d_clip_coef,
+                                       c->stream));
         else
-            HIP_TRY(launch_update_adamw(c->params, c->grads, c->state0, c->state1, n, c->d_state,
+            HIP_TRY(launch_update_adamw(c->params, c->grads, c->state0, c->state1, cfg.K, cfg.P, c->d_state,
                                         c->d_scal, (float)(1.0 - cfg.beta1), (float)(1.0 - cfg.beta2),
-                                        (float)cfg.eps, fused, c->stream));
+                                        (float)cfg.eps, fused, c->d_clip_coef, c->stream));
         int rc = br.close(c->t_host);
         if (rc != QSR_OK) return rc;
     }
@@ -419,11 +432,11 @@ extern "C" int qsr_local_step(qsr_ctx *c)
         if (br.rc != QSR_OK) return br.rc;
         if (cfg.opt == QSR_OPT_SGDM)
             HIP_TRY(launch_update_sgdm_sync(c->params, c->grads, c->state0, cfg.K, cfg.P, c->d_state, c->d_scal,
-                                            (float)cfg.momentum, (float)cfg.weight_decay, c->stream));
+                                            (float)cfg.momentum, (float)cfg.weight_decay, c->d_clip_coef, c->stream));
         else
             HIP_TRY(launch_update_adamw_sync(c->params, c->grads, c->state0, c->state1, cfg.K, cfg.P, c->d_state,
                                              c->d_scal, (float)(1.0 - cfg.beta1), (float)(1.0 - cfg.beta2),
-                                             (float)cfg.eps, c->stream));
+                                             (float)cfg.eps, c->d_clip_coef, c->stream));
         int rc = br.close(c->t_host + 1);
         if (rc != QSR_OK) return rc;
     }

@@ -60,20 +60,27 @@ hipError_t launch_sched_set(DevState *st, SchedParams sp, long long t, long long
                             hipStream_t s);
 hipError_t launch_sched_next_round(DevState *st, SchedParams sp, hipStream_t s);
 
-// fused_sync: leave the step that completes a round to launch_update_*_sync
-hipError_t launch_update_sgdm(float *theta, const float *g, float *buf, long long n,
+// fused_sync: leave the step that completes a round to launch_update_*_sync.
+// row_coef: K clipping factors the gradient rows are multiplied by as they are read, or nullptr.
+hipError_t launch_update_sgdm(float *theta, const float *g, float *buf, int K, long long P,
                               const DevState *st, const StepScalars *sc, float mu, float lambda,
-                              bool fused_sync, hipStream_t s);
-hipError_t launch_update_adamw(float *theta, const float *g, float *m, float *v, long long n,
+                              bool fused_sync, const float *row_coef, hipStream_t s);
+hipError_t launch_update_adamw(float *theta, const float *g, float *m, float *v, int K, long long P,
                                const DevState *st, const StepScalars *sc, float c1, float c2,
-                               float eps, bool fused_sync, hipStream_t s);
+                               float eps, bool fused_sync, const float *row_coef, hipStream_t s);
 // update + averaging in one pass over the [K][P] buffers, only on the step that completes a round
 hipError_t launch_update_sgdm_sync(float *theta, const float *g, float *buf, int K, long long P,
                                    const DevState *st, const StepScalars *sc, float mu, float lambda,
-                                   hipStream_t s);
+                                   const float *row_coef, hipStream_t s);
 hipError_t launch_update_adamw_sync(float *theta, const float *g, float *m, float *v, int K, long long P,
                                     const DevState *st, const StepScalars *sc, float c1, float c2,
-                                    float eps, hipStream_t s);
+                                    float eps, const float *row_coef, hipStream_t s);
+
+// gradient clipping: coef[k] = min(1, max_norm / (||g_k|| + 1e-6)), norm[k] = ||g_k||;
+// partial: K * clip_blocks_per_row(P) doubles of scratch
+int clip_blocks_per_row(long long P);
+hipError_t launch_clip_coef(const float *g, int K, long long P, float max_norm, double *partial, float *coef,
+                            float *norm, hipStream_t s);
 
 // mean over the K rows of buf [K][P], written to all rows; skipped on the device when
 // st != nullptr and st->do_sync == 0

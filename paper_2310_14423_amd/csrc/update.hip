@@ -20,12 +20,22 @@ __device__ __forceinline__ void stg_nt(float4 *p, float4 v) { st_nt4(p, v); }
 
 // `fused_sync`: the context folds the averaging into the last local step of a round (see the
 // *_sync kernels below), so the plain update leaves that step alone.
+// CLIP: the launch has one grid row per worker (blockIdx.y), n4 and n are one worker's row, and
+// the gradient is multiplied by that worker's clipping factor as it is read.
+template <bool CLIP>
 __global__ __launch_bounds__(UPD_THREADS) void update_adamw_kernel(
     float4 *__restrict__ theta, const float4 *__restrict__ g, float4 *__restrict__ m,
     float4 *__restrict__ v, long long n4, long long n, const DevState *__restrict__ st,
-    const StepScalars *__restrict__ sc, float c1, float c2, float eps, int fused_sync)
+    const StepScalars *__restrict__ sc, float c1, float c2, float eps, int fused_sync,
+    const float *__restrict__ row_coef)
 {
     if (fused_sync && st->h + 1 == st->H) return;
+    float gs = 1.0f;
+    if (CLIP) {
+        const long long off = (long long)blockIdx.y * n4;      // rows are 16-byte aligned here
+        theta += off; g += off; m += off; v += off;
+        gs = row_coef[blockIdx.y];
+    }
     const StepScalars s = sc[st->t];
     const long long stride = (long long)gridDim.x * UPD_THREADS * UPD_UNROLL;
     long long base = (long long)blockIdx.x * UPD_THREADS * UPD_UNROLL + threadIdx.x;
@@ -35,6 +45,7 @@ __global__ __launch_bounds__(UPD_THREADS) void update_adamw_kernel(
         for (int u = 0; u < UPD_UNROLL; ++u) {
             long long i = base + (long long)u * UPD_THREADS;
             if (i < n4) { a[u] = ldg_nt(theta + i); b[u] = ldg_nt(g + i); c[u] = ldg_nt(m + i); d[u] = ldg_nt(v + i); }
+            if (CLIP) { b[u].x *= gs; b[u].y *= gs; b[u].z *= gs; b[u].w *= gs; }
         }
 #pragma unroll
         for (int u = 0; u < UPD_UNROLL; ++u) {
@@ -49,7 +60,7 @@ __global__ __launch_bounds__(UPD_THREADS) void update_adamw_kernel(
         }
     }
     // ragged tail (n not a multiple of 4): at most 3 elements, done by the first threads
-    if (blockIdx.x == 0 && threadIdx.x < (int)(n - n4 * 4)) {
+    if (!CLIP && blockIdx.x == 0 && threadIdx.x < (int)(n - n4 * 4)) {
         long long i = n4 * 4 + threadIdx.x;
         float *th = (float *)theta, *mm = (float *)m, *vv = (float *)v;
         const float *gg = (const float *)g;
@@ -59,12 +70,20 @@ __global__ __launch_bounds__(UPD_THREADS) void update_adamw_kernel(
     }
 }
 
+template <bool CLIP>
 __global__ __launch_bounds__(UPD_THREADS) void update_sgdm_kernel(
     float4 *__restrict__ theta, const float4 *__restrict__ g, float4 *__restrict__ buf,
     long long n4, long long n, const DevState *__restrict__ st,
-    const StepScalars *__restrict__ sc, float mu, float lambda, int fused_sync)
+    const StepScalars *__restrict__ sc, float mu, float lambda, int fused_sync,
+    const float *__restrict__ row_coef)
 {
     if (fused_sync && st->h + 1 == st->H) return;
+    float gs = 1.0f;
+    if (CLIP) {
+        const long long off = (long long)blockIdx.y * n4;
+        theta += off; g += off; buf += off;
+        gs = row_coef[blockIdx.y];
+    }
     const float eta = sc[st->t].x;
     const long long stride = (long long)gridDim.x * UPD_THREADS * UPD_UNROLL;
     long long base = (long long)blockIdx.x * UPD_THREADS * UPD_UNROLL + threadIdx.x;
@@ -74,6 +93,7 @@ __global__ __launch_bounds__(UPD_THREADS) void update_sgdm_kernel(
         for (int u = 0; u < UPD_UNROLL; ++u) {
             long long i = base + (long long)u * UPD_THREADS;
             if (i < n4) { a[u] = ldg_nt(theta + i); b[u] = ldg_nt(g + i); c[u] = ldg_nt(buf + i); }
+            if (CLIP) { b[u].x *= gs; b[u].y *= gs; b[u].z *= gs; b[u].w *= gs; }
         }
 #pragma unroll
         for (int u = 0; u < UPD_UNROLL; ++u) {
@@ -87,7 +107,7 @@ __global__ __launch_bounds__(UPD_THREADS) void update_sgdm_kernel(
             }
         }
     }
-    if (blockIdx.x == 0 && threadIdx.x < (int)(n - n4 * 4)) {
+    if (!CLIP && blockIdx.x == 0 && threadIdx.x < (int)(n - n4 * 4)) {
         long long i = n4 * 4 + threadIdx.x;
         float *th = (float *)theta, *bb = (float *)buf;
         const float *gg = (const float *)g;
@@ -127,7 +147,7 @@ constexpr int SYNC_THREADS = 256;
 __global__ __launch_bounds__(SYNC_THREADS) void update_adamw_sync_kernel(
     float4 *__restrict__ theta, const float4 *__restrict__ g, float4 *__restrict__ m,
     float4 *__restrict__ v, int K, long long P4, const DevState *__restrict__ st,
-    const StepScalars *__restrict__ sc, float c1, float c2, float eps)
+    const StepScalars *__restrict__ sc, float c1, float c2, float eps, const float *__restrict__ row_coef)
 {
     if (st->h + 1 != st->H) return;
     const StepScalars s = sc[st->t];
@@ -142,6 +162,7 @@ __global__ __launch_bounds__(SYNC_THREADS) void update_adamw_sync_kernel(
                 if (k0 + u < K) {
                     const long long o = (long long)(k0 + u) * P4 + i;
                     a[u] = ldg_nt(theta + o); b[u] = ldg_nt(g + o); c[u] = ldg_nt(m + o); d[u] = ldg_nt(v + o);
+                    if (row_coef != nullptr) { const float gs = row_coef[k0 + u]; b[u].x *= gs; b[u].y *= gs; b[u].z *= gs; b[u].w *= gs; }
                 }
 #pragma unroll
             for (int u = 0; u < SYNC_ROWS; ++u)
@@ -165,7 +186,7 @@ __global__ __launch_bounds__(SYNC_THREADS) void update_adamw_sync_kernel(
 __global__ __launch_bounds__(SYNC_THREADS) void update_sgdm_sync_kernel(
     float4 *__restrict__ theta, const float4 *__restrict__ g, float4 *__restrict__ buf, int K,
     long long P4, const DevState *__restrict__ st, const StepScalars *__restrict__ sc, float mu,
-    float lambda)
+    float lambda, const float *__restrict__ row_coef)
 {
     if (st->h + 1 != st->H) return;
     const float eta = sc[st->t].x;
@@ -180,6 +201,7 @@ __global__ __launch_bounds__(SYNC_THREADS) void update_sgdm_sync_kernel(
                 if (k0 + u < K) {
                     const long long o = (long long)(k0 + u) * P4 + i;
                     a[u] = ldg_nt(theta + o); b[u] = ldg_nt(g + o); c[u] = ldg_nt(buf + o);
+                    if (row_coef != nullptr) { const float gs = row_coef[k0 + u]; b[u].x *= gs; b[u].y *= gs; b[u].z *= gs; b[u].w *= gs; }
                 }
 #pragma unroll
             for (int u = 0; u < SYNC_ROWS; ++u)
@@ -205,7 +227,7 @@ __global__ __launch_bounds__(SYNC_THREADS) void update_sgdm_sync_kernel(
 __global__ __launch_bounds__(SYNC_THREADS) void update_sync_scalar_kernel(
     float *__restrict__ theta, const float *__restrict__ g, float *__restrict__ m,
     float *__restrict__ v, int K, long long P, const DevState *__restrict__ st,
-    const StepScalars *__restrict__ sc, float c1, float c2, float eps)
+    const StepScalars *__restrict__ sc, float c1, float c2, float eps, const float *__restrict__ row_coef)
 {
     if (st->h + 1 != st->H) return;
     const StepScalars s = sc[st->t];
@@ -216,18 +238,45 @@ __global__ __launch_bounds__(SYNC_THREADS) void update_sync_scalar_kernel(
         for (int k = 0; k < K; ++k) {
             const long long o = (long long)k * P + i;
             float a = theta[o], c = m[o];
+            const float gk = row_coef != nullptr ? g[o] * row_coef[k] : g[o];
             if (v != nullptr) {
                 float d = v[o];
-                adamw_elem(a, g[o], c, d, s.x, s.y, s.z, c1, c2, eps);
+                adamw_elem(a, gk, c, d, s.x, s.y, s.z, c1, c2, eps);
                 v[o] = d;
             } else {
-                sgdm_elem(a, g[o], c, s.x, c1, c2);
+                sgdm_elem(a, gk, c, s.x, c1, c2);
             }
             m[o] = c;
             add_comp(acc, cmp, a);
         }
         const float mean = (acc + cmp) / fK;
         for (int k = 0; k < K; ++k) theta[(long long)k * P + i] = mean;
+    }
+}
+
+// clipped update of rows that are not 16-byte aligned (P not a multiple of 4): one element per
+// lane, one grid row per worker (v == nullptr: SGD with momentum, c1 = mu, c2 = lambda)
+__global__ __launch_bounds__(SYNC_THREADS) void update_clip_scalar_kernel(
+    float *__restrict__ theta, const float *__restrict__ g, float *__restrict__ m,
+    float *__restrict__ v, long long P, const DevState *__restrict__ st,
+    const StepScalars *__restrict__ sc, float c1, float c2, float eps, int fused_sync,
+    const float *__restrict__ row_coef)
+{
+    if (fused_sync && st->h + 1 == st->H) return;
+    const StepScalars s = sc[st->t];
+    const float gs = row_coef[blockIdx.y];
+    const long long stride = (long long)gridDim.x * SYNC_THREADS;
+    for (long long i = (long long)blockIdx.x * SYNC_THREADS + threadIdx.x; i < P; i += stride) {
+        const long long o = (long long)blockIdx.y * P + i;
+        float a = theta[o], c = m[o];
+        if (v != nullptr) {
+            float d = v[o];
+            adamw_elem(a, g[o] * gs, c, d, s.x, s.y, s.z, c1, c2, eps);
+            v[o] = d;
+        } else {
+            sgdm_elem(a, g[o] * gs, c, s.x, c1, c2);
+        }
+        theta[o] = a; m[o] = c;
     }
 }
 
@@ -242,46 +291,66 @@ static int sync_grid(long long items)
 
 hipError_t launch_update_adamw_sync(float *theta, const float *g, float *m, float *v, int K, long long P,
                                     const DevState *st, const StepScalars *sc, float c1, float c2,
-                                    float eps, hipStream_t s)
+                                    float eps, const float *row_coef, hipStream_t s)
 {
     if ((P & 3) == 0)
         update_adamw_sync_kernel<<<sync_grid(P / 4), SYNC_THREADS, 0, s>>>(
-            (float4 *)theta, (const float4 *)g, (float4 *)m, (float4 *)v, K, P / 4, st, sc, c1, c2, eps);
+            (float4 *)theta, (const float4 *)g, (float4 *)m, (float4 *)v, K, P / 4, st, sc, c1, c2, eps, row_coef);
     else
-        update_sync_scalar_kernel<<<sync_grid(P), SYNC_THREADS, 0, s>>>(theta, g, m, v, K, P, st, sc, c1, c2, eps);
+        update_sync_scalar_kernel<<<sync_grid(P), SYNC_THREADS, 0, s>>>(theta, g, m, v, K, P, st, sc, c1, c2, eps,
+                                                                        row_coef);
     return hipGetLastError();
 }
 
 hipError_t launch_update_sgdm_sync(float *theta, const float *g, float *buf, int K, long long P,
                                    const DevState *st, const StepScalars *sc, float mu, float lambda,
-                                   hipStream_t s)
+                                   const float *row_coef, hipStream_t s)
 {
     if ((P & 3) == 0)
         update_sgdm_sync_kernel<<<sync_grid(P / 4), SYNC_THREADS, 0, s>>>(
-            (float4 *)theta, (const float4 *)g, (float4 *)buf, K, P / 4, st, sc, mu, lambda);
+            (float4 *)theta, (const float4 *)g, (float4 *)buf, K, P / 4, st, sc, mu, lambda, row_coef);
     else
         update_sync_scalar_kernel<<<sync_grid(P), SYNC_THREADS, 0, s>>>(theta, g, buf, nullptr, K, P, st, sc, mu,
-                                                                       lambda, 0.f);
+                                                                        lambda, 0.f, row_coef);
     return hipGetLastError();
 }
 
-hipError_t launch_update_adamw(float *theta, const float *g, float *m, float *v, long long n,
+// row_coef != nullptr: clipped update, one grid row per worker
+hipError_t launch_update_adamw(float *theta, const float *g, float *m, float *v, int K, long long P,
                                const DevState *st, const StepScalars *sc, float c1, float c2,
-                               float eps, bool fused_sync, hipStream_t s)
+                               float eps, bool fused_sync, const float *row_coef, hipStream_t s)
 {
-    long long n4 = n / 4;
-    update_adamw_kernel<<<update_grid(n4), UPD_THREADS, 0, s>>>(
-        (float4 *)theta, (const float4 *)g, (float4 *)m, (float4 *)v, n4, n, st, sc, c1, c2, eps, fused_sync ? 1 : 0);
+    const int fs = fused_sync ? 1 : 0;
+    if (row_coef == nullptr) {
+        const long long n = (long long)K * P, n4 = n / 4;
+        update_adamw_kernel<false><<<update_grid(n4), UPD_THREADS, 0, s>>>(
+            (float4 *)theta, (const float4 *)g, (float4 *)m, (float4 *)v, n4, n, st, sc, c1, c2, eps, fs, nullptr);
+    } else if ((P & 3) == 0) {
+        update_adamw_kernel<true><<<dim3((unsigned)update_grid(P / 4), (unsigned)K), UPD_THREADS, 0, s>>>(
+            (float4 *)theta, (const float4 *)g, (float4 *)m, (float4 *)v, P / 4, P, st, sc, c1, c2, eps, fs, row_coef);
+    } else {
+        update_clip_scalar_kernel<<<dim3((unsigned)sync_grid(P), (unsigned)K), SYNC_THREADS, 0, s>>>(
+            theta, g, m, v, P, st, sc, c1, c2, eps, fs, row_coef);
+    }
     return hipGetLastError();
 }
 
-hipError_t launch_update_sgdm(float *theta, const float *g, float *buf, long long n,
+hipError_t launch_update_sgdm(float *theta, const float *g, float *buf, int K, long long P,
                               const DevState *st, const StepScalars *sc, float mu, float lambda,
-                              bool fused_sync, hipStream_t s)
+                              bool fused_sync, const float *row_coef, hipStream_t s)
 {
-    long long n4 = n / 4;
-    update_sgdm_kernel<<<update_grid(n4), UPD_THREADS, 0, s>>>(
-        (float4 *)theta, (const float4 *)g, (float4 *)buf, n4, n, st, sc, mu, lambda, fused_sync ? 1 : 0);
+    const int fs = fused_sync ? 1 : 0;
+    if (row_coef == nullptr) {
+        const long long n = (long long)K * P, n4 = n / 4;
+        update_sgdm_kernel<false><<<update_grid(n4), UPD_THREADS, 0, s>>>(
+            (float4 *)theta, (const float4 *)g, (float4 *)buf, n4, n, st, sc, mu, lambda, fs, nullptr);
+    } else if ((P & 3) == 0) {
+        update_sgdm_kernel<true><<<dim3((unsigned)update_grid(P / 4), (unsigned)K), UPD_THREADS, 0, s>>>(
+            (float4 *)theta, (const float4 *)g, (float4 *)buf, P / 4, P, st, sc, mu, lambda, fs, row_coef);
+    } else {
+        update_clip_scalar_kernel<<<dim3((unsigned)sync_grid(P), (unsigned)K), SYNC_THREADS, 0, s>>>(
+            theta, g, buf, nullptr, P, st, sc, mu, lambda, 0.f, fs, row_coef);
+    }
     return hipGetLastError();
 }
 

@@ -554,6 +554,36 @@ def test_fused_sync_on_noise_workload():
     ctx.close()
 
 
+@pytest.mark.parametrize("opt", ["adamw", "sgdm"])
+@pytest.mark.parametrize("K,P,extra", [(4, 65536 + 8, {}), (3, 4099, {}), (4, 30000, dict(fuse_sync=True)),
+                                       (3, 1001, dict(fuse_sync=True)),
+                                       (4, 20000, dict(parallel=True, H_base=1, power=0, alpha=0.0))])
+def test_gradient_clipping(opt, K, P, extra):
+    """Clipping by global norm per worker (App. C): gradients far above, around and below the
+    threshold; aligned and unaligned rows; with the fused synchronization and with Parallel OPT
+    (where the averaged gradient is clipped)."""
+    import torch
+    kw = dict(mu=0.9, lam=1e-3) if opt == "sgdm" else dict(beta1=0.9, beta2=0.99, eps=1e-8, lam=0.01)
+    T = 24
+    base = dict(H_base=2, alpha=0.08)
+    base.update(extra)
+    w = _ext_workload(opt, K, P, T, T_warm=3, clip_norm=2.0, **base, **kw)
+    rng = np.random.default_rng(K * 7 + P)
+    th0 = rng.standard_normal(P).astype(np.float32)
+    ctx = gpu_ctx(w, theta0=th0)
+    orc = oracle_run(w, theta0=th0)
+    for t in range(T):
+        # norms of about 0.02, 2 and 60 against the threshold 2, different per worker
+        scale = rng.choice([0.02, 2.0, 60.0], size=(K, 1)) / np.sqrt(P)
+        g = (rng.standard_normal((K, P)) * scale).astype(np.float32)
+        ctx.grads.copy_(torch.from_numpy(g))
+        ctx.step(); orc.step(1, ext_g=g[None].astype(np.float64))
+    assert list(ctx.read_sync_log()[0]) == list(orc.sync_log)
+    assert_params_close(ctx.params.cpu().numpy(), orc.theta, what="clipped params")
+    assert_params_close(ctx.state0.cpu().numpy(), orc.st0, rtol=1e-4, what="clipped state0")
+    ctx.close()
+
+
 def test_checkpoint_and_resume():
     """Stop after 700 of 2000 iterations (inside a round), restore buffers and scheduler state in a
     fresh context, finish: bit-identical to the uninterrupted run, and the log continues."""
