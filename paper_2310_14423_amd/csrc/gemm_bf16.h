@@ -51,8 +51,9 @@ struct GemmNT {
 // so that 16 consecutive lanes hold one row's consecutive columns: whole 128- or 256-byte row
 // segments per global instruction (N must be a multiple of 4).  Rows are padded by 16 B:
 // conflict-free both ways.  The functor has two parts, so that what it reads from global memory
-// is requested before the LDS round trip and arrives during it:
-//     Aux  epi.pre(z, m, n)            -- loads for C[z][m][n..n+3] (may be empty)
+// can be requested one 32-row block ahead of its use:
+//     Aux  epi.pre(z, m, n)            -- loads for C[z][m][n..n+3] (may be empty; also called
+//                                         with coordinates clamped into the matrix, N >= 4)
 //     void epi(z, m, n, v[4], aux)     -- consumes the accumulators and stores
 struct NoAux {};
 
