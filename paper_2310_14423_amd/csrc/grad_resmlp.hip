@@ -28,7 +28,7 @@ struct ResWs {
     // per-replica strides are the element counts of one replica's array
     float *X;      long long sX;       // [L+1][M][d]
     float *MU, *RSTD; long long sStat; // [L][M]
-    bf16_t *H;     long long sH;       // [L][M][dh]  pre-GELU
+    bf16_t *H;     long long sH;       // [L][M][dh]  gelu'(pre-activation)
     bf16_t *U;     long long sU;       // [L][M][d]   LayerNorm output
     bf16_t *A;     long long sA;       // [L][M][dh]  GELU output
     float *Y;      long long sY;       // [M][d]
@@ -392,7 +392,10 @@ struct EpiScaleF32 {             // C = scale * acc
                make_float4(v[0] * scale, v[1] * scale, v[2] * scale, v[3] * scale));
     }
 };
-struct EpiBiasGelu {             // h = acc + b1; H = bf16(h); A = bf16(gelu(h))
+struct EpiBiasGelu {             // h = acc + b1; H = bf16(gelu'(h)); A = bf16(gelu(h))
+    // The backward pass needs h only through gelu'(h) = Phi(h) + h phi(h), and both factors are at
+    // hand here: storing the derivative instead of h costs two instructions per element now and
+    // saves the whole GELU evaluation in the data-gradient epilogue.
     const float *bias; long long sBias; bf16_t *H; long long sH; bf16_t *A; long long sA; long long ld;
     typedef NoAux Aux;
     __device__ Aux pre(int, int, int) const { return Aux{}; }
@@ -400,11 +403,16 @@ struct EpiBiasGelu {             // h = acc + b1; H = bf16(h); A = bf16(gelu(h))
     {
         const float4 b = *(const float4 *)(bias + (long long)z * sBias + n);
         const float h[4] = {v[0] + b.x, v[1] + b.y, v[2] + b.z, v[3] + b.w};
-        float a[4];
+        float a[4], dg[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) { float c, pdf; gelu_parts(h[i], c, pdf); a[i] = h[i] * c; }
+        for (int i = 0; i < 4; ++i) {
+            float c, pdf;
+            gelu_parts(h[i], c, pdf);
+            a[i] = h[i] * c;
+            dg[i] = fmaf(h[i], pdf, c);
+        }
         const long long o = (long long)m * ld + n;
-        __builtin_nontemporal_store(pack4(h[0], h[1], h[2], h[3]), (bf16x4 *)(H + (long long)z * sH + o));
+        __builtin_nontemporal_store(pack4(dg[0], dg[1], dg[2], dg[3]), (bf16x4 *)(H + (long long)z * sH + o));
         __builtin_nontemporal_store(pack4(a[0], a[1], a[2], a[3]), (bf16x4 *)(A + (long long)z * sA + o));
     }
 };
@@ -422,7 +430,7 @@ struct EpiBiasResidual {         // x_out = x_in + acc + b2
         st_nt4((float4 *)(Xout + o), make_float4(x.x + v[0] + b.x, x.y + v[1] + b.y, x.z + v[2] + b.z, x.w + v[3] + b.w));
     }
 };
-struct EpiGeluBwd {              // dh = acc * gelu'(h)
+struct EpiGeluBwd {              // dh = acc * gelu'(h), H holding gelu'(h) from the forward pass
     const bf16_t *H; long long sH; bf16_t *DH; long long sDH; long long ld;
     typedef bf16x4 Aux;
     __device__ Aux pre(int z, int m, int n) const
@@ -433,12 +441,7 @@ struct EpiGeluBwd {              // dh = acc * gelu'(h)
     {
         float r[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float h = (float)hb[i];
-            float c, pdf;
-            gelu_parts(h, c, pdf);
-            r[i] = v[i] * fmaf(h, pdf, c);
-        }
+        for (int i = 0; i < 4; ++i) r[i] = v[i] * (float)hb[i];
         __builtin_nontemporal_store(pack4(r[0], r[1], r[2], r[3]), (bf16x4 *)(DH + (long long)z * sDH + (long long)m * ld + n));
     }
 };

@@ -339,7 +339,9 @@ def test_resmlp_mid_size_gradient():
 def test_resmlp_weight_gradient_many_tiles():
     """Full-width layer (768 x 3072) with 9 workers: 288 weight-gradient tiles of 192 x 384 for 256
     persistent workgroups, so some of them walk two tiles; the token count (200) leaves a ragged
-    last reduction slab."""
+    last reduction slab.  The weight groups have 2.4 million entries each: the 2e-2 bound is about
+    five standard deviations of the bf16 rounding noise of their dot products, so one entry in
+    100 000 may pass it, none by more than half."""
     dims = dict(d_in=768, d_hidden=3072, n_blocks=1, B_loc=200, K=9)
     w = workloads.get("resmlp", T=4, T_warm=1, **dims)
     ctx = gpu_ctx(w)
@@ -352,7 +354,8 @@ def test_resmlp_weight_gradient_many_tiles():
         want, wl = orc.grad(k, 0, th0)
         assert loss[k] == pytest.approx(wl, rel=1e-2)
         for name, sl in _resmlp_groups(w):
-            assert_params_close(g[k, sl], want[sl], rtol=RTOL_BF16, what="resmlp wide grad %s k=%d" % (name, k))
+            assert_params_close(g[k, sl], want[sl], rtol=RTOL_BF16, tail=(1e-5, 1.5),
+                                what="resmlp wide grad %s k=%d" % (name, k))
     ctx.close()
 
 

@@ -48,7 +48,10 @@ def gpu_ctx(w, theta0=None, eta_table=None):
 RTOL_F32 = 1e-5
 
 
-def assert_params_close(gpu, orc, rtol=RTOL_F32, what=""):
+def assert_params_close(gpu, orc, rtol=RTOL_F32, what="", tail=None):
+    """Every entry within rtol * (|oracle| + rms(oracle)).  tail = (fraction, factor): that fraction
+    of the entries may exceed the bound, none by more than the factor (for groups of millions of
+    bf16 dot products, where the bound is about five standard deviations of the rounding noise)."""
     gpu = np.asarray(gpu, dtype=np.float64)
     orc = np.asarray(orc, dtype=np.float64)
     assert gpu.shape == orc.shape
@@ -56,7 +59,11 @@ def assert_params_close(gpu, orc, rtol=RTOL_F32, what=""):
     rms = np.sqrt(np.mean(orc * orc))
     err = np.abs(gpu - orc)
     bound = rtol * (np.abs(orc) + rms)
-    worst = np.max(err - bound)
-    assert worst <= 0, "%s: max |diff| %.3e, max ratio to bound %.3f (rms %.3e)" % (
-        what, err.max(), np.max(err / np.maximum(bound, 1e-300)), rms)
+    ratio = err / np.maximum(bound, 1e-300)
+    msg = "%s: max |diff| %.3e, max ratio to bound %.3f (rms %.3e)" % (what, err.max(), ratio.max(), rms)
+    if tail is None:
+        assert ratio.max() <= 1.0, msg
+    else:
+        frac, factor = tail
+        assert ratio.max() <= factor and np.count_nonzero(ratio > 1.0) <= frac * ratio.size, msg
     return float(np.max(err / np.maximum(bound, 1e-300)))
