@@ -294,9 +294,21 @@ __global__ __launch_bounds__(256) void colsum_final_kernel(const float *__restri
     out += (long long)blockIdx.z * cols;
     const int per = (chunks + 3) / 4;
     const int c0 = wave * per, c1 = min(chunks, c0 + per);
-    float acc = 0.f;
-    if (j < cols)
-        for (int c = c0; c < c1; ++c) acc += p[(long long)c * cols + j];
+    // 8 independent partial sums per lane (rows c0+u, c0+u+8, ...), so that 8 loads are in flight;
+    // combined in a fixed order
+    float a8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (j < cols) {
+        int c = c0;
+        for (; c + 8 <= c1; c += 8) {
+            float r[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) r[u] = p[(long long)(c + u) * cols + j];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) a8[u] += r[u];
+        }
+        for (int u = 0; c < c1; ++c, ++u) a8[u] += p[(long long)c * cols + j];
+    }
+    const float acc = ((a8[0] + a8[1]) + (a8[2] + a8[3])) + ((a8[4] + a8[5]) + (a8[6] + a8[7]));
     red[wave][lane] = acc;
     __syncthreads();
     if (wave == 0 && j < cols)
