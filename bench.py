@@ -170,7 +170,7 @@ def run_workload(name, steps, warmup, kernel_timing=True):
         "value": K * P * steps / dt, "steps": steps, "ms_per_step": dt * 1e3 / steps,
         "dtype": "bf16" if w["model"] == "resmlp" else "f32",
         "config": {"workload": name, "K": K, "P": P, "T": T, "optimizer": w["opt"],
-                   "model": w["model"], "H_base": w["H_base"], "alpha": w["alpha"],
+                   "gradient": w["model"], "H_base": w["H_base"], "alpha": w["alpha"],
                    "lr": w["lr"], "eta_max": w["eta_max"]},
         "sync_rounds": rounds,
         "hbm_GBs_update": kernels.get("update_GBs"),
@@ -254,7 +254,7 @@ def main():
                     help="do not add the short runs of the four other workloads (per_workload)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (K simulated workers on one MI355X); "
+        print("bench.py: the K workers are simulated on ONE GPU; "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
