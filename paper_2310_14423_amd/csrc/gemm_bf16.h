@@ -40,9 +40,10 @@ struct GemmNT {
     int M, N, K;
     long long lda, ldb;
     long long sA, sB;      // per-batch strides (elements)
-    float *colsum_B;       // TN form only, optional: colsum_B[z*s_colsum + n] = sum_k B[z][k][n]
+    // TN form (gemm_pp.h) only:
+    float *colsum_B;       // optional: colsum_B[z*s_colsum + n] = sum_k B[z][k][n]
     long long s_colsum;
-    const bf16_t *zeros;   // TN form of gemm_pp.h only: 64 bytes of zeros, read in place of k-rows beyond K
+    const bf16_t *zeros;   // 64 bytes of zeros, read in place of k-rows beyond K (needed if K % 32 != 0)
 };
 
 // Epilogue.  The MFMA leaves lane l with 4 consecutive columns of row l%32, i.e. one store
@@ -242,150 +243,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_bf16_kernel(GemmNT p, Ep
                              m0 + wm * TM * 32, n0 + wn * TN * 32, p.M, p.N, z, epi);
 }
 
-// "TN" form for the weight gradients: both operands are stored with the reduction axis as the
-// ROW index (activations [tokens][features], features contiguous),
-//
-//     C[z][m][n] = sum_k A[z][k][m] * B[z][k][n]
-//
-// so the 8 consecutive k a lane needs lie in 8 different rows.  The slabs are staged in LDS as
-// they are in memory ([BK tokens][features]) and the fragments are fetched with the gfx950 LDS
-// transpose read (ds_read_b64_tr_b16): within each group of 16 lanes, lane j receives element
-// j%4 of the 64-bit words addressed by lanes j/4, j/4+4, j/4+8, j/4+12 of the group (checked on
-// the hardware).  Pointing lane r = q + 4e of a group at token e, features 4q..4q+3 of a
-// 4-token x 16-feature block therefore hands lane j feature j and the 4 tokens in order; two
-// such reads give the 8 k values of an MFMA operand, and the four groups of a wavefront cover
-// 32 features x 16 tokens in exactly the instruction's operand layout.  K (tokens) may be
-// ragged: rows beyond it are zero-filled.  M and N must be multiples of 8.
-// By-product: the workgroups of the first M-tile also add up the columns of the B slabs as they
-// pass through LDS (sum over tokens, fixed order), which yields the bias gradient that goes
-// with each weight gradient without another pass over the activations.
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-
-template <int BM, int BN, int BK, int WM, int WN, class Epi>
-__global__ __launch_bounds__(WM * WN * 64) void gemm_tn_bf16_kernel(GemmNT p, Epi epi)
-{
-    constexpr int NT = WM * WN * 64;
-    constexpr int LDA = BM + 32, LDB = BN + 32;    // row stride = 64 B mod 256 B: conflict-free
-    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
-    constexpr int A_PIECES = BK * (BM / 8) / NT, B_PIECES = BK * (BN / 8) / NT;
-    static_assert(BK * (BM / 8) % NT == 0 && BK * (BN / 8) % NT == 0, "tile / thread mismatch");
-
-    extern __shared__ __attribute__((aligned(16))) unsigned char gemm_smem[];
-    bf16_t(*As)[BK * LDA] = (bf16_t(*)[BK * LDA])gemm_smem;
-    bf16_t(*Bs)[BK * LDB] = (bf16_t(*)[BK * LDB])(gemm_smem + 2 * BK * LDA * sizeof(bf16_t));
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WN, wn = wave % WN;
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-    const int z = blockIdx.z;
-    const bf16_t *A = p.A + (long long)z * p.sA;
-    const bf16_t *B = p.B + (long long)z * p.sB;
-
-    uint4 ra[A_PIECES], rb[B_PIECES];
-    auto load_global = [&](int k0) {
-#pragma unroll
-        for (int i = 0; i < A_PIECES; ++i) {
-            int pc = tid + i * NT, row = pc / (BM / 8), c = pc % (BM / 8);
-            int gk = k0 + row, gm = m0 + c * 8;
-            ra[i] = (gk < p.K && gm < p.M) ? *(const uint4 *)(A + (long long)gk * p.lda + gm)
-                                           : make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int i = 0; i < B_PIECES; ++i) {
-            int pc = tid + i * NT, row = pc / (BN / 8), c = pc % (BN / 8);
-            int gk = k0 + row, gn = n0 + c * 8;
-            rb[i] = (gk < p.K && gn < p.N) ? *(const uint4 *)(B + (long long)gk * p.ldb + gn)
-                                           : make_uint4(0, 0, 0, 0);
-        }
-    };
-    auto store_lds = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < A_PIECES; ++i) {
-            int pc = tid + i * NT, row = pc / (BM / 8), c = pc % (BM / 8);
-            *(uint4 *)(&As[buf][row * LDA + c * 8]) = ra[i];
-        }
-#pragma unroll
-        for (int i = 0; i < B_PIECES; ++i) {
-            int pc = tid + i * NT, row = pc / (BN / 8), c = pc % (BN / 8);
-            *(uint4 *)(&Bs[buf][row * LDB + c * 8]) = rb[i];
-        }
-    };
-    // lane's place in the transpose reads: token offset and feature offset inside a
-    // 16-token x 32-feature operand block
-    const int grp = lane >> 4, r16 = lane & 15;
-    const int tok_off = (grp >> 1) * 8 + (r16 >> 2), feat_off = (grp & 1) * 16 + (r16 & 3) * 4;
-    auto frag = [&](const bf16_t *tile, int ld, int kbase, int fbase) {
-        typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-        const bf16_t *q0 = tile + (kbase + tok_off) * ld + fbase + feat_off;
-        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)q0);
-        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(q0 + 4 * ld));
-        union { struct { s16x4 a, b; } s; bf16x8 v; } u;
-        u.s.a = lo; u.s.b = hi;
-        return u.v;
-    };
-
-    f32x16 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
-    const int nk = (p.K + BK - 1) / BK;
-    // column sums of B: thread = (column pair, token group); groups are combined at the end
-    constexpr int CS_PAIRS = BN / 2, CS_GROUPS = NT / CS_PAIRS, CS_TOK = BK / CS_GROUPS;
-    static_assert(NT % CS_PAIRS == 0 && BK % CS_GROUPS == 0, "column-sum layout");
-    const bool do_colsum = p.colsum_B != nullptr && blockIdx.y == 0;
-    const int cs_pair = tid % CS_PAIRS, cs_grp = tid / CS_PAIRS;
-    float csum0 = 0.f, csum1 = 0.f;
-    load_global(0);
-    store_lds(0);
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < nk) load_global((kt + 1) * BK);
-        if (do_colsum) {
-#pragma unroll
-            for (int k = 0; k < CS_TOK; ++k) {
-                const uint32_t two = *(const uint32_t *)(&Bs[cur][(cs_grp * CS_TOK + k) * LDB + 2 * cs_pair]);
-                csum0 += __uint_as_float(two << 16);            // bf16 -> fp32 is a 16-bit shift
-                csum1 += __uint_as_float(two & 0xffff0000u);
-            }
-        }
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 fa[TM], fb[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) fa[i] = frag(As[cur], LDA, ks * 16, wm * TM * 32 + i * 32);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) fb[j] = frag(Bs[cur], LDB, ks * 16, wn * TN * 32 + j * 32);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
-        }
-        if (kt + 1 < nk) store_lds(cur ^ 1);
-        __syncthreads();
-    }
-    if (do_colsum) {                                   // all slabs are consumed: LDS is free
-        float *red = (float *)gemm_smem;               // [CS_GROUPS][BN]
-        red[cs_grp * BN + 2 * cs_pair] = csum0;
-        red[cs_grp * BN + 2 * cs_pair + 1] = csum1;
-        __syncthreads();
-        if (tid < BN && n0 + tid < p.N) {
-            float t = 0.f;
-#pragma unroll
-            for (int q = 0; q < CS_GROUPS; ++q) t += red[q * BN + tid];
-            p.colsum_B[(long long)z * p.s_colsum + n0 + tid] = t;
-        }
-    }
-
-    __syncthreads();                                   // every wavefront is done with the slabs
-    epilogue_via_lds<TM, TN>(acc, (float *)gemm_smem + wave * (32 * (TN * 32 + 4)), lane,
-                             m0 + wm * TM * 32, n0 + wn * TN * 32, p.M, p.N, z, epi);
-}
+typedef short s16x4 __attribute__((ext_vector_type(4)));   // operand of the LDS transpose read
 
 template <int BM, int BN, int BK, int WM, int WN, class Epi>
 inline hipError_t launch_gemm_nt(const GemmNT &p, const Epi &epi, int batch, hipStream_t s)
@@ -403,24 +261,6 @@ inline hipError_t launch_gemm_nt(const GemmNT &p, const Epi &epi, int batch, hip
         lds_limit_raised = true;
     }
     kern<<<grid, WM * WN * 64, smem, s>>>(p, epi, batch);
-    return hipGetLastError();
-}
-
-template <int BM, int BN, int BK, int WM, int WN, class Epi>
-inline hipError_t launch_gemm_tn(const GemmNT &p, const Epi &epi, int batch, hipStream_t s)
-{
-    dim3 grid((unsigned)((p.N + BN - 1) / BN), (unsigned)((p.M + BM - 1) / BM), (unsigned)batch);
-    constexpr size_t smem = 2 * (size_t)BK * (BM + 32 + BN + 32) * sizeof(bf16_t);
-    static_assert(smem <= 160 * 1024, "tile does not fit the 160 KB LDS");
-    static_assert((size_t)WM * WN * 32 * (BN / WN + 4) * sizeof(float) <= smem, "epilogue staging does not fit the slab buffers");
-    auto kern = gemm_tn_bf16_kernel<BM, BN, BK, WM, WN, Epi>;
-    static bool lds_limit_raised = false;     // per instantiation; contexts are not thread-safe
-    if (smem > 64 * 1024 && !lds_limit_raised) {
-        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        lds_limit_raised = true;
-    }
-    kern<<<grid, WM * WN * 64, smem, s>>>(p, epi);
     return hipGetLastError();
 }
 

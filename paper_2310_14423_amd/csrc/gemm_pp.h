@@ -3,8 +3,17 @@
 //
 //     C[z][m][n] = sum_k A[z][k][m] * B[z][k][n]      (both operands stored [k][feature], k = token)
 //
-// with the conventions of gemm_tn_bf16_kernel in gemm_bf16.h (which stays as the fall-back).
-// What differs, and why (measured on MI355X: 768 x 3072 outputs, 12608 tokens, 8 workers):
+// so the 8 consecutive k a lane of the MFMA needs lie in 8 different rows.  The slabs are staged in
+// LDS as they are in memory (tokens x features) and the fragments are fetched with the gfx950 LDS
+// transpose read (ds_read_b64_tr_b16): within each group of 16 lanes, lane j receives element
+// j%4 of the 64-bit words addressed by lanes j/4, j/4+4, j/4+8, j/4+12 of the group (checked on
+// the hardware).  Pointing lane r = q + 4e of a group at token e, features 4q..4q+3 of a
+// 4-token x 16-feature block therefore hands lane j feature j and the 4 tokens in order; two
+// such reads give the 8 k values of an MFMA operand, and the four groups of a wavefront cover
+// 32 features x 16 tokens in exactly the instruction's operand layout.
+// Design, and what it was measured against (MI355X: 768 x 3072 outputs, 12608 tokens, 8 workers; a
+// first version with 128 x 128 tiles, register-staged copies and a common barrier per slab took
+// 743 us per launch, this one 434):
 //
 //  * Tiles of 192 x 384 (wavefront 96 x 96).  768 x 3072 outputs per worker are 32 such tiles, so
 //    8 workers fill the 256 compute units exactly once: no tail, and per multiply-add half the
@@ -120,7 +129,7 @@ __global__ __launch_bounds__(512) void gemm_pp_tn_kernel(GemmNT p, Epi epi, int 
 
     f32x16 acc[TM][TN];
     bf16x8 fa[2][TM], fb[2][TN];
-    // lane's place in the transpose reads (see gemm_tn_bf16_kernel): token and feature offset
+    // lane's place in the transpose reads: token and feature offset
     // inside a 16-token x 32-feature operand block
     const int grp = lane >> 4, r16 = lane & 15;
     const int tok_off = (grp >> 1) * 8 + (r16 >> 2), feat_off = (grp & 1) * 16 + (r16 & 3) * 4;
@@ -240,7 +249,7 @@ __global__ __launch_bounds__(512) void gemm_pp_tn_kernel(GemmNT p, Epi epi, int 
     }
 }
 
-// Whether launch_gemm_pp_tn can take the problem (otherwise gemm_tn_bf16_kernel does).
+// Whether launch_gemm_pp_tn can take the problem.
 inline bool gemm_pp_tn_supports(const GemmNT &p)
 {
     if (p.K < 1 || p.lda % 8 != 0 || p.ldb % 8 != 0) return false;

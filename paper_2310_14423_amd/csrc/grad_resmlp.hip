@@ -466,9 +466,8 @@ struct EpiGeluBwd {              // dh = acc * gelu'(h), H holding gelu'(h) from
 // 4 % slower: they fetch 1.5 times the bytes from L2, which is what bounds the main loop).
 // The weight gradients (768 x 3072 outputs per worker, reduction over the tokens) go to the
 // persistent two-group kernel of gemm_pp.h, whose 192x384 tiles make exactly 256 workgroups for 8
-// workers; 128x128x64 tiles of the plain kernel remain as the fall-back.
+// workers.
 #define QSR_GEMM_BIG 256, 256, 64, 2, 4
-#define QSR_GEMM_WGRAD 128, 128, 64, 2, 2
 
 // NT: the plain tiled kernel (the persistent one timed the same to slower here: a workgroup that
 // goes on to its next tile must first see its epilogue's stores complete, where a fresh workgroup
@@ -481,8 +480,10 @@ static hipError_t gemm_nt(const GemmNT &p, const Epi &epi, int batch, hipStream_
 template <class Epi>
 static hipError_t gemm_tn(const GemmNT &p, const Epi &epi, int batch, hipStream_t s)
 {
-    if (gemm_pp_tn_supports(p)) return launch_gemm_pp_tn(p, epi, batch, s);
-    return launch_gemm_tn<QSR_GEMM_WGRAD>(p, epi, batch, s);
+    // widths are multiples of 64 and a block of zeros stands in for ragged token counts, so every
+    // weight gradient of this model qualifies
+    if (!gemm_pp_tn_supports(p)) return hipErrorInvalidValue;
+    return launch_gemm_pp_tn(p, epi, batch, s);
 }
 
 #define TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return e_; } while (0)
