@@ -96,7 +96,9 @@ __global__ __launch_bounds__(256) void mlp2_softmax_ce_kernel(float *__restrict_
     if (threadIdx.x == 0) loss[k] = (red[0] + red[1] + red[2] + red[3]) * invB;
 }
 
-// out[k][j] = sum_i A[k][i][j]   (bias gradients)
+// out[k][j] = sum_i A[k][i][j]   (bias gradients).  One thread per column, rows added in ascending
+// order; eight loads are in flight at a time, since the launch has too few wavefronts to hide the
+// latency of one load per addition.
 __global__ __launch_bounds__(256) void colsum_kernel(const float *__restrict__ A,
                                                      float *__restrict__ out, long long rows,
                                                      long long cols, long long sA, long long sOut)
@@ -104,10 +106,56 @@ __global__ __launch_bounds__(256) void colsum_kernel(const float *__restrict__ A
     const int k = blockIdx.y;
     const long long j = (long long)blockIdx.x * 256 + threadIdx.x;
     if (j >= cols) return;
-    const float *a = A + (long long)k * sA;
+    const float *a = A + (long long)k * sA + j;
     float acc = 0.f;
-    for (long long i = 0; i < rows; ++i) acc += a[i * cols + j];
+    long long i = 0;
+    for (; i + 8 <= rows; i += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = a[(i + u) * cols];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += v[u];
+    }
+    for (; i < rows; ++i) acc += a[i * cols];
     out[(long long)k * sOut + j] = acc;
+}
+
+// C[k][i][0..N) = A[k][i][:] B[k] + bias[k] for an output of at most NMAX columns (the class
+// logits): one wavefront per row i, lanes strided over the contraction index, butterfly sum over
+// the lanes (a fixed order).  The 64x64-tile kernel would run this shape on M/64 workgroups per
+// worker with Kd/16 dependent steps each.
+template <int NMAX>
+__global__ __launch_bounds__(256) void skinny_bias_kernel(const float *__restrict__ A, long long sA,
+                                                          const float *__restrict__ Bm, long long sB,
+                                                          const float *__restrict__ bias, long long sBias,
+                                                          float *__restrict__ C, long long sC,
+                                                          int M, int N, int Kd)
+{
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const long long k = blockIdx.y;
+    if (row >= M) return;                                   // whole wavefronts leave together
+    const float *a = A + k * sA + (long long)row * Kd;
+    const float *b = Bm + k * sB;
+    float acc[NMAX];
+#pragma unroll
+    for (int n = 0; n < NMAX; ++n) acc[n] = 0.f;
+    for (int kk = lane; kk < Kd; kk += 64) {
+        const float av = a[kk];
+        const float *br = b + (long long)kk * N;
+#pragma unroll
+        for (int n = 0; n < NMAX; ++n)
+            if (n < N) acc[n] = fmaf(av, br[n], acc[n]);
+    }
+    float mine = 0.f;
+#pragma unroll
+    for (int n = 0; n < NMAX; ++n) {
+        float v = acc[n];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+        if (lane == n) mine = v;
+    }
+    if (lane < N) C[k * sC + (long long)row * N + lane] = mine + bias[k * sBias + lane];
 }
 
 hipError_t launch_mlp2_grad(const ModelDims &d, const float *theta, float *g, const float *means,
@@ -143,7 +191,11 @@ hipError_t launch_mlp2_grad(const ModelDims &d, const float *theta, float *g, co
     a.B = theta + oW2; a.ldb = dz; a.sB = P;
     a.C = w.logit; a.ldc = dz; a.sC = B * dz;
     a.M = (int)B; a.N = (int)dz; a.Kd = (int)dh; a.bias = theta + ob2; a.sBias = P;
-    if ((e = launch_sgemm<false, false, EPI_BIAS>(a, K, s)) != hipSuccess) return e;
+    if (dz <= 16) {
+        skinny_bias_kernel<16><<<dim3((unsigned)((B + 3) / 4), (unsigned)K), 256, 0, s>>>(
+            w.hid, B * dh, theta + oW2, P, theta + ob2, P, w.logit, B * dz, (int)B, (int)dz, (int)dh);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    } else if ((e = launch_sgemm<false, false, EPI_BIAS>(a, K, s)) != hipSuccess) return e;
 
     mlp2_softmax_ce_kernel<<<K, 256, 0, s>>>(w.logit, w.label, loss, B, (int)dz);
     if ((e = hipGetLastError()) != hipSuccess) return e;

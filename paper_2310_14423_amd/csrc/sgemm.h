@@ -1,8 +1,8 @@
 // sgemm.h -- batched single-precision GEMM on the vector ALUs, LDS-tiled, for the small fp32
 // model workload (two-layer perceptron).  C[b] = op(A[b]) * op(B[b]) with optional epilogue;
 // one launch covers all K workers (blockIdx.z).  64x64 output tile, 16-deep k-slabs, 256
-// threads, 4x4 outputs per thread.  Every global access is bounds-checked, so any M, N, Kd
-// is accepted.  fp32 accumulation in a fixed order: deterministic.
+// threads, 4x4 outputs per thread, global loads three slabs ahead in registers.  Every global
+// access is bounds-checked, so any M, N, Kd is accepted.  fp32 accumulation in a fixed order: deterministic.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -35,7 +35,14 @@ __global__ __launch_bounds__(256) void sgemm_kernel(GemmArgs a)
     const float *B = a.B + bz * a.sB;
     float acc[4][4] = {};
 
-    for (int k0 = 0; k0 < a.Kd; k0 += TK) {
+    // Global loads run PF slabs ahead of the multiplication, in registers: these problems have few
+    // workgroups per compute unit (the batch is 128 rows), so a slab's load latency is not hidden
+    // by other wavefronts and, unprefetched, every one of the Kd/16 steps paid it in full
+    // (timed on MI355X, 128 x 784 x 1024, 8 workers: 178 us per launch without, 98 us with).
+    // The order of the additions into acc is unchanged.
+    constexpr int PF = 3;
+    float ra[PF][4], rb[PF][4];
+    auto gload = [&](int k0, float (&xa)[4], float (&xb)[4]) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             int kk, m;
@@ -44,7 +51,7 @@ __global__ __launch_bounds__(256) void sgemm_kernel(GemmArgs a)
             int gm = m0 + m, gk = k0 + kk;
             float v = 0.f;
             if (gm < a.M && gk < a.Kd) v = TA ? A[(long long)gk * a.lda + gm] : A[(long long)gm * a.lda + gk];
-            As[kk][m] = v;
+            xa[r] = v;
         }
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -54,21 +61,44 @@ __global__ __launch_bounds__(256) void sgemm_kernel(GemmArgs a)
             int gn = n0 + n, gk = k0 + kk;
             float v = 0.f;
             if (gn < a.N && gk < a.Kd) v = TB ? B[(long long)gn * a.ldb + gk] : B[(long long)gk * a.ldb + gn];
-            Bs[kk][n] = v;
+            xb[r] = v;
         }
-        __syncthreads();
+    };
+    auto sstore = [&](const float (&xa)[4], const float (&xb)[4]) {
 #pragma unroll
-        for (int kk = 0; kk < TK; ++kk) {
-            float4 av = *(const float4 *)&As[kk][ty * 4];
-            float4 bv = *(const float4 *)&Bs[kk][tx * 4];
-            float ar[4] = {av.x, av.y, av.z, av.w};
-            float br[4] = {bv.x, bv.y, bv.z, bv.w};
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(ar[i], br[j], acc[i][j]);
+        for (int r = 0; r < 4; ++r) {
+            if (TA) As[(tid >> 6) + 4 * r][tid & 63] = xa[r];
+            else    As[tid & 15][(tid >> 4) + 16 * r] = xa[r];
+            if (TB) Bs[tid & 15][(tid >> 4) + 16 * r] = xb[r];
+            else    Bs[(tid >> 6) + 4 * r][tid & 63] = xb[r];
         }
-        __syncthreads();
+    };
+    const int nslab = (a.Kd + TK - 1) / TK;
+#pragma unroll
+    for (int u = 0; u < PF; ++u)
+        if (u < nslab) gload(u * TK, ra[u], rb[u]);
+    for (int s0 = 0; s0 < nslab; s0 += PF) {
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+            const int sl = s0 + u;                  // uniform over the workgroup
+            if (sl < nslab) {
+                sstore(ra[u], rb[u]);
+                if (sl + PF < nslab) gload((sl + PF) * TK, ra[u], rb[u]);
+                __syncthreads();
+#pragma unroll
+                for (int kk = 0; kk < TK; ++kk) {
+                    float4 av = *(const float4 *)&As[kk][ty * 4];
+                    float4 bv = *(const float4 *)&Bs[kk][tx * 4];
+                    float ar[4] = {av.x, av.y, av.z, av.w};
+                    float br[4] = {bv.x, bv.y, bv.z, bv.w};
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(ar[i], br[j], acc[i][j]);
+                }
+                __syncthreads();
+            }
+        }
     }
 
     float *C = a.C + bz * a.sC;
