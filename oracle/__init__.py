@@ -36,10 +36,10 @@ class Config(C.Structure):
     _fields_ = [
         ("K", C.c_int32), ("opt", C.c_int32), ("model", C.c_int32), ("H_base", C.c_int32),
         ("n_threads", C.c_int32), ("n_blocks", C.c_int32), ("power", C.c_int32), ("parallel", C.c_int32),
-        ("average_state", C.c_int32), ("pad_", C.c_int32),
+        ("average_state", C.c_int32), ("n_heads", C.c_int32),
         ("n", C.c_int64), ("T", C.c_int64), ("T_warm", C.c_int64), ("t_local_start", C.c_int64),
         ("t_swap_start", C.c_int64), ("B_loc", C.c_int64),
-        ("d_in", C.c_int64), ("d_hidden", C.c_int64), ("d_out", C.c_int64),
+        ("d_in", C.c_int64), ("d_hidden", C.c_int64), ("d_out", C.c_int64), ("seq_len", C.c_int64),
         ("mu", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double),
         ("lam", C.c_double), ("alpha", C.c_double), ("grad_sigma", C.c_double),
         ("data_sigma", C.c_double), ("clip_norm", C.c_double),
@@ -173,16 +173,19 @@ class Run:
                  eps=1e-8, lam=0.0, H_base=1, alpha=0.0, model="external", seed=0,
                  grad_sigma=0.0, data_sigma=0.0, B_loc=0, d_in=0, d_hidden=0, d_out=0,
                  n_blocks=0, model_const=None, p_idx=None, theta0=None, n_threads=1, power=2,
-                 parallel=False, t_local_start=0, average_state=False, t_swap_start=0, clip_norm=0.0):
+                 parallel=False, t_local_start=0, average_state=False, t_swap_start=0, clip_norm=0.0,
+                 n_heads=0, seq_len=0):
         self.eta = _f64(eta)
         self.K, self.n = int(K), int(n)
         self._const = None if model_const is None else np.ascontiguousarray(model_const, np.float32)
         self._pidx = None if p_idx is None else np.ascontiguousarray(p_idx, np.int64)
+        if n_heads:
+            assert d_in % n_heads == 0 and seq_len > 0 and B_loc % seq_len == 0
         self.cfg = Config(K=K, opt=OPTS[opt], model=MODELS[model], H_base=H_base,
                           n_threads=n_threads, n_blocks=n_blocks, power=power, parallel=int(parallel), average_state=int(average_state),
                           t_local_start=t_local_start, t_swap_start=t_swap_start, n=n, T=len(self.eta),
                           T_warm=T_warm, B_loc=B_loc, d_in=d_in, d_hidden=d_hidden, d_out=d_out,
-                          mu=mu, beta1=beta1, beta2=beta2, eps=eps, lam=lam, alpha=alpha,
+                          n_heads=n_heads, seq_len=seq_len, mu=mu, beta1=beta1, beta2=beta2, eps=eps, lam=lam, alpha=alpha,
                           grad_sigma=grad_sigma, data_sigma=data_sigma, clip_norm=clip_norm, seed=seed,
                           model_const=_p(self._const), p_idx=_p(self._pidx))
         self.state = State(0, 0, 0, 0)

@@ -18,7 +18,8 @@ typedef struct {
                              every step and all workers take the same update  */
     int32_t average_state;/* 1 = the optimizer state is averaged at a sync too
                              (Alg. 2 averages the parameters only: 0)           */
-    int32_t pad_;
+    int32_t n_heads;      /* model 4: attention heads per block, 0 = MLP
+                             sub-blocks only                                  */
     int64_t n;            /* tracked parameters per worker (= P, or a sample) */
     int64_t T, T_warm;
     int64_t t_local_start;/* post-local schedule: rounds that start before this
@@ -27,6 +28,8 @@ typedef struct {
                              after this iteration lasts until T; 0 = off        */
     int64_t B_loc;        /* samples (model 4: tokens) per worker per step    */
     int64_t d_in, d_hidden, d_out;
+    int64_t seq_len;      /* model 4 with n_heads > 0: tokens per sequence
+                             (divides B_loc)                                  */
     double mu, beta1, beta2, eps, lambda;
     double alpha;
     double grad_sigma;    /* model 1: std of the gradient noise               */

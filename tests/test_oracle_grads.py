@@ -25,7 +25,7 @@ def _mk(name, **ov):
                      B_loc=w["B_loc"], d_in=w["d_in"], d_hidden=w.get("d_hidden", 0),
                      d_out=w.get("d_out", 0), n_blocks=w.get("n_blocks", 0),
                      data_sigma=w.get("data_sigma", 0.0), model_const=workloads.model_const(w),
-                     theta0=workloads.theta0(w))
+                     theta0=workloads.theta0(w), n_heads=w.get("n_heads", 0), seq_len=w.get("seq_len", 0))
     return w, run
 
 
@@ -110,6 +110,125 @@ def test_resmlp_gradient_matches_autograd():
     assert np.allclose(g, p.grad.numpy(), rtol=1e-9, atol=1e-14)
     idx = [0, d + 1, 2 * d + 5, per - 1, per + 3, 2 * per + 2 * d + d * dh + 1]
     assert np.allclose(g[idx], _fd(run, 1, 2, th, idx), rtol=1e-5, atol=1e-9)
+
+
+def _vit_torch_loss(p, X, Y, d, dh, L, heads, S, attention=torch.nn.functional.scaled_dot_product_attention):
+    """The attention + MLP blocks from library routines (layer_norm, the library's attention, gelu);
+    p is the packed parameter tensor."""
+    per_a = 2 * d + d * 3 * d + 3 * d + d * d + d
+    per = per_a + 2 * d + d * dh + dh + dh * d + d
+    x = torch.tensor(X)
+    M = x.shape[0]
+    for l in range(L):
+        q = p[l * per:(l + 1) * per]
+        o = 0
+        def take(n, *shape):
+            nonlocal o
+            v = q[o:o + n]; o += n
+            return v.view(*shape) if shape else v
+        ga, ba = take(d), take(d)
+        Wqkv, bqkv = take(d * 3 * d, d, 3 * d), take(3 * d)
+        Wo, bo = take(d * d, d, d), take(d)
+        gm, bm = take(d), take(d)
+        W1, b1 = take(d * dh, d, dh), take(dh)
+        W2, b2 = take(dh * d, dh, d), take(d)
+        u = torch.nn.functional.layer_norm(x, (d,), ga, ba, eps=1e-5)
+        z = (u @ Wqkv + bqkv).view(M // S, S, 3, heads, d // heads)        # [seq][tok][q|k|v][head][dk]
+        qh, kh, vh = (z[:, :, i].permute(0, 2, 1, 3) for i in range(3))    # [seq][head][tok][dk]
+        att = attention(qh, kh, vh)                                        # softmax(q k^T / sqrt(dk)) v
+        x = x + att.permute(0, 2, 1, 3).reshape(M, d) @ Wo + bo
+        u = torch.nn.functional.layer_norm(x, (d,), gm, bm, eps=1e-5)
+        x = x + torch.nn.functional.gelu(u @ W1 + b1) @ W2 + b2
+    return 0.5 * ((x - torch.tensor(Y)) ** 2).mean()
+
+
+def test_vit_block_gradient_matches_autograd_of_the_library_attention():
+    d, dh, L, heads, S = 12, 20, 2, 3, 5
+    w, run = _mk("vit", d_in=d, d_hidden=dh, n_blocks=L, n_heads=heads, seq_len=S, B_loc=3 * S, K=2, T=4)
+    assert w["P"] == L * (2 * d + 3 * d * d + 3 * d + d * d + d + 2 * d + 2 * d * dh + dh + d)
+    rng = np.random.default_rng(5)
+    # large enough weights that the attention probabilities are far from uniform
+    th = workloads.theta0(w).astype(np.float64) + 0.3 * rng.standard_normal(w["P"])
+    X, Y = run.resmlp_batch(1, 2)
+    g, loss = run.grad(1, 2, th)
+    p = torch.tensor(th, requires_grad=True)
+    Lt = _vit_torch_loss(p, X, Y, d, dh, L, heads, S)
+    Lt.backward()
+    assert loss == pytest.approx(Lt.item(), rel=1e-12)
+    assert np.allclose(g, p.grad.numpy(), rtol=1e-9, atol=1e-13)
+    per_a = 2 * d + d * 3 * d + 3 * d + d * d + d
+    per = w["P"] // L
+    idx = [0, d + 2, 2 * d + 7, 2 * d + d * 3 * d - 1, 2 * d + d * 3 * d + d + 1, per_a - d - 3, per_a - 1,
+           per_a + 1, per + 2 * d + 2 * d + 5, per + per_a + 2 * d + 3]
+    assert np.allclose(g[idx], _fd(run, 1, 2, th, idx), rtol=1e-5, atol=1e-9)
+
+
+def test_attention_special_cases_with_closed_forms():
+    """(a) Sequences of one token: the softmax is 1, so the sub-block is x + (u Wv + bv) Wo + bo.
+    (b) Zero query weights and bias: every probability is 1/S, so each token receives the mean
+    value vector of its sequence.  Both written out in NumPy and compared through the loss."""
+    d, dh, heads = 8, 6, 2
+    rng = np.random.default_rng(9)
+
+    def ref_loss(w, th, X, Y, mix):
+        per_a = 2 * d + d * 3 * d + 3 * d + d * d + d
+        ga, ba = th[:d], th[d:2 * d]
+        Wqkv = th[2 * d:2 * d + 3 * d * d].reshape(d, 3 * d); bqkv = th[2 * d + 3 * d * d:2 * d + 3 * d * d + 3 * d]
+        Wo = th[per_a - d - d * d:per_a - d].reshape(d, d); bo = th[per_a - d:per_a]
+        m = th[per_a:]
+        gm, bm = m[:d], m[d:2 * d]
+        W1 = m[2 * d:2 * d + d * dh].reshape(d, dh); b1 = m[2 * d + d * dh:2 * d + d * dh + dh]
+        W2 = m[2 * d + d * dh + dh:2 * d + d * dh + dh + dh * d].reshape(dh, d); b2 = m[-d:]
+        def ln(x, g_, b_):
+            mu = x.mean(1, keepdims=True); var = ((x - mu) ** 2).mean(1, keepdims=True)
+            return g_ * (x - mu) / np.sqrt(var + 1e-5) + b_
+        u = ln(X, ga, ba)
+        v = u @ Wqkv[:, 2 * d:] + bqkv[2 * d:]
+        x = X + mix(v) @ Wo + bo
+        h = ln(x, gm, bm) @ W1 + b1
+        from scipy.special import erf
+        x = x + (0.5 * h * (1 + erf(h / np.sqrt(2)))) @ W2 + b2
+        return 0.5 * np.mean((x - Y) ** 2)
+
+    # (a)
+    w, run = _mk("vit", d_in=d, d_hidden=dh, n_blocks=1, n_heads=heads, seq_len=1, B_loc=6, K=1, T=2)
+    th = workloads.theta0(w).astype(np.float64) + 0.3 * rng.standard_normal(w["P"])
+    X, Y = run.resmlp_batch(0, 1)
+    assert run.grad(0, 1, th)[1] == pytest.approx(ref_loss(w, th, X, Y, lambda v: v), rel=1e-12)
+    # (b)
+    S = 3
+    w, run = _mk("vit", d_in=d, d_hidden=dh, n_blocks=1, n_heads=heads, seq_len=S, B_loc=2 * S, K=1, T=2)
+    th = workloads.theta0(w).astype(np.float64) + 0.3 * rng.standard_normal(w["P"])
+    th[2 * d:2 * d + 3 * d * d].reshape(d, 3 * d)[:, :d] = 0.0          # Wq
+    th[2 * d + 3 * d * d:2 * d + 3 * d * d + d] = 0.0                   # bq
+    X, Y = run.resmlp_batch(0, 1)
+    mean_of_sequence = lambda v: np.repeat(v.reshape(-1, S, d).mean(1), S, axis=0)
+    assert run.grad(0, 1, th)[1] == pytest.approx(ref_loss(w, th, X, Y, mean_of_sequence), rel=1e-12)
+
+
+def test_attention_groups_tokens_by_sequence():
+    """Attention acts within a sequence (seq_len consecutive token rows) and the loss is a mean over
+    tokens: reordering whole sequences leaves the library model's parameter gradient unchanged,
+    moving one token into another sequence changes it, and the oracle agrees with the former."""
+    d, dh, heads, S = 8, 6, 2, 4
+    w, run = _mk("vit", d_in=d, d_hidden=dh, n_blocks=1, n_heads=heads, seq_len=S, B_loc=3 * S, K=1, T=2)
+    rng = np.random.default_rng(3)
+    th = workloads.theta0(w).astype(np.float64) + 0.3 * rng.standard_normal(w["P"])
+    X, Y = run.resmlp_batch(0, 0)
+    p = torch.tensor(th, requires_grad=True)
+    _vit_torch_loss(p, X, Y, d, dh, 1, heads, S).backward()
+    g1 = p.grad.numpy().copy()
+    perm = np.concatenate([np.arange(S) + S * s for s in (2, 0, 1)])
+    p2 = torch.tensor(th, requires_grad=True)
+    _vit_torch_loss(p2, X[perm], Y[perm], d, dh, 1, heads, S).backward()
+    assert np.allclose(g1, p2.grad.numpy(), rtol=1e-10, atol=1e-15)
+    # whereas moving one token into another sequence does change it (the oracle groups by rows)
+    swap = np.arange(3 * S); swap[0], swap[S] = swap[S], swap[0]
+    p3 = torch.tensor(th, requires_grad=True)
+    _vit_torch_loss(p3, X[swap], Y[swap], d, dh, 1, heads, S).backward()
+    assert not np.allclose(g1, p3.grad.numpy(), rtol=1e-6)
+    g, _ = run.grad(0, 0, th)
+    assert np.allclose(g, g1, rtol=1e-9, atol=1e-13)
 
 
 def test_local_sgd_with_H1_is_minibatch_sgd():

@@ -33,7 +33,8 @@ def oracle_run(w, p_idx=None, n_threads=8, theta0=None, eta=None):
                       model_const=workloads.model_const(w), p_idx=p_idx, theta0=th0,
                       n_threads=n_threads, power=w.get("power", 2), parallel=w.get("parallel", False),
                       t_local_start=w.get("t_local_start", 0), average_state=w.get("average_state", False), t_swap_start=w.get("t_swap_start", 0),
-                      clip_norm=w.get("clip_norm", 0.0))
+                      clip_norm=w.get("clip_norm", 0.0), n_heads=w.get("n_heads", 0),
+                      seq_len=w.get("seq_len", 0))
 
 
 def gpu_ctx(w, theta0=None, eta_table=None):

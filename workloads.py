@@ -11,7 +11,8 @@ The five workloads stand in for the paper's ImageNet runs (Sec. 4, App. C of
 arXiv 2310.14423), which need a dataset and trained models that are not
 available: "lsq" and "mlp" carry the ResNet recipe's optimizer (SGD, momentum
 0.9, step or cosine decay), "flat60m"/"flat350m" carry the ViT recipe's
-AdamW traffic at two sizes, and "resmlp" has ViT-B's MLP sub-block shapes.
+AdamW traffic at two sizes, "resmlp" has ViT-B's MLP sub-block shapes and
+"vit" adds the attention sub-blocks (ViT-B's whole encoder block).
 """
 import numpy as np
 
@@ -24,8 +25,9 @@ def mlp2_param_count(d_in, d_hidden, d_out):
     return d_in * d_hidden + d_hidden + d_hidden * d_out + d_out
 
 
-def resmlp_param_count(d, d_hidden, n_blocks):
-    return n_blocks * (2 * d + d * d_hidden + d_hidden + d_hidden * d + d)
+def resmlp_param_count(d, d_hidden, n_blocks, n_heads=0):
+    attn = 2 * d + d * 3 * d + 3 * d + d * d + d if n_heads else 0
+    return n_blocks * (attn + 2 * d + d * d_hidden + d_hidden + d_hidden * d + d)
 
 
 WORKLOADS = {
@@ -50,6 +52,13 @@ WORKLOADS = {
                    opt="adamw", beta1=0.9, beta2=0.999, eps=1e-8, lam=0.05,
                    lr="cosine", eta_max=8e-4, eta_min=0.0,
                    H_base=4, alpha=0.0175, seed=0),
+    # the same 12 blocks, each preceded by its attention sub-block (12 heads of width 64, sequences
+    # of 197 tokens): a whole ViT-B encoder block
+    "vit": dict(model="resmlp", K=8, P=resmlp_param_count(768, 3072, 12, 12), T=2000, T_warm=100,
+                B_loc=64 * 197, d_in=768, d_hidden=3072, n_blocks=12, n_heads=12, seq_len=197,
+                opt="adamw", beta1=0.9, beta2=0.999, eps=1e-8, lam=0.05,
+                lr="cosine", eta_max=8e-4, eta_min=0.0,
+                H_base=4, alpha=0.0175, seed=0),
     # optimizer-only, 350 M parameters, 32 replicas (~180 GB of state)
     "flat350m": dict(model="noise", K=32, P=350_000_000, T=2000, T_warm=0,
                      opt="adamw", beta1=0.9, beta2=0.999, eps=1e-8, lam=0.05,
@@ -64,7 +73,7 @@ def get(name, **overrides):
     if w["model"] == "mlp2":
         w["P"] = mlp2_param_count(w["d_in"], w["d_hidden"], w["d_out"])
     elif w["model"] == "resmlp":
-        w["P"] = resmlp_param_count(w["d_in"], w["d_hidden"], w["n_blocks"])
+        w["P"] = resmlp_param_count(w["d_in"], w["d_hidden"], w["n_blocks"], w.get("n_heads", 0))
     elif w["model"] == "linreg":
         w["P"] = w["d_in"]
     return w
@@ -85,6 +94,9 @@ def theta0(w):
         d, dh, L = w["d_in"], w["d_hidden"], w["n_blocks"]
         parts = []
         for _ in range(L):
+            if w.get("n_heads", 0):     # attention sub-block: LayerNorm, q|k|v and output projections
+                parts += [np.ones(d), np.zeros(d), 0.02 * r.standard_normal(d * 3 * d), np.zeros(3 * d),
+                          0.02 * r.standard_normal(d * d), np.zeros(d)]
             parts += [np.ones(d), np.zeros(d), 0.02 * r.standard_normal(d * dh), np.zeros(dh),
                       0.02 * r.standard_normal(dh * d), np.zeros(d)]
         return np.concatenate(parts).astype(np.float32)
