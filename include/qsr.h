@@ -55,7 +55,8 @@ enum {
     QSR_MODEL_NOISE = 1,    /* g = grad_sigma * N(0,1), optimizer-only workloads          */
     QSR_MODEL_LINREG = 2,   /* linear least squares, P = d_in                             */
     QSR_MODEL_MLP2 = 3,     /* d_in - d_hidden - d_out perceptron, ReLU, softmax CE       */
-    QSR_MODEL_RESMLP = 4    /* n_blocks pre-LN residual MLP blocks, bf16 GEMMs            */
+    QSR_MODEL_RESMLP = 4    /* n_blocks pre-LN residual MLP blocks (optionally each with its
+                               attention sub-block, see n_heads), bf16 GEMMs              */
 };
 
 /* Plain-data configuration (Alg. 2's inputs and hyper-parameters, Eq. (2)'s alpha and H_base,
@@ -83,7 +84,9 @@ typedef struct {
                              the buffers: 28 B per replica-parameter for AdamW on that step instead
                              of 28 + 8); qsr_maybe_sync then only opens the next round.  Same
                              results bit for bit.  Not with parallel or average_state.  0 = off */
-    int32_t reserved;     /* must be 0                                                    */
+    int32_t n_heads;      /* QSR_MODEL_RESMLP: > 0 puts a multi-head self-attention sub-block (heads of
+                             width 64, so d_in = 64 n_heads) in front of every MLP sub-block: the
+                             encoder block of the paper's ViT-B (App. C.2).  0 = MLP sub-blocks only */
     int64_t P;            /* parameters per worker, >= 1                                   */
     int64_t T;            /* total iterations, eta_t is defined for t in 0..T-1, >= 1      */
     int64_t T_warm;       /* linear warm-up 0 -> eta_max over the first T_warm iterations  */
@@ -94,6 +97,8 @@ typedef struct {
                              0 = off                                                        */
     int64_t B_loc;        /* local batch: samples (RESMLP: tokens) per worker per step     */
     int64_t d_in, d_hidden, d_out;
+    int64_t seq_len;      /* n_heads > 0: tokens per sequence, 1..224, dividing B_loc; attention
+                             acts within runs of seq_len consecutive tokens                */
     double momentum;      /* SGD heavy-ball coefficient                                    */
     double beta1, beta2, eps; /* AdamW                                                     */
     double weight_decay;  /* SGD: coupled (added to the gradient); AdamW: decoupled        */

@@ -13,6 +13,14 @@
 // weight-gradient GEMMs reduce over the token axis and read the row-major bf16 activations as
 // they are ("TN" form, LDS transpose reads), so no transposed activation copies exist.
 // Per-block parameter packing: gamma[d], beta[d], W1[d][dh], b1[dh], W2[dh][d], b2[d].
+//
+// With n_heads > 0 each block first runs the attention half of a ViT encoder block,
+//   u = LayerNorm(x_l; gamma_a, beta_a);  q|k|v = u Wqkv + bqkv;
+//   o = softmax(q k^T / sqrt(64)) v per head and sequence;  x_l' = x_l + o Wo + bo,
+// its parameters gamma_a[d], beta_a[d], Wqkv[d][3d], bqkv[3d], Wo[d][d], bo[d] packed in front of
+// the block's six arrays above: four more GEMMs forward/data-gradient and two weight-gradient
+// GEMMs of the same kinds, and the attention core of attention.h.
+#include "attention.h"
 #include "gemm_bf16.h"
 #include "gemm_pp.h"
 #include "qsr_internal.h"
@@ -26,10 +34,11 @@ constexpr int LN_ROWS_PER_WAVE = 16;
 
 struct ResWs {
     // per-replica strides are the element counts of one replica's array
-    float *X;      long long sX;       // [L+1][M][d]
-    float *MU, *RSTD; long long sStat; // [L][M]
+    // "sub" counts residual sub-blocks: L without attention, 2L with (attention, MLP, attention, ...)
+    float *X;      long long sX;       // [sub+1][M][d]
+    float *MU, *RSTD; long long sStat; // [sub][M]
     bf16_t *H;     long long sH;       // [L][M][dh]  gelu'(pre-activation)
-    bf16_t *U;     long long sU;       // [L][M][d]   LayerNorm output
+    bf16_t *U;     long long sU;       // [sub][M][d] LayerNorm output
     bf16_t *A;     long long sA;       // [L][M][dh]  GELU output
     float *Y;      long long sY;       // [M][d]
     float *DX;     long long sDX;      // [2][M][d]
@@ -41,11 +50,20 @@ struct ResWs {
     float *PART;   long long sPART;    // [2][wave_rows][d] partial dgamma, dbeta
     float *LPART;  long long sLPART;   // loss partials
     bf16_t *ZERO;                      // 256 bytes of zeros (stand-in rows of ragged GEMM slabs)
+    // attention sub-blocks only
+    bf16_t *QKV;   long long sQKV;     // [L][M][3d]
+    bf16_t *O;     long long sO;       // [L][M][d]   attention output before the projection
+    float *LSE;    long long sLSE;     // [L][heads][M]
+    bf16_t *DO;    long long sDO;      // [M][d]
+    bf16_t *DQKV;  long long sDQKV;    // [M][3d]
+    bf16_t *Wqb, *WqTb; long long sWq; // [L][d*3d] each
+    bf16_t *Wob, *WoTb; long long sWo; // [L][d*d] each
 };
 
 static ResWs carve(const ModelDims &dm, void *ws, size_t *total)
 {
     const long long K = dm.K, M = dm.B, d = dm.d_in, dh = dm.d_hidden, L = dm.n_blocks;
+    const long long heads = dm.n_heads, sub = heads > 0 ? 2 * L : L;
     char *p = (char *)ws;
     size_t off = 0;
     ResWs w;
@@ -60,10 +78,10 @@ static ResWs carve(const ModelDims &dm, void *ws, size_t *total)
         off += up256((size_t)per_replica * elt * (size_t)copies);
         return r;
     };
-    w.sX = padded((L + 1) * M * d, 4);   w.X = (float *)take(w.sX, 4, K);
-    w.sStat = padded(L * M, 4);          w.MU = (float *)take(w.sStat, 4, K); w.RSTD = (float *)take(w.sStat, 4, K);
+    w.sX = padded((sub + 1) * M * d, 4); w.X = (float *)take(w.sX, 4, K);
+    w.sStat = padded(sub * M, 4);        w.MU = (float *)take(w.sStat, 4, K); w.RSTD = (float *)take(w.sStat, 4, K);
     w.sH = padded(L * M * dh, 2);        w.H = (bf16_t *)take(w.sH, 2, K);
-    w.sU = padded(L * M * d, 2);         w.U = (bf16_t *)take(w.sU, 2, K);
+    w.sU = padded(sub * M * d, 2);       w.U = (bf16_t *)take(w.sU, 2, K);
     w.sA = padded(L * M * dh, 2);        w.A = (bf16_t *)take(w.sA, 2, K);
     w.sY = padded(M * d, 4);             w.Y = (float *)take(w.sY, 4, K);
     w.sDX = padded(2 * M * d, 4);        w.DX = (float *)take(w.sDX, 4, K);
@@ -78,6 +96,19 @@ static ResWs carve(const ModelDims &dm, void *ws, size_t *total)
     w.sPART = padded(2 * wave_rows * d, 4); w.PART = (float *)take(w.sPART, 4, K);
     w.sLPART = padded((M * d + 1023) / 1024, 4); w.LPART = (float *)take(w.sLPART, 4, K);
     w.ZERO = (bf16_t *)take(128, 2, 1);
+    w.QKV = w.O = w.DO = w.DQKV = w.Wqb = w.WqTb = w.Wob = w.WoTb = nullptr; w.LSE = nullptr;
+    w.sQKV = w.sO = w.sLSE = w.sDO = w.sDQKV = w.sWq = w.sWo = 0;
+    if (heads > 0) {
+        w.sQKV = padded(L * M * 3 * d, 2);   w.QKV = (bf16_t *)take(w.sQKV, 2, K);
+        w.sO = padded(L * M * d, 2);         w.O = (bf16_t *)take(w.sO, 2, K);
+        w.sLSE = padded(L * heads * M, 4);   w.LSE = (float *)take(w.sLSE, 4, K);
+        w.sDO = padded(M * d, 2);            w.DO = (bf16_t *)take(w.sDO, 2, K);
+        w.sDQKV = padded(M * 3 * d, 2);      w.DQKV = (bf16_t *)take(w.sDQKV, 2, K);
+        w.sWq = padded(L * d * 3 * d, 2);
+        w.Wqb = (bf16_t *)take(w.sWq, 2, K); w.WqTb = (bf16_t *)take(w.sWq, 2, K);
+        w.sWo = padded(L * d * d, 2);
+        w.Wob = (bf16_t *)take(w.sWo, 2, K); w.WoTb = (bf16_t *)take(w.sWo, 2, K);
+    }
     if (total) *total = off;
     return w;
 }
@@ -404,6 +435,25 @@ struct EpiScaleF32 {             // C = scale * acc
                make_float4(v[0] * scale, v[1] * scale, v[2] * scale, v[3] * scale));
     }
 };
+struct EpiBf16 {                 // C = bf16(acc)
+    bf16_t *C; long long ldc, sC;
+    typedef NoAux Aux;
+    __device__ Aux pre(int, int, int) const { return Aux{}; }
+    __device__ void operator()(int z, int m, int n, const float (&v)[4], const Aux &) const
+    {
+        *(bf16x4 *)(C + (long long)z * sC + (long long)m * ldc + n) = pack4(v[0], v[1], v[2], v[3]);
+    }
+};
+struct EpiBiasBf16 {             // C = bf16(acc + bias)
+    const float *bias; long long sBias; bf16_t *C; long long ldc, sC;
+    typedef NoAux Aux;
+    __device__ Aux pre(int, int, int) const { return Aux{}; }
+    __device__ void operator()(int z, int m, int n, const float (&v)[4], const Aux &) const
+    {
+        const float4 b = *(const float4 *)(bias + (long long)z * sBias + n);
+        *(bf16x4 *)(C + (long long)z * sC + (long long)m * ldc + n) = pack4(v[0] + b.x, v[1] + b.y, v[2] + b.z, v[3] + b.w);
+    }
+};
 struct EpiBiasGelu {             // h = acc + b1; H = bf16(gelu'(h)); A = bf16(gelu(h))
     // The backward pass needs h only through gelu'(h) = Phi(h) + h phi(h), and both factors are at
     // hand here: storing the derivative instead of h costs two instructions per element now and
@@ -492,18 +542,67 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
                               void *ws, float *loss, const DevState *st, hipStream_t s)
 {
     const int K = dm.K, M = (int)dm.B, d = (int)dm.d_in, dh = (int)dm.d_hidden, L = dm.n_blocks;
+    const int heads = dm.n_heads, S = (int)dm.seq_len;
+    const int nsub = heads > 0 ? 2 : 1;           // residual sub-blocks per block
     const long long P = dm.P;
-    const long long per_block = 2LL * d + (long long)d * dh + dh + (long long)dh * d + d;
+    const long long dd = (long long)d * d;
+    const long long per_attn = heads > 0 ? 2LL * d + 3 * dd + 3LL * d + dd + d : 0;
+    const long long per_block = per_attn + 2LL * d + (long long)d * dh + dh + (long long)dh * d + d;
+    if (heads > 0 && !attn_supports(d, heads, S, M)) return hipErrorInvalidValue;
     ResWs w = carve(dm, ws, nullptr);
     const long long Md = (long long)M * d, Mdh = (long long)M * dh;
+    const int wave_rows = (M + LN_ROWS_PER_WAVE - 1) / LN_ROWS_PER_WAVE;
+
+    AttnArgs att{};
+    if (heads > 0) {
+        att.sQKV = w.sQKV; att.sO = w.sO; att.sLSE = w.sLSE; att.DO = w.DO; att.sDO = w.sDO;
+        att.DQKV = w.DQKV; att.sDQKV = w.sDQKV;
+        att.M = M; att.d = d; att.S = S; att.nb = (S + 31) / 32;
+        att.scale = 1.0f / sqrtf((float)ATT_DK);
+        att.c2 = 1.4426950408889634f * att.scale;
+    }
+
+    // LayerNorm of residual state number `sub` with the parameters at off_gamma
+    auto ln_fwd = [&](int sub, long long off_gamma) -> hipError_t {
+        dim3 grid((unsigned)((M + 3) / 4), (unsigned)K);
+#define LN_FWD(VPL) ln_fwd_kernel<VPL><<<grid, 256, 0, s>>>(w.X + (long long)sub * Md, w.sX, theta, P, off_gamma, \
+                        w.U + (long long)sub * Md, w.sU, w.MU + (long long)sub * M, w.RSTD + (long long)sub * M, w.sStat, M, d)
+        const int vpl = (d + 255) / 256;
+        if (vpl <= 1) LN_FWD(1); else if (vpl <= 2) LN_FWD(2); else if (vpl <= 3) LN_FWD(3); else LN_FWD(4);
+#undef LN_FWD
+        return hipGetLastError();
+    };
+    // its backward pass plus the residual path: DX[cur] (d loss / d state sub+1) and DU -> DX[cur^1]
+    // (d loss / d state sub, also in bf16), and the LayerNorm parameter gradients
+    int cur = 0;
+    auto ln_bwd = [&](int sub, long long off_gamma) -> hipError_t {
+        dim3 grid((unsigned)((wave_rows + 3) / 4), (unsigned)K);
+        const float *DXc = w.DX + (long long)cur * Md;
+        float *DXn = w.DX + (long long)(cur ^ 1) * Md;
+#define LN_BWD(VPL) ln_bwd_kernel<VPL><<<grid, 256, 0, s>>>(w.DU, w.sDU, w.X + (long long)sub * Md, w.sX, w.MU + (long long)sub * M, \
+                        w.RSTD + (long long)sub * M, w.sStat, theta, P, off_gamma, DXc, DXn, w.sDX, w.DXb, w.sDXb, w.PART, w.sPART, wave_rows, M, d)
+        const int vpl = (d + 255) / 256;
+        if (vpl <= 1) LN_BWD(1); else if (vpl <= 2) LN_BWD(2); else if (vpl <= 3) LN_BWD(3); else LN_BWD(4);
+#undef LN_BWD
+        TRY(hipGetLastError());
+        colsum_final_kernel<<<dim3((unsigned)((d + 63) / 64), (unsigned)K, 2), 256, 0, s>>>(
+            w.PART, w.sPART, g + off_gamma, P, wave_rows, d);
+        cur ^= 1;
+        return hipGetLastError();
+    };
 
     TRY(launch_fill_zero((float *)w.ZERO, 64, s));
     // bf16 copies of the weights in both orientations (the master weights changed last step)
     for (int l = 0; l < L; ++l) {
-        const long long oW1 = l * per_block + 2LL * d, oW2 = oW1 + (long long)d * dh + dh;
+        const long long oW1 = l * per_block + per_attn + 2LL * d, oW2 = oW1 + (long long)d * dh + dh;
         const long long ow = (long long)l * d * dh;
         TRY(launch_cvt_transpose<float>(theta + oW1, dh, P, w.W1b + ow, w.sW, w.W1Tb + ow, d, w.sW, d, dh, K, s));
         TRY(launch_cvt_transpose<float>(theta + oW2, d, P, w.W2b + ow, w.sW, w.W2Tb + ow, dh, w.sW, dh, d, K, s));
+        if (heads > 0) {
+            const long long oWq = l * per_block + 2LL * d, oWo = oWq + 3 * dd + 3LL * d;
+            TRY(launch_cvt_transpose<float>(theta + oWq, 3LL * d, P, w.Wqb + l * 3 * dd, w.sWq, w.WqTb + l * 3 * dd, d, w.sWq, d, 3 * d, K, s));
+            TRY(launch_cvt_transpose<float>(theta + oWo, d, P, w.Wob + l * dd, w.sWo, w.WoTb + l * dd, d, w.sWo, d, d, K, s));
+        }
     }
     TRY(launch_cvt_transpose<float>(teacher, d, 0, nullptr, 0, w.WTt, d, 0, d, d, 1, s));
 
@@ -522,21 +621,32 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
 
     // forward
     for (int l = 0; l < L; ++l) {
-        const long long og = l * per_block, ob1 = og + 2LL * d + (long long)d * dh,
+        int sub = nsub * l;
+        if (heads > 0) {
+            const long long oga = l * per_block, obq = oga + 2LL * d + 3 * dd, obo = obq + 3LL * d + dd;
+            bf16_t *QKVl = w.QKV + (long long)l * M * 3 * d, *Ol = w.O + (long long)l * Md;
+            TRY(ln_fwd(sub, oga));
+            {
+                GemmNT p{w.U + (long long)sub * Md, w.WqTb + l * 3 * dd, M, 3 * d, d, d, d, w.sU, w.sWq};
+                EpiBiasBf16 epi{theta + obq, P, QKVl, 3LL * d, w.sQKV};
+                TRY(gemm_nt(p, epi, K, s));
+            }
+            att.QKV = QKVl; att.O = Ol; att.LSE = w.LSE + (long long)l * heads * M;
+            TRY(launch_attn_fwd(att, heads, K, s));
+            {
+                GemmNT p{Ol, w.WoTb + l * dd, M, d, d, d, d, w.sO, w.sWo};
+                EpiBiasResidual epi{theta + obo, P, w.X + (long long)sub * Md, w.X + (long long)(sub + 1) * Md, w.sX, d};
+                TRY(gemm_nt(p, epi, K, s));
+            }
+            ++sub;
+        }
+        const long long og = l * per_block + per_attn, ob1 = og + 2LL * d + (long long)d * dh,
                         ob2 = ob1 + dh + (long long)dh * d;
         const long long ow = (long long)l * d * dh;
-        const float *Xl = w.X + (long long)l * Md;
-        float *Xn = w.X + (long long)(l + 1) * Md;
-        bf16_t *Ul = w.U + (long long)l * Md, *Al = w.A + (long long)l * Mdh;
-        {
-            dim3 grid((unsigned)((M + 3) / 4), (unsigned)K);
-#define LN_FWD(VPL) ln_fwd_kernel<VPL><<<grid, 256, 0, s>>>(Xl, w.sX, theta, P, og, Ul, w.sU, w.MU + (long long)l * M, \
-                        w.RSTD + (long long)l * M, w.sStat, M, d)
-            const int vpl = (d + 255) / 256;
-            if (vpl <= 1) LN_FWD(1); else if (vpl <= 2) LN_FWD(2); else if (vpl <= 3) LN_FWD(3); else LN_FWD(4);
-#undef LN_FWD
-            TRY(hipGetLastError());
-        }
+        const float *Xl = w.X + (long long)sub * Md;
+        float *Xn = w.X + (long long)(sub + 1) * Md;
+        bf16_t *Ul = w.U + (long long)sub * Md, *Al = w.A + (long long)l * Mdh;
+        TRY(ln_fwd(sub, og));
         {
             GemmNT p{Ul, w.W1Tb + ow, M, dh, d, d, d, w.sU, w.sW};
             EpiBiasGelu epi{theta + ob1, P, w.H + (long long)l * Mdh, w.sH, Al, w.sA, dh};
@@ -554,20 +664,18 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
         const int nparts = (int)((Md + 1023) / 1024);
         const float inv = 1.0f / ((float)M * (float)d);
         loss_kernel<<<dim3((unsigned)nparts, (unsigned)K), 256, 0, s>>>(
-            w.X + (long long)L * Md, w.sX, w.Y, w.sY, w.DX, w.sDX, w.DXb, w.sDXb, w.LPART, w.sLPART, Md, inv);
+            w.X + (long long)(nsub * L) * Md, w.sX, w.Y, w.sY, w.DX, w.sDX, w.DXb, w.sDXb, w.LPART, w.sLPART, Md, inv);
         TRY(hipGetLastError());
         loss_final_kernel<<<K, 256, 0, s>>>(w.LPART, w.sLPART, nparts, 0.5f * inv, loss);
         TRY(hipGetLastError());
     }
 
-    // backward
-    int cur = 0;                                  // DX[cur] holds d loss / d x_{l+1}
-    const int wave_rows = (M + LN_ROWS_PER_WAVE - 1) / LN_ROWS_PER_WAVE;
+    // backward; DX[cur] (and its bf16 copy DXb) holds d loss / d (output of the sub-block at hand)
     for (int l = L - 1; l >= 0; --l) {
-        const long long og = l * per_block, oW1 = og + 2LL * d, ob1 = oW1 + (long long)d * dh,
+        int sub = nsub * l + nsub - 1;
+        const long long og = l * per_block + per_attn, oW1 = og + 2LL * d, ob1 = oW1 + (long long)d * dh,
                         oW2 = ob1 + dh, ob2 = oW2 + (long long)dh * d;
         const long long ow = (long long)l * d * dh;
-        float *DXc = w.DX + (long long)cur * Md, *DXn = w.DX + (long long)(cur ^ 1) * Md;
         // W2 and b2:  dW2 = a^T dx, db2 = column sums of dx (by-product of the same GEMM)
         {
             GemmNT p{w.A + (long long)l * Mdh, w.DXb, dh, d, M, dh, d, w.sA, w.sDXb, g + ob2, P, w.ZERO};
@@ -582,31 +690,50 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
         }
         // W1 and b1:  dW1 = u^T dh, db1 = column sums of dh
         {
-            GemmNT p{w.U + (long long)l * Md, w.DH, d, dh, M, d, dh, w.sU, w.sDH, g + ob1, P, w.ZERO};
+            GemmNT p{w.U + (long long)sub * Md, w.DH, d, dh, M, d, dh, w.sU, w.sDH, g + ob1, P, w.ZERO};
             EpiScaleF32 epi{g + oW1, dh, P, 1.0f};
             TRY(gemm_tn(p, epi, K, s));
         }
-        // du = dh W1^T, then LayerNorm backward + residual: dx_l
+        // du = dh W1^T, then LayerNorm backward + residual
         {
             GemmNT p{w.DH, w.W1b + ow, M, d, dh, dh, dh, w.sDH, w.sW};
             EpiScaleF32 epi{w.DU, d, w.sDU, 1.0f};
             TRY(gemm_nt(p, epi, K, s));
         }
-        {
-            dim3 grid((unsigned)((wave_rows + 3) / 4), (unsigned)K);
-            const float *Xl = w.X + (long long)l * Md;
-            const float *mu = w.MU + (long long)l * M, *rs = w.RSTD + (long long)l * M;
-#define LN_BWD(VPL) ln_bwd_kernel<VPL><<<grid, 256, 0, s>>>(w.DU, w.sDU, Xl, w.sX, mu, rs, w.sStat, theta, P, og, \
-                        DXc, DXn, w.sDX, w.DXb, w.sDXb, w.PART, w.sPART, wave_rows, M, d)
-            const int vpl = (d + 255) / 256;
-            if (vpl <= 1) LN_BWD(1); else if (vpl <= 2) LN_BWD(2); else if (vpl <= 3) LN_BWD(3); else LN_BWD(4);
-#undef LN_BWD
-            TRY(hipGetLastError());
-            colsum_final_kernel<<<dim3((unsigned)((d + 63) / 64), (unsigned)K, 2), 256, 0, s>>>(
-                w.PART, w.sPART, g + og, P, wave_rows, d);
-            TRY(hipGetLastError());
+        TRY(ln_bwd(sub, og));
+        if (heads > 0) {
+            --sub;
+            const long long oga = l * per_block, oWq = oga + 2LL * d, obq = oWq + 3 * dd, oWo = obq + 3LL * d,
+                            obo = oWo + dd;
+            bf16_t *QKVl = w.QKV + (long long)l * M * 3 * d, *Ol = w.O + (long long)l * Md;
+            // Wo and bo:  dWo = o^T dx, dbo = column sums of dx
+            {
+                GemmNT p{Ol, w.DXb, d, d, M, d, d, w.sO, w.sDXb, g + obo, P, w.ZERO};
+                EpiScaleF32 epi{g + oWo, d, P, 1.0f};
+                TRY(gemm_tn(p, epi, K, s));
+            }
+            // do = dx Wo^T
+            {
+                GemmNT p{w.DXb, w.Wob + l * dd, M, d, d, d, d, w.sDXb, w.sWo};
+                EpiBf16 epi{w.DO, d, w.sDO};
+                TRY(gemm_nt(p, epi, K, s));
+            }
+            att.QKV = QKVl; att.O = Ol; att.LSE = w.LSE + (long long)l * heads * M;
+            TRY(launch_attn_bwd(att, heads, K, s));
+            // Wqkv and bqkv:  dWqkv = u^T dqkv, dbqkv = column sums of dqkv
+            {
+                GemmNT p{w.U + (long long)sub * Md, w.DQKV, d, 3 * d, M, d, 3LL * d, w.sU, w.sDQKV, g + obq, P, w.ZERO};
+                EpiScaleF32 epi{g + oWq, 3LL * d, P, 1.0f};
+                TRY(gemm_tn(p, epi, K, s));
+            }
+            // du = dqkv Wqkv^T, then LayerNorm backward + residual
+            {
+                GemmNT p{w.DQKV, w.Wqb + l * 3 * dd, M, d, 3 * d, 3LL * d, 3LL * d, w.sDQKV, w.sWq};
+                EpiScaleF32 epi{w.DU, d, w.sDU, 1.0f};
+                TRY(gemm_nt(p, epi, K, s));
+            }
+            TRY(ln_bwd(sub, oga));
         }
-        cur ^= 1;
     }
     return hipSuccess;
 }

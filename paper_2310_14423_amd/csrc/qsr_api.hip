@@ -66,8 +66,9 @@ static long long mlp2_params(const qsr_config *c)
 }
 static long long resmlp_params(const qsr_config *c)
 {
-    return (long long)c->n_blocks *
-           (2 * c->d_in + c->d_in * c->d_hidden + c->d_hidden + c->d_hidden * c->d_in + c->d_in);
+    const long long d = c->d_in;
+    const long long attn = c->n_heads > 0 ? 2 * d + 3 * d * d + 3 * d + d * d + d : 0;
+    return (long long)c->n_blocks * (attn + 2 * d + d * c->d_hidden + c->d_hidden + c->d_hidden * d + d);
 }
 
 extern "C" int qsr_validate(const qsr_config *c, const char **why)
@@ -87,7 +88,7 @@ extern "C" int qsr_validate(const qsr_config *c, const char **why)
     else if (c->average_state != 0 && c->average_state != 1) w = "average_state";
     else if (c->fuse_sync != 0 && c->fuse_sync != 1) w = "fuse_sync";
     else if (c->fuse_sync == 1 && (c->parallel == 1 || c->average_state == 1)) w = "fuse_sync with parallel or average_state";
-    else if (c->reserved != 0) w = "reserved";
+    else if (c->n_heads < 0 || (c->n_heads > 0 && c->model != QSR_MODEL_RESMLP)) w = "n_heads";
     else if (!finite_ge0(c->clip_norm)) w = "clip_norm";
     else if (c->power < 0 || c->power > 8) w = "power";
     else if (c->parallel != 0 && c->parallel != 1) w = "parallel";
@@ -142,6 +143,9 @@ extern "C" int qsr_validate(const qsr_config *c, const char **why)
             else if (c->d_in % 64 != 0 || c->d_hidden % 64 != 0) w = "d_in/d_hidden not multiples of 64";
             else if (c->d_in > 1024) w = "d_in (above 1024)";
             else if (c->B_loc > (1 << 24) || c->d_hidden > (1 << 20)) w = "B_loc/d_hidden too large";
+            else if (c->n_heads > 0 && c->d_in != 64LL * c->n_heads) w = "n_heads (heads are 64 wide: d_in = 64 n_heads)";
+            else if (c->n_heads > 0 && (c->seq_len < 1 || c->seq_len > 224 || c->B_loc % c->seq_len != 0))
+                w = "seq_len (1..224, dividing B_loc)";
             else if (c->P != resmlp_params(c)) w = "P != residual-MLP parameter count";
             else if (c->B_loc * c->d_in > ((long long)1 << 34)) w = "B_loc*d_in";
             break;
@@ -157,6 +161,7 @@ static ModelDims make_dims(const qsr_config *c)
     ModelDims d;
     d.K = c->K; d.P = c->P; d.B = c->B_loc; d.d_in = c->d_in; d.d_hidden = c->d_hidden;
     d.d_out = c->d_out; d.n_blocks = c->n_blocks; d.data_sigma = (float)c->data_sigma;
+    d.n_heads = c->n_heads; d.seq_len = c->seq_len;
     d.seed = c->seed;
     return d;
 }

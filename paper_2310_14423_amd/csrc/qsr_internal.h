@@ -99,6 +99,8 @@ struct ModelDims {
     int K;
     long long P, B, d_in, d_hidden, d_out;
     int n_blocks;
+    int n_heads;            // residual-MLP model: attention heads per block, 0 = none
+    long long seq_len;      //   tokens per sequence (attention only)
     float data_sigma;
     uint64_t seed;
 };

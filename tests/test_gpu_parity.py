@@ -286,18 +286,48 @@ def test_mlp2_full_size_first_steps():
 
 
 def _resmlp_groups(w):
+    """(name, index) of every parameter array; the packed q|k|v projection is split into its three
+    matrices (their gradients differ in scale by large factors, and the tolerance is relative to a
+    group's rms)."""
     d, dh, L = w["d_in"], w["d_hidden"], w["n_blocks"]
-    per = 2 * d + d * dh + dh + dh * d + d
+    arrays = [("gamma", d), ("beta", d), ("W1", d * dh), ("b1", dh), ("W2", dh * d), ("b2", d)]
+    if w.get("n_heads", 0):
+        arrays = [("gamma_a", d), ("beta_a", d), ("Wqkv", d * 3 * d), ("bqkv", 3 * d), ("Wo", d * d), ("bo", d)] + arrays
     out = []
+    o = 0
     for l in range(L):
-        o = l * per
-        for name, n in (("gamma", d), ("beta", d), ("W1", d * dh), ("b1", dh), ("W2", dh * d), ("b2", d)):
-            out.append(("%s[%d]" % (name, l), slice(o, o + n)))
+        for name, n in arrays:
+            if name in ("Wqkv", "bqkv"):
+                idx = o + np.arange(n).reshape(-1, 3, d)
+                for i, part in enumerate("qkv"):
+                    out.append(("%s%s[%d]" % (name[0], part, l), idx[:, i, :].ravel()))
+            else:
+                out.append(("%s[%d]" % (name, l), slice(o, o + n)))
             o += n
+    assert o == w["P"]
     return out
 
 
 RTOL_BF16 = 2e-2      # bf16 GEMM inputs, fp32 accumulation
+
+
+def _assert_groups_close(w, gpu, orc, what, tail=None, weights_only_tail=False):
+    """All parameter groups of one worker's gradient (or parameters) to the bf16 tolerance.  The
+    gradient of the key bias is exactly zero (adding a constant to every key shifts all scores of a
+    query alike, which the softmax ignores); in bf16 it is a sum of rounding errors, measured here
+    against the scale of the query bias's gradient.  With sequences of one token every query and
+    key gradient is exactly zero (the only probability is 1): measured against the value
+    projection's."""
+    groups = dict(_resmlp_groups(w))
+    rms_of = lambda nm: float(np.sqrt(np.mean(orc[..., groups[nm]] ** 2)))
+    for name, sl in groups.items():
+        rms = None
+        if name.startswith("bk["):
+            rms = rms_of("bq" + name[2:])
+        if name[:2] in ("Wq", "Wk", "bq", "bk") and (rms == 0.0 or rms_of(name) == 0.0):
+            rms = rms_of(name[0] + "v" + name[2:])
+        t = tail if (name[0] == "W" or not weights_only_tail) else None
+        assert_params_close(gpu[..., sl], orc[..., sl], rtol=RTOL_BF16, tail=t, rms=rms, what="%s %s" % (what, name))
 
 
 @pytest.mark.parametrize("dims", [dict(d_in=64, d_hidden=128, n_blocks=2, B_loc=100, K=2),
@@ -385,6 +415,101 @@ def test_resmlp_full_size_properties():
         outs.append((p, np.array(losses)))
         ctx.close()
     assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+
+
+def _vit_theta0(w, seed, qk_std):
+    """Initial parameters with non-trivial biases / LayerNorm parameters and q|k|v weights of standard
+    deviation about qk_std, which sets how far the attention probabilities are from uniform."""
+    rng = np.random.default_rng(seed)
+    th0 = workloads.theta0(w).astype(np.float64)
+    th0 += 0.02 * rng.standard_normal(th0.size)
+    for name, sl in _resmlp_groups(w):
+        if name[:2] in ("Wq", "Wk", "Wv"):
+            th0[sl] += qk_std * rng.standard_normal(len(sl))
+    return th0.astype(np.float32)
+
+
+# Gradients that pass through the attention core see three more bf16 roundings in a row (q|k|v, the
+# probabilities, d scores) than those of the MLP sub-block: their noise is about 0.5 % of a group's
+# rms (0.7 % where only 15 tokens are summed over), so the 2e-2 bound is three to four standard
+# deviations and a few entries of a matrix of 4 096 - 16 384 land beyond it (never by much).
+VIT_TAIL = (1e-3, 1.5)
+
+
+@pytest.mark.parametrize("dims", [
+    dict(d_in=64, n_heads=1, seq_len=5, B_loc=15, d_hidden=128, n_blocks=1, K=2),       # one ragged block
+    dict(d_in=128, n_heads=2, seq_len=70, B_loc=280, d_hidden=256, n_blocks=2, K=2),    # 3 blocks, ragged
+    dict(d_in=128, n_heads=2, seq_len=197, B_loc=394, d_hidden=128, n_blocks=1, K=2),   # the paper's length
+    dict(d_in=64, n_heads=1, seq_len=224, B_loc=224, d_hidden=64, n_blocks=1, K=1),     # the maximum, not ragged
+    dict(d_in=64, n_heads=1, seq_len=32, B_loc=96, d_hidden=64, n_blocks=1, K=1),       # exactly one block
+    dict(d_in=64, n_heads=1, seq_len=1, B_loc=40, d_hidden=64, n_blocks=1, K=1),        # degenerate: p = 1
+])
+def test_vit_block_gradient_single_step(dims):
+    """Attention + MLP blocks (the 'vit' workload at reduced sizes): every parameter group of the
+    gradient against the oracle, to the bf16 tolerance.  Scores of standard deviation about 0.5:
+    probabilities within a sequence differ by factors of several."""
+    w = workloads.get("vit", T=8, T_warm=2, **dims)
+    th0 = _vit_theta0(w, 11, 0.06)
+    ctx = gpu_ctx(w, theta0=th0)
+    orc = oracle_run(w, theta0=th0)
+    ctx.local_step()
+    g = ctx.grads.cpu().numpy()
+    loss = ctx.read_loss()
+    for k in range(dims["K"]):
+        want, wl = orc.grad(k, 0, th0.astype(np.float64))
+        assert loss[k] == pytest.approx(wl, rel=1e-2)
+        _assert_groups_close(w, g[k], want, "vit grad k=%d" % k, tail=VIT_TAIL, weights_only_tail=True)
+    ctx.close()
+
+
+def test_vit_block_gradient_with_sharp_attention():
+    """Scores of standard deviation about 2 (the largest of a row near 6, probabilities spread over
+    several orders of magnitude): the maximum subtraction, the masking of the ragged tail and the
+    saved log-sum-exp all matter here.  A score s computed from bf16 q and k carries an absolute
+    error of about |s| 2^-9, which the exponential turns into a relative error of the probability:
+    the noise of the gradients grows with the scores (0.8 % of a group's rms here; 3 % at scores
+    twice as large), whatever the kernel.  The bound is the same (2.5 standard deviations here), so
+    up to 3 % of a group's entries may pass it, none by more than a factor 3; in addition the rms
+    error of every group stays below 1.5 % of its rms."""
+    dims = dict(d_in=128, n_heads=2, seq_len=70, B_loc=280, d_hidden=256, n_blocks=2, K=2)
+    w = workloads.get("vit", T=8, T_warm=2, **dims)
+    th0 = _vit_theta0(w, 11, 0.12)
+    ctx = gpu_ctx(w, theta0=th0)
+    orc = oracle_run(w, theta0=th0)
+    ctx.local_step()
+    g = ctx.grads.cpu().numpy()
+    for k in range(2):
+        want, wl = orc.grad(k, 0, th0.astype(np.float64))
+        assert ctx.read_loss()[k] == pytest.approx(wl, rel=1e-2)
+        _assert_groups_close(w, g[k], want, "vit sharp grad k=%d" % k, tail=(3e-2, 3.0))
+        for name, sl in _resmlp_groups(w):
+            if not name.startswith("bk["):
+                err, ref = g[k, sl] - want[sl], want[sl]
+                assert np.sqrt(np.mean(err * err)) <= 1.5e-2 * np.sqrt(np.mean(ref * ref)), name
+    ctx.close()
+
+
+def test_vit_short_run():
+    """Local AdamW + QSR over attention + MLP blocks at reduced size."""
+    w = workloads.get("vit", d_in=64, n_heads=1, seq_len=25, d_hidden=128, n_blocks=2, B_loc=100, K=2, T=40,
+                      T_warm=4, eta_max=8e-4, alpha=0.0035)
+    th0 = _vit_theta0(w, 12, 0.06)
+    ctx = gpu_ctx(w, theta0=th0)
+    orc = oracle_run(w, n_threads=2, theta0=th0)
+    ctx.step(40); orc.step(40)
+    st, Hs = ctx.read_sync_log()
+    assert list(st) == list(orc.sync_log) and list(Hs) == list(orc.H_log) and len(st) >= 2
+    p = ctx.params.cpu().numpy()
+    for name, sl in _resmlp_groups(w):
+        # The key bias does not enter the model's function (the softmax ignores a shift common to
+        # all scores of a query): its exact gradient is zero, its bf16 gradient is rounding noise, and
+        # AdamW's normalization turns any non-zero gradient into steps of size eta.  Its value is
+        # not unique; what is compared is everything the loss depends on.
+        if name.startswith("bk["):
+            continue
+        assert_params_close(p[:, sl], orc.theta[:, sl], rtol=RTOL_BF16, what="vit params %s" % name)
+    assert all(np.array_equal(p[k], p[0]) for k in range(2))
+    ctx.close()
 
 
 def test_resmlp_short_run():
