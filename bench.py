@@ -140,9 +140,14 @@ def run_workload(name, steps, warmup, kernel_timing=True):
         # the dense contraction dominates: 6 GEMMs of 2*M*d*dh flop per block and worker; the
         # duration is that of the whole gradient stage (GEMMs and their HBM-bound helpers)
         flops = 6 * w["n_blocks"] * K * 2.0 * w["B_loc"] * w["d_in"] * w["d_hidden"]
+        if w.get("n_heads", 0):
+            # attention sub-block: q|k|v and output projections (4 d^2 weights, forward + data
+            # gradient + weight gradient) and the core's six products of M x seq_len x d each
+            # (q k^T, p v forward; dV, dP, dQ, dK backward; recomputed scores not counted)
+            flops += w["n_blocks"] * K * w["B_loc"] * (3 * 2.0 * 4 * w["d_in"] ** 2 + 6 * 2.0 * w["seq_len"] * w["d_in"])
         g_ms = ms[0] / cnt[0]
         ach = flops / (g_ms * 1e-3) / 1e12
-        roofline = {"kernel": "gradient stage: gemm_nt_bf16_kernel / gemm_pp_tn_kernel + helpers",
+        roofline = {"kernel": "gradient stage: gemm_nt_bf16_kernel / gemm_pp_tn_kernel%s + helpers" % (" / attn_*_kernel" if w.get("n_heads", 0) else ""),
                     "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "avg_ms": g_ms,
                     "launches": cnt[0], "flops_per_launch": flops}
@@ -238,7 +243,8 @@ def clip_probe(name):
 
 # short runs of the other workloads, reported next to the headline one
 OTHER_WORKLOADS = {"lsq": dict(steps=None, warmup=5), "mlp": dict(steps=None, warmup=5),
-                   "resmlp": dict(steps=10, warmup=2), "flat350m": dict(steps=100, warmup=2)}
+                   "resmlp": dict(steps=10, warmup=2), "vit": dict(steps=10, warmup=2),
+                   "flat350m": dict(steps=100, warmup=2)}
 
 
 def main():
@@ -246,12 +252,12 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="flat60m", choices=["flat60m", "flat350m", "lsq", "mlp", "resmlp"])
+    ap.add_argument("--workload", default="flat60m", choices=["flat60m", "flat350m", "lsq", "mlp", "resmlp", "vit"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="skip the per-kernel HIP events (the roofline object is then null)")
     ap.add_argument("--headline-only", action="store_true",
-                    help="do not add the short runs of the four other workloads (per_workload)")
+                    help="do not add the short runs of the other workloads (per_workload)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: the K workers are simulated on ONE GPU; "

@@ -4,26 +4,32 @@
 // 196-197 tokens).  The projections around it are ordinary GEMMs (gemm_bf16.h, gemm_pp.h).
 //
 // One workgroup per (sequence, head, worker); sequences are short, so a whole head's K and V (or
-// Q and dO) tiles sit in LDS and each wavefront owns one block of 32 tokens.  Everything is
-// computed in the transposed sense, S^T = K Q^T, so that a lane owns one query (the column l%32
-// of v_mfma_f32_32x32x16_bf16's result) and the keys run over its 16 accumulator registers:
+// Q and dO) tiles sit in LDS, as they are in memory ([token][feature]), and each wavefront owns one
+// block of 32 tokens.  Everything is computed in the transposed sense, S^T = K Q^T, so that a lane
+// owns one query (the column l%32 of v_mfma_f32_32x32x16_bf16's result) and the keys run over its
+// 16 accumulator registers:
 //   * the softmax statistics of a query are reductions over a lane's own registers plus one
-//     exchange with lane l^32;
+//     exchange with lane l^32 (kept as running maximum and sum over the key blocks, the partial
+//     output rescaled when the maximum moves);
 //   * the probabilities are, as they lie in the registers, the B operand of the next product
 //     (O^T = V^T P^T): accumulator registers 8c..8c+7 of a lane are eight key indices of one
 //     16-wide contraction step.  Which eight is a fixed permutation (keys 16c + 8(j/4) + 4(l/32) +
 //     j%4 for slot j), and a contraction may run in any order as long as both operands use the
-//     same one: the A operand is read from a transposed [feature][token] copy in LDS at exactly
-//     those token indices (two 8-byte reads).  No probability ever passes through LDS.
+//     same one: the A operand, V^T, comes from the [token][feature] tile through the LDS transpose
+//     read (ds_read_b64_tr_b16), whose 4-token groups are pointed at exactly those tokens.
+//     No probability ever passes through LDS, and no transposed copy of a tile exists.
 // The backward pass recomputes the probabilities from the saved log-sum-exp (base 2) of each query
 // and splits in two kernels by what is summed over: dK, dV (a wavefront owns 32 keys and walks the
-// query blocks, lanes = keys, S itself rather than S^T) and dQ (a wavefront owns 32 queries and
-// walks the key blocks, lanes = queries).
+// query blocks, lanes = keys, S itself rather than S^T; dV and dK in two passes over the query
+// blocks, which keeps the registers of a wavefront under 128 so that two workgroups share a
+// compute unit and one's loads overlap the other's products) and dQ (a wavefront owns 32 queries
+// and walks the key blocks, lanes = queries).
 //
 // Limits: head width 64, sequence length <= 224 (7 blocks of 32; the last block may be ragged:
 // rows beyond the sequence are zero in LDS and masked in the probabilities).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <type_traits>
 #include "gemm_bf16.h"
 
 namespace qsr {
@@ -31,8 +37,9 @@ namespace qsr {
 constexpr int ATT_DK = 64;                    // head width
 constexpr int ATT_MAXB = 7;                   // 32-token blocks per sequence
 constexpr int ATT_ROWS = ATT_MAXB * 32;
-constexpr int ATT_LDR = ATT_DK + 8;           // row stride (bf16) of a [token][feature] tile in LDS
-constexpr int ATT_LDT = ATT_ROWS + 8;         // row stride (bf16) of a [feature][token] tile in LDS
+constexpr int ATT_LDR = ATT_DK + 8;           // row stride (bf16) of a [token][feature] tile in LDS:
+                                              // 16-byte fragment reads and transpose reads both conflict-free
+constexpr int ATT_TILE = ATT_ROWS * ATT_LDR;  // elements of one tile
 
 struct AttnArgs {
     const bf16_t *QKV; long long sQKV;        // [M][3d] per worker: q | k | v, head h in columns h*64..
@@ -53,6 +60,14 @@ __device__ __forceinline__ bf16x8 att_zero8()
     return z;
 }
 
+// A zero accumulator as a constant: the first MFMA of a chain then takes the inline constant 0
+// instead of sixteen register moves.
+__device__ __forceinline__ f32x16 att_zero16()
+{
+    const f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    return z;
+}
+
 // eight consecutive accumulator registers as one MFMA operand (the k-slot permutation above)
 __device__ __forceinline__ bf16x8 att_pack8(const float (&v)[16], int c)
 {
@@ -62,37 +77,45 @@ __device__ __forceinline__ bf16x8 att_pack8(const float (&v)[16], int c)
     return r;
 }
 
-// A operand from a [feature][token] tile: feature row, tokens t0..t0+3 and t0+8..t0+11
-__device__ __forceinline__ bf16x8 att_read_t(const bf16_t *tile, int row, int t0)
+// A operand "tile^T" from a [token][feature] tile: row = feature 32 fb + l%32, contraction slots =
+// tokens t0 + 8(j/4) + 4(l/32) + j%4.  The LDS transpose read hands lane j of each group of 16
+// lanes element j%4 of the 64-bit words addressed by lanes j/4, j/4+4, j/4+8, j/4+12 of the group:
+// lane r = q + 4e of a group points at token e, features 4q..4q+3 of a 4-token x 16-feature block.
+__device__ __forceinline__ bf16x8 att_read_tr(const bf16_t *tile, int t0, int fb, int lane)
 {
-    const bf16x4 lo = *(const bf16x4 *)(tile + row * ATT_LDT + t0);
-    const bf16x4 hi = *(const bf16x4 *)(tile + row * ATT_LDT + t0 + 8);
-    bf16x8 r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-    return r;
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    const int grp = lane >> 4, r16 = lane & 15;
+    const bf16_t *q0 = tile + (t0 + (grp >> 1) * 4 + (r16 >> 2)) * ATT_LDR + fb * 32 + (grp & 1) * 16 + (r16 & 3) * 4;
+    union { struct { s16x4 a, b; } s; bf16x8 v; } u;
+    u.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)q0);
+    u.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(q0 + 8 * ATT_LDR));
+    return u.v;
+}
+
+// rows [0, 32 nb) of one head's [S][64] slice (row stride ld in global memory) -> LDS tile, rows >= S zero
+__device__ __forceinline__ void att_load_tile(bf16_t *tile, const bf16_t *src, long long ld, int S, int nb, int tid)
+{
+    for (int it = tid; it < nb * 256; it += nb * 64) {
+        const int t = it >> 3, pc = it & 7;
+        bf16x8 v = att_zero8();
+        if (t < S) v = *(const bf16x8 *)(src + (long long)t * ld + pc * 8);
+        *(bf16x8 *)(tile + t * ATT_LDR + pc * 8) = v;
+    }
 }
 
 // Forward: O and the log-sum-exp per query.  blockDim.x = 64 * nb, wavefront w owns queries 32w..
-__global__ __launch_bounds__(64 * ATT_MAXB) void attn_fwd_kernel(AttnArgs a)
+__global__ __launch_bounds__(64 * ATT_MAXB, 4) void attn_fwd_kernel(AttnArgs a)
 {
-    __shared__ __attribute__((aligned(16))) bf16_t Ks[ATT_ROWS * ATT_LDR];
-    __shared__ __attribute__((aligned(16))) bf16_t Vt[ATT_DK * ATT_LDT];
+    __shared__ __attribute__((aligned(16))) bf16_t Ks[ATT_TILE];
+    __shared__ __attribute__((aligned(16))) bf16_t Vs[ATT_TILE];
     const int seq = blockIdx.x, head = blockIdx.y, z = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5, l32 = lane & 31;
     const int S = a.S, nb = a.nb;
     const long long ld = 3LL * a.d;
     const bf16_t *base = a.QKV + (long long)z * a.sQKV + (long long)seq * S * ld + head * ATT_DK;
 
-    for (int it = tid; it < nb * 256; it += nb * 64) {
-        const int t = it >> 3, pc = it & 7;
-        bf16x8 kv = att_zero8(), vv = att_zero8();
-        if (t < S) {
-            kv = *(const bf16x8 *)(base + (long long)t * ld + a.d + pc * 8);
-            vv = *(const bf16x8 *)(base + (long long)t * ld + 2 * a.d + pc * 8);
-        }
-        *(bf16x8 *)(Ks + t * ATT_LDR + pc * 8) = kv;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) Vt[(pc * 8 + e) * ATT_LDT + t] = vv[e];
-    }
+    att_load_tile(Ks, base + a.d, ld, S, nb, tid);
+    att_load_tile(Vs, base + 2 * a.d, ld, S, nb, tid);
     const int q = wave * 32 + l32;
     const int qrow = min(q, S - 1);
     bf16x8 qf[4];
@@ -100,64 +123,61 @@ __global__ __launch_bounds__(64 * ATT_MAXB) void attn_fwd_kernel(AttnArgs a)
     for (int c = 0; c < 4; ++c) qf[c] = *(const bf16x8 *)(base + (long long)qrow * ld + c * 16 + hf * 8);
     __syncthreads();
 
-    // scores, transposed: st[kb][i] = q . k_key, key = 32 kb + 8 (i/4) + 4 hf + i%4
-    float st[ATT_MAXB][16];
-    float mx = -INFINITY;
+    // Running softmax over the key blocks.  m is the reference exponent of the probabilities held so
+    // far (both halves of a query agree on it), sum this half's share of their sum.  m follows the
+    // running maximum lazily: it moves only when a block's maximum exceeds it by more than 8 (in
+    // log2 units), so probabilities stay below 2^8 and the rescaling of the partial output, 32
+    // multiplications per lane, is skipped for most blocks (the branch is uniform over the
+    // wavefront).  Keys beyond the sequence exist only in the last block: only that one is masked.
+    float m = -INFINITY, sum = 0.f;
+    f32x16 ot[2] = {att_zero16(), att_zero16()};      // O^T = V^T P^T, unnormalized
+    auto block = [&](int kb, auto masked) {
+        // scores, transposed: acc[i] = q . k_key, key = 32 kb + 8 (i/4) + 4 hf + i%4
+        f32x16 acc = att_zero16();
 #pragma unroll
-    for (int kb = 0; kb < ATT_MAXB; ++kb) {
-        if (kb < nb) {
-            f32x16 acc;
+        for (int c = 0; c < 4; ++c) {
+            const bf16x8 kf = *(const bf16x8 *)(Ks + (kb * 32 + l32) * ATT_LDR + c * 16 + hf * 8);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[c], acc, 0, 0, 0);
+        }
+        float st[16];
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+        for (int i = 0; i < 16; ++i) {
+            st[i] = acc[i];
+            if (decltype(masked)::value && kb * 32 + (i >> 2) * 8 + hf * 4 + (i & 3) >= S) st[i] = -INFINITY;
+        }
+        float mx = st[0];
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const bf16x8 kf = *(const bf16x8 *)(Ks + (kb * 32 + l32) * ATT_LDR + c * 16 + hf * 8);
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[c], acc, 0, 0, 0);
-            }
+        for (int i = 1; i < 16; ++i) mx = fmaxf(mx, st[i]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * a.c2;  // finite: every block holds a key of the sequence
+        const bool move = mx > m + 8.0f;
+        if (__builtin_amdgcn_ballot_w64(move)) {
+            const float m_new = move ? mx : m;
+            const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+            sum *= alpha;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int key = kb * 32 + (i >> 2) * 8 + hf * 4 + (i & 3);
-                const float v = key < S ? acc[i] * a.c2 : -INFINITY;
-                st[kb][i] = v;
-                mx = fmaxf(mx, v);
+            for (int fb = 0; fb < 2; ++fb)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) ot[fb][e] *= alpha;
+            m = m_new;
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            st[i] = __builtin_amdgcn_exp2f(fmaf(st[i], a.c2, -m));
+            sum += st[i];
+        }
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const bf16x8 pb = att_pack8(st, c);
+#pragma unroll
+            for (int fb = 0; fb < 2; ++fb) {
+                const bf16x8 vf = att_read_tr(Vs, kb * 32 + 16 * c, fb, lane);
+                ot[fb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb, ot[fb], 0, 0, 0);
             }
         }
-    }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    float sum = 0.f;
-#pragma unroll
-    for (int kb = 0; kb < ATT_MAXB; ++kb) {
-        if (kb < nb) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const float p = __builtin_amdgcn_exp2f(st[kb][i] - mx);
-                st[kb][i] = p;
-                sum += p;
-            }
-        }
-    }
+    };
+    for (int kb = 0; kb < nb - 1; ++kb) block(kb, std::false_type{});
+    block(nb - 1, std::true_type{});
     sum += __shfl_xor(sum, 32, 64);
-
-    // O^T = V^T P^T
-    f32x16 ot[2];
-#pragma unroll
-    for (int fb = 0; fb < 2; ++fb)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) ot[fb][e] = 0.f;
-#pragma unroll
-    for (int kb = 0; kb < ATT_MAXB; ++kb) {
-        if (kb < nb) {
-#pragma unroll
-            for (int c = 0; c < 2; ++c) {
-                const bf16x8 pb = att_pack8(st[kb], c);
-#pragma unroll
-                for (int fb = 0; fb < 2; ++fb) {
-                    const bf16x8 vf = att_read_t(Vt, fb * 32 + l32, kb * 32 + 16 * c + hf * 4);
-                    ot[fb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb, ot[fb], 0, 0, 0);
-                }
-            }
-        }
-    }
     if (q < S) {
         const float inv = 1.0f / sum;
         const long long tok = (long long)seq * S + q;
@@ -170,24 +190,21 @@ __global__ __launch_bounds__(64 * ATT_MAXB) void attn_fwd_kernel(AttnArgs a)
                             (bf16_t)(ot[fb][4 * g + 2] * inv), (bf16_t)(ot[fb][4 * g + 3] * inv)};
                 *(bf16x4 *)(o + fb * 32 + g * 8 + hf * 4) = r;
             }
-        if (hf == 0) a.LSE[(long long)z * a.sLSE + (long long)head * a.M + tok] = mx + log2f(sum);
+        if (hf == 0) a.LSE[(long long)z * a.sLSE + (long long)head * a.M + tok] = m + log2f(sum);
     }
 }
 
-constexpr size_t ATT_BWD_KV_SMEM = (size_t)(2 * ATT_ROWS * ATT_LDR + 2 * ATT_DK * ATT_LDT) * sizeof(bf16_t) + 2 * ATT_ROWS * sizeof(float);
-constexpr size_t ATT_BWD_Q_SMEM = (size_t)(2 * ATT_ROWS * ATT_LDR + ATT_DK * ATT_LDT) * sizeof(bf16_t);
+constexpr size_t ATT_BWD_KV_SMEM = (size_t)2 * ATT_TILE * sizeof(bf16_t) + 2 * ATT_ROWS * sizeof(float);
 
 // Backward, dK and dV: wavefront w owns keys 32w.. (lanes = keys) and walks the query blocks.
 //   P = 2^(c2 S - lse),  dV = P^T dO,  dP = dO V^T,  D = rowsum(dO o),  dS = P (dP - D),
 //   dK = dS^T Q / sqrt(dk)
-__global__ __launch_bounds__(64 * ATT_MAXB) void attn_bwd_kv_kernel(AttnArgs a)
+__global__ __launch_bounds__(64 * ATT_MAXB, 4) void attn_bwd_kv_kernel(AttnArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char att_smem[];
     bf16_t *Qs = (bf16_t *)att_smem;
-    bf16_t *dOs = Qs + ATT_ROWS * ATT_LDR;
-    bf16_t *Qt = dOs + ATT_ROWS * ATT_LDR;
-    bf16_t *dOt = Qt + ATT_DK * ATT_LDT;
-    float *Ds = (float *)(dOt + ATT_DK * ATT_LDT);
+    bf16_t *dOs = Qs + ATT_TILE;
+    float *Ds = (float *)(dOs + ATT_TILE);
     float *Ls = Ds + ATT_ROWS;
     const int seq = blockIdx.x, head = blockIdx.y, z = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5, l32 = lane & 31;
@@ -212,11 +229,7 @@ __global__ __launch_bounds__(64 * ATT_MAXB) void attn_bwd_kv_kernel(AttnArgs a)
         *(bf16x8 *)(dOs + t * ATT_LDR + pc * 8) = dv;
         float dot = 0.f;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            Qt[(pc * 8 + e) * ATT_LDT + t] = qv[e];
-            dOt[(pc * 8 + e) * ATT_LDT + t] = dv[e];
-            dot = fmaf((float)dv[e], (float)ov[e], dot);
-        }
+        for (int e = 0; e < 8; ++e) dot = fmaf((float)dv[e], (float)ov[e], dot);
         dot += __shfl_xor(dot, 1, 64);
         dot += __shfl_xor(dot, 2, 64);
         dot += __shfl_xor(dot, 4, 64);
@@ -227,33 +240,76 @@ __global__ __launch_bounds__(64 * ATT_MAXB) void attn_bwd_kv_kernel(AttnArgs a)
     }
     const int key = wave * 32 + l32;
     const int krow = min(key, S - 1);
-    bf16x8 kf[4], vf[4];
+    bf16x8 kf[4];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        kf[c] = *(const bf16x8 *)(base + (long long)krow * ld + a.d + c * 16 + hf * 8);
-        vf[c] = *(const bf16x8 *)(base + (long long)krow * ld + 2 * a.d + c * 16 + hf * 8);
-    }
+    for (int c = 0; c < 4; ++c) kf[c] = *(const bf16x8 *)(base + (long long)krow * ld + a.d + c * 16 + hf * 8);
     __syncthreads();
+    bf16_t *dst = a.DQKV + (long long)z * a.sDQKV + (tok0 + krow) * ld + head * ATT_DK;
 
-    f32x16 dvt[2], dkt[2];
-#pragma unroll
-    for (int fb = 0; fb < 2; ++fb)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) { dvt[fb][e] = 0.f; dkt[fb][e] = 0.f; }
-
-    for (int qb = 0; qb < nb; ++qb) {
-        f32x16 sacc, dpacc;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) { sacc[e] = 0.f; dpacc[e] = 0.f; }
+    // Scores of query block qb against this lane's key: rows of the MFMA result = queries
+    // 32 qb + 8 (i/4) + 4 hf + i%4, column = the key.  Nothing is masked: a query row beyond the
+    // sequence has q = dO = 0 in LDS and lse = D = 0, so its probability is 2^0 and it multiplies
+    // zeros in both products; a key beyond the sequence is a lane of its own (an MFMA column),
+    // whose results are not stored.
+    auto scores = [&](int qb) {
+        f32x16 sacc = att_zero16();
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const bf16x8 qa = *(const bf16x8 *)(Qs + (qb * 32 + l32) * ATT_LDR + c * 16 + hf * 8);
-            const bf16x8 da = *(const bf16x8 *)(dOs + (qb * 32 + l32) * ATT_LDR + c * 16 + hf * 8);
             sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[c], sacc, 0, 0, 0);
+        }
+        return sacc;
+    };
+    auto store = [&](const f32x16 (&acc)[2], long long col0, float mul) {
+        if (key < S) {
+#pragma unroll
+            for (int fb = 0; fb < 2; ++fb)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    bf16x4 r = {(bf16_t)(acc[fb][4 * g] * mul), (bf16_t)(acc[fb][4 * g + 1] * mul),
+                                (bf16_t)(acc[fb][4 * g + 2] * mul), (bf16_t)(acc[fb][4 * g + 3] * mul)};
+                    *(bf16x4 *)(dst + col0 + fb * 32 + g * 8 + hf * 4) = r;
+                }
+        }
+    };
+
+    // pass 1: dV^T = dO^T P
+    f32x16 acc2[2] = {att_zero16(), att_zero16()};
+    for (int qb = 0; qb < nb; ++qb) {
+        const f32x16 sacc = scores(qb);
+        float p[16];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int q0 = qb * 32 + g * 8 + hf * 4;
+            const float4 l4 = *(const float4 *)(Ls + q0);
+            const float lq[4] = {l4.x, l4.y, l4.z, l4.w};
+#pragma unroll
+            for (int r = 0; r < 4; ++r) p[4 * g + r] = __builtin_amdgcn_exp2f(fmaf(sacc[4 * g + r], a.c2, -lq[r]));
+        }
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const bf16x8 pb = att_pack8(p, c);
+#pragma unroll
+            for (int fb = 0; fb < 2; ++fb)
+                acc2[fb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(att_read_tr(dOs, qb * 32 + 16 * c, fb, lane), pb, acc2[fb], 0, 0, 0);
+        }
+    }
+    store(acc2, 2LL * a.d, 1.0f);
+
+    // pass 2: dK^T = Q^T dS
+    bf16x8 vf[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) vf[c] = *(const bf16x8 *)(base + (long long)krow * ld + 2 * a.d + c * 16 + hf * 8);
+    acc2[0] = att_zero16(); acc2[1] = att_zero16();
+    for (int qb = 0; qb < nb; ++qb) {
+        const f32x16 sacc = scores(qb);
+        f32x16 dpacc = att_zero16();
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const bf16x8 da = *(const bf16x8 *)(dOs + (qb * 32 + l32) * ATT_LDR + c * 16 + hf * 8);
             dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vf[c], dpacc, 0, 0, 0);
         }
-        // rows of the result = queries 32 qb + 8 (i/4) + 4 hf + i%4, column = this lane's key
-        float p[16], ds[16];
+        float ds[16];
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const int q0 = qb * 32 + g * 8 + hf * 4;
@@ -262,49 +318,26 @@ __global__ __launch_bounds__(64 * ATT_MAXB) void attn_bwd_kv_kernel(AttnArgs a)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int i = 4 * g + r;
-                const bool valid = key < S && q0 + r < S;
-                const float pv = valid ? __builtin_amdgcn_exp2f(fmaf(sacc[i], a.c2, -lq[r])) : 0.f;
-                p[i] = pv;
-                ds[i] = pv * (dpacc[i] - dq[r]);
+                ds[i] = __builtin_amdgcn_exp2f(fmaf(sacc[i], a.c2, -lq[r])) * (dpacc[i] - dq[r]);
             }
         }
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
-            const bf16x8 pb = att_pack8(p, c), sb = att_pack8(ds, c);
+            const bf16x8 sb = att_pack8(ds, c);
 #pragma unroll
-            for (int fb = 0; fb < 2; ++fb) {
-                const bf16x8 dot_ = att_read_t(dOt, fb * 32 + l32, qb * 32 + 16 * c + hf * 4);
-                const bf16x8 qt_ = att_read_t(Qt, fb * 32 + l32, qb * 32 + 16 * c + hf * 4);
-                dvt[fb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dot_, pb, dvt[fb], 0, 0, 0);
-                dkt[fb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt_, sb, dkt[fb], 0, 0, 0);
-            }
+            for (int fb = 0; fb < 2; ++fb)
+                acc2[fb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(att_read_tr(Qs, qb * 32 + 16 * c, fb, lane), sb, acc2[fb], 0, 0, 0);
         }
     }
-    if (key < S) {
-        bf16_t *dst = a.DQKV + (long long)z * a.sDQKV + (tok0 + key) * ld + head * ATT_DK;
-#pragma unroll
-        for (int fb = 0; fb < 2; ++fb)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int f = fb * 32 + g * 8 + hf * 4;
-                bf16x4 rk = {(bf16_t)(dkt[fb][4 * g] * a.scale), (bf16_t)(dkt[fb][4 * g + 1] * a.scale),
-                             (bf16_t)(dkt[fb][4 * g + 2] * a.scale), (bf16_t)(dkt[fb][4 * g + 3] * a.scale)};
-                bf16x4 rv = {(bf16_t)dvt[fb][4 * g], (bf16_t)dvt[fb][4 * g + 1], (bf16_t)dvt[fb][4 * g + 2],
-                             (bf16_t)dvt[fb][4 * g + 3]};
-                *(bf16x4 *)(dst + a.d + f) = rk;
-                *(bf16x4 *)(dst + 2 * a.d + f) = rv;
-            }
-    }
+    store(acc2, a.d, a.scale);
 }
 
 // Backward, dQ: wavefront w owns queries 32w.. (lanes = queries) and walks the key blocks.
 //   dQ = dS K / sqrt(dk), computed as dQ^T = K^T dS^T with dS^T in the registers
-__global__ __launch_bounds__(64 * ATT_MAXB) void attn_bwd_q_kernel(AttnArgs a)
+__global__ __launch_bounds__(64 * ATT_MAXB, 4) void attn_bwd_q_kernel(AttnArgs a)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char att_smem[];
-    bf16_t *Ks = (bf16_t *)att_smem;
-    bf16_t *Vs = Ks + ATT_ROWS * ATT_LDR;
-    bf16_t *Kt = Vs + ATT_ROWS * ATT_LDR;
+    __shared__ __attribute__((aligned(16))) bf16_t Ks[ATT_TILE];
+    __shared__ __attribute__((aligned(16))) bf16_t Vs[ATT_TILE];
     const int seq = blockIdx.x, head = blockIdx.y, z = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5, l32 = lane & 31;
     const int S = a.S, nb = a.nb;
@@ -313,18 +346,8 @@ __global__ __launch_bounds__(64 * ATT_MAXB) void attn_bwd_q_kernel(AttnArgs a)
     const bf16_t *dob = a.DO + (long long)z * a.sDO + tok0 * a.d + head * ATT_DK;
     const bf16_t *ob = a.O + (long long)z * a.sO + tok0 * a.d + head * ATT_DK;
 
-    for (int it = tid; it < nb * 256; it += nb * 64) {
-        const int t = it >> 3, pc = it & 7;
-        bf16x8 kv = att_zero8(), vv = att_zero8();
-        if (t < S) {
-            kv = *(const bf16x8 *)(base + (long long)t * ld + a.d + pc * 8);
-            vv = *(const bf16x8 *)(base + (long long)t * ld + 2 * a.d + pc * 8);
-        }
-        *(bf16x8 *)(Ks + t * ATT_LDR + pc * 8) = kv;
-        *(bf16x8 *)(Vs + t * ATT_LDR + pc * 8) = vv;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) Kt[(pc * 8 + e) * ATT_LDT + t] = kv[e];
-    }
+    att_load_tile(Ks, base + a.d, ld, S, nb, tid);
+    att_load_tile(Vs, base + 2 * a.d, ld, S, nb, tid);
     const int q = wave * 32 + l32;
     const int qrow = min(q, S - 1);
     bf16x8 qf[4], dof[4];
@@ -341,16 +364,11 @@ __global__ __launch_bounds__(64 * ATT_MAXB) void attn_bwd_q_kernel(AttnArgs a)
     const float L = a.LSE[(long long)z * a.sLSE + (long long)head * a.M + tok0 + qrow];
     __syncthreads();
 
-    f32x16 dqt[2];
-#pragma unroll
-    for (int fb = 0; fb < 2; ++fb)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) dqt[fb][e] = 0.f;
-
-    for (int kb = 0; kb < nb; ++kb) {
-        f32x16 sacc, dpacc;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) { sacc[e] = 0.f; dpacc[e] = 0.f; }
+    // Keys beyond the sequence exist only in the last block: only there the probabilities are masked
+    // (their K and V rows are zero in LDS, but 2^(-lse) need not be finite).
+    f32x16 dqt[2] = {att_zero16(), att_zero16()};
+    auto block = [&](int kb, auto masked) {
+        f32x16 sacc = att_zero16(), dpacc = att_zero16();
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const bf16x8 ka = *(const bf16x8 *)(Ks + (kb * 32 + l32) * ATT_LDR + c * 16 + hf * 8);
@@ -362,20 +380,20 @@ __global__ __launch_bounds__(64 * ATT_MAXB) void attn_bwd_q_kernel(AttnArgs a)
         float ds[16];
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            const int key = kb * 32 + (i >> 2) * 8 + hf * 4 + (i & 3);
-            const float pv = key < S ? __builtin_amdgcn_exp2f(fmaf(sacc[i], a.c2, -L)) : 0.f;
+            float pv = __builtin_amdgcn_exp2f(fmaf(sacc[i], a.c2, -L));
+            if (decltype(masked)::value && kb * 32 + (i >> 2) * 8 + hf * 4 + (i & 3) >= S) pv = 0.f;
             ds[i] = pv * (dpacc[i] - D);
         }
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
             const bf16x8 sb = att_pack8(ds, c);
 #pragma unroll
-            for (int fb = 0; fb < 2; ++fb) {
-                const bf16x8 kt_ = att_read_t(Kt, fb * 32 + l32, kb * 32 + 16 * c + hf * 4);
-                dqt[fb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt_, sb, dqt[fb], 0, 0, 0);
-            }
+            for (int fb = 0; fb < 2; ++fb)
+                dqt[fb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(att_read_tr(Ks, kb * 32 + 16 * c, fb, lane), sb, dqt[fb], 0, 0, 0);
         }
-    }
+    };
+    for (int kb = 0; kb < nb - 1; ++kb) block(kb, std::false_type{});
+    block(nb - 1, std::true_type{});
     if (q < S) {
         bf16_t *dst = a.DQKV + (long long)z * a.sDQKV + (tok0 + q) * ld + head * ATT_DK;
 #pragma unroll
@@ -408,15 +426,13 @@ inline hipError_t launch_attn_bwd(const AttnArgs &a, int heads, int K, hipStream
     if (!lds_limit_raised) {
         hipError_t e = hipFuncSetAttribute((const void *)attn_bwd_kv_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)ATT_BWD_KV_SMEM);
         if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute((const void *)attn_bwd_q_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)ATT_BWD_Q_SMEM);
-        if (e != hipSuccess) return e;
         lds_limit_raised = true;
     }
     dim3 grid((unsigned)(a.M / a.S), (unsigned)heads, (unsigned)K);
     attn_bwd_kv_kernel<<<grid, 64 * a.nb, ATT_BWD_KV_SMEM, s>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    attn_bwd_q_kernel<<<grid, 64 * a.nb, ATT_BWD_Q_SMEM, s>>>(a);
+    attn_bwd_q_kernel<<<grid, 64 * a.nb, 0, s>>>(a);
     return hipGetLastError();
 }
 
