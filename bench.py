@@ -7,7 +7,7 @@ the K-axis replica averaging and the next H from the quadratic rule.  The defaul
 the optimizer-only 60 M-parameter, 16-replica Local AdamW run (T = 5000, 8 rounds): with the
 default --steps the timed region is exactly one complete run, all averaging rounds included.
 
-After the headline run, the four other workloads are run briefly and reported under
+After the headline run, the five other workloads are run briefly and reported under
 "per_workload" (--headline-only skips them).  Prints ONE JSON line.
 """
 import argparse

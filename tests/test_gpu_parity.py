@@ -489,6 +489,37 @@ def test_vit_block_gradient_with_sharp_attention():
     ctx.close()
 
 
+def test_vit_full_size_properties():
+    """The 'vit' workload in the benchmark's launch configuration (8 workers, 12 encoder blocks of
+    width 768, 12 heads, 64 sequences of 197 tokens each): finite gradients, two runs bit-identical,
+    rows equal after an averaging, the loss falling.  Parity with the oracle is established on the
+    reduced sizes, which include this sequence length."""
+    w = workloads.get("vit", T=4, T_warm=0, H_base=2, alpha=0.0)
+    outs = []
+    for rep in range(2):
+        ctx = gpu_ctx(w)
+        losses = []
+        for t in range(4):
+            ctx.local_step()
+            if t == 0:
+                g = ctx.grads.cpu().numpy()
+                assert np.all(np.isfinite(g)) and float(np.abs(g).max()) > 0
+                for name, sl in _resmlp_groups(w):
+                    if not name.startswith("bk["):          # exactly zero in exact arithmetic
+                        assert float(np.abs(g[:, sl]).max()) > 0, name
+                del g
+            losses.append(ctx.read_loss().copy())
+            ctx.maybe_sync()
+        p = ctx.params.cpu().numpy()
+        st, Hs = ctx.read_sync_log()
+        assert list(st) == [2, 4] and list(Hs) == [2, 2]
+        assert np.all(np.isfinite(p)) and all(np.array_equal(p[k], p[0]) for k in range(w["K"]))
+        assert np.all(np.isfinite(losses)) and np.all(losses[3] < losses[0])
+        outs.append((p, np.array(losses)))
+        ctx.close()
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+
+
 def test_vit_short_run():
     """Local AdamW + QSR over attention + MLP blocks at reduced size."""
     w = workloads.get("vit", d_in=64, n_heads=1, seq_len=25, d_hidden=128, n_blocks=2, B_loc=100, K=2, T=40,
