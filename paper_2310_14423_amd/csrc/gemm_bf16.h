@@ -44,6 +44,8 @@ struct GemmNT {
     float *colsum_B;       // optional: colsum_B[z*s_colsum + n] = sum_k B[z][k][n]
     long long s_colsum;
     const bf16_t *zeros;   // 64 bytes of zeros, read in place of k-rows beyond K (needed if K % 32 != 0)
+    int split;             // > 1: the reduction is cut into `split` ranges of k_chunk rows (a multiple of 32);
+    int k_chunk;           //      range s of batch z is handed to the epilogue (and column sums) as batch z*split + s
 };
 
 // Epilogue.  The MFMA leaves lane l with 4 consecutive columns of row l%32, i.e. one store

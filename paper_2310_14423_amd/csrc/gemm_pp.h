@@ -40,6 +40,10 @@
 //    of the multiply phase.  Re-reading the slabs from LDS for them made the workgroups of the
 //    first M-tile 35 % slower than the rest.
 //
+//  * Problems with few tiles (a 768 x 768 gradient for 8 workers is 64) can have the reduction cut
+//    into ranges (GemmNT::split): each (tile, range) is a work item of its own, handed to the epilogue
+//    as a batch entry of its own; the caller adds the partial results up in a fixed order.
+//
 // The copies are written as inline asm: seen as a builtin, the compiler treats every later LDS
 // access as possibly aliasing the copies in flight and waits for all outstanding vector memory
 // operations before it.
@@ -68,16 +72,17 @@ __global__ __launch_bounds__(512) void gemm_pp_tn_kernel(GemmNT p, Epi epi, int 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;                     // wm is also the ping-pong group
     const int nx = (p.N + BN - 1) / BN, ny = (p.M + BM - 1) / BM;
-    const int nk = (p.K + BK - 1) / BK;                           // a ragged last slab is filled up with zero rows
-    const int per_z = nx * ny, T = Z * per_z, Tc = (T + 7) / 8;
+    const int split = p.split > 1 ? p.split : 1;                  // ranges of the reduction, each a work item
+    const int per_z = nx * ny, T = Z * split * per_z, Tc = (T + 7) / 8;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, slots = gridDim.x >> 3;
     const int c0 = xcd * Tc, c1 = min(T, c0 + Tc);
     const int n_my = c1 - c0 > slot ? (c1 - c0 - slot + slots - 1) / slots : 0;
     if (n_my == 0) return;
-    auto decode = [&](int i, int &z, int &m0, int &n0) {
+    // work item i of this workgroup: zz = batch * split + range, and the tile's origin
+    auto decode = [&](int i, int &zz, int &m0, int &n0) {
         const int f = c0 + slot + i * slots;
-        z = f / per_z;
-        int r = f - z * per_z;
+        zz = f / per_z;
+        int r = f - zz * per_z;
         const int pn = r / (ny * PANEL);
         r -= pn * ny * PANEL;
         const int bw = min(PANEL, nx - pn * PANEL);
@@ -91,11 +96,18 @@ __global__ __launch_bounds__(512) void gemm_pp_tn_kernel(GemmNT p, Epi epi, int 
     const unsigned lds_ring = (unsigned)(uintptr_t)(__attribute__((address_space(3))) void *)gemm_smem;
     const bf16_t *src[CPW];
     const long long stepA = (long long)BK * p.lda, stepB = (long long)BK * p.ldb;   // elements per slab
+    int k_end = p.K;                                // end of the current item's range of the reduction
+    int d_stage = 0;                                // stage the next copy goes to
+    int d_row = 0;                                  // first token of the next slab to copy
     auto set_src = [&](int i) {
-        int z, m0, n0;
-        decode(i, z, m0, n0);
-        const bf16_t *A = p.A + (long long)z * p.sA;
-        const bf16_t *B = p.B + (long long)z * p.sB;
+        int zz, m0, n0;
+        decode(i, zz, m0, n0);
+        const int z = zz / split, k0 = (zz - z * split) * (split > 1 ? p.k_chunk : 0);
+        k_end = split > 1 ? min(p.K, k0 + p.k_chunk) : p.K;
+        d_row = k0;
+        d_stage = 0;
+        const bf16_t *A = p.A + (long long)z * p.sA + (long long)k0 * p.lda;
+        const bf16_t *B = p.B + (long long)z * p.sB + (long long)k0 * p.ldb;
 #pragma unroll
         for (int c = 0; c < CPW; ++c) {
             const int chunk = c * 8 + wave;
@@ -107,8 +119,6 @@ __global__ __launch_bounds__(512) void gemm_pp_tn_kernel(GemmNT p, Epi epi, int 
                          : B + (long long)t * p.ldb + min(n0 + f, p.N - 8);
         }
     };
-    int d_stage = 0;                                // stage the next copy goes to
-    int d_row = 0;                                  // first token of the next slab to copy
     auto issue_slab = [&]() {                       // copies this wavefront's chunks of the next slab
 #pragma unroll
         for (int c = 0; c < CPW; ++c) {
@@ -116,7 +126,7 @@ __global__ __launch_bounds__(512) void gemm_pp_tn_kernel(GemmNT p, Epi epi, int 
             if (CHUNKS % 8 == 0 || chunk < CHUNKS) {
                 const unsigned dst = __builtin_amdgcn_readfirstlane(lds_ring + d_stage * STAGE_BYTES + chunk * 1024);
                 const int cc = chunk < A_CHUNKS ? chunk : chunk - A_CHUNKS;
-                const bf16_t *g = d_row + (cc & 1) * 16 + (lane >> 2) < p.K ? src[c] : p.zeros + (lane & 3) * 8;
+                const bf16_t *g = d_row + (cc & 1) * 16 + (lane >> 2) < k_end ? src[c] : p.zeros + (lane & 3) * 8;
                 asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" :: "s"(dst), "v"(g) : "memory", "m0");
                 src[c] += __builtin_amdgcn_readfirstlane(chunk) < A_CHUNKS ? stepA : stepB;
             }
@@ -171,10 +181,9 @@ __global__ __launch_bounds__(512) void gemm_pp_tn_kernel(GemmNT p, Epi epi, int 
     for (int ti = 0; ti < n_my; ++ti) {
         int cz, cm0, cn0;
         decode(ti, cz, cm0, cn0);
-        // prime the ring with the first NS-1 slabs of the tile
+        // prime the ring with the first NS-1 slabs of the item
         set_src(ti);
-        d_stage = 0;
-        d_row = 0;
+        const int nk = (k_end - d_row + BK - 1) / BK;             // a ragged last slab is filled up with zero rows
 #pragma unroll
         for (int s = 0; s < NS - 1; ++s)
             if (s < nk) issue_slab();
@@ -254,6 +263,7 @@ inline bool gemm_pp_tn_supports(const GemmNT &p)
 {
     if (p.K < 1 || p.lda % 8 != 0 || p.ldb % 8 != 0) return false;
     if (p.M % 8 != 0 || p.N % 8 != 0 || p.M < 8 || p.N < 8) return false;
+    if (p.split > 1 && (p.k_chunk < 32 || p.k_chunk % 32 != 0 || (long long)(p.split - 1) * p.k_chunk >= p.K)) return false;
     return p.K % 32 == 0 || p.zeros != nullptr;
 }
 

@@ -30,6 +30,7 @@ namespace qsr {
 static inline size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 constexpr float LN_EPS = 1e-5f;
+constexpr int WGRAD_SPLIT = 4;          // most ranges a weight gradient's token reduction is cut into
 constexpr int LN_ROWS_PER_WAVE = 16;
 
 struct ResWs {
@@ -50,6 +51,7 @@ struct ResWs {
     float *PART;   long long sPART;    // [2][wave_rows][d] partial dgamma, dbeta
     float *LPART;  long long sLPART;   // loss partials
     bf16_t *ZERO;                      // 256 bytes of zeros (stand-in rows of ragged GEMM slabs)
+    float *SPLITK, *SPLITKB;           // [K][WGRAD_SPLIT][largest weight matrix], [K][WGRAD_SPLIT][widest bias]
     // attention sub-blocks only
     bf16_t *QKV;   long long sQKV;     // [L][M][3d]
     bf16_t *O;     long long sO;       // [L][M][d]   attention output before the projection
@@ -96,6 +98,11 @@ static ResWs carve(const ModelDims &dm, void *ws, size_t *total)
     w.sPART = padded(2 * wave_rows * d, 4); w.PART = (float *)take(w.sPART, 4, K);
     w.sLPART = padded((M * d + 1023) / 1024, 4); w.LPART = (float *)take(w.sLPART, 4, K);
     w.ZERO = (bf16_t *)take(128, 2, 1);
+    {
+        const long long widest = heads > 0 && 3 * d > dh ? 3 * d : dh;
+        w.SPLITK = (float *)take(K * WGRAD_SPLIT * d * widest, 4, 1);
+        w.SPLITKB = (float *)take(K * WGRAD_SPLIT * widest, 4, 1);
+    }
     w.QKV = w.O = w.DO = w.DQKV = w.Wqb = w.WqTb = w.Wob = w.WoTb = nullptr; w.LSE = nullptr;
     w.sQKV = w.sO = w.sLSE = w.sDO = w.sDQKV = w.sWq = w.sWo = 0;
     if (heads > 0) {
@@ -538,6 +545,52 @@ static hipError_t gemm_tn(const GemmNT &p, const Epi &epi, int batch, hipStream_
 
 #define TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return e_; } while (0)
 
+// out[z][i] = part[z][0][i] + part[z][1][i] + ... (ascending: a fixed order), i < n, n a multiple of 4
+__global__ __launch_bounds__(256) void splitk_sum_kernel(const float *__restrict__ part, long long n, int split,
+                                                         float *__restrict__ out, long long sOut)
+{
+    const long long i = ((long long)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i >= n) return;
+    const int z = blockIdx.y;
+    const float *p = part + (long long)z * split * n + i;
+    float4 a = *(const float4 *)p;
+    for (int s = 1; s < split; ++s) {
+        const float4 b = *(const float4 *)(p + (long long)s * n);
+        a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+    }
+    *(float4 *)(out + (long long)z * sOut + i) = a;
+}
+
+// Weight gradient dW[z] = A[z]^T B[z] (p.M x p.N, rows contiguous, per-worker stride sOut) with the
+// bias gradient (column sums of B) as a by-product.  A gradient with few tiles for the chip's
+// persistent workgroups has its token reduction cut into up to WGRAD_SPLIT ranges, whose partial
+// results are added up afterwards (the 768 x 768 output projection of 8 workers is 64 tiles of
+// 192 x 384 for 256 compute units: 0.37 ms as one range each, as long as a gradient four times
+// its size).
+static hipError_t wgrad(GemmNT p, float *dW, float *db, long long sOut, const ResWs &w, int batch, hipStream_t s)
+{
+    p.zeros = w.ZERO;
+    const int tiles = ((p.M + 191) / 192) * ((p.N + 383) / 384) * batch;
+    const int cus = gemm_pp_cu_count();
+    int split = tiles * 2 <= cus ? (cus / tiles < WGRAD_SPLIT ? cus / tiles : WGRAD_SPLIT) : 1;
+    const int k_chunk = ((p.K + split - 1) / split + 31) / 32 * 32;
+    split = (p.K + k_chunk - 1) / k_chunk;
+    if (split <= 1) {
+        p.colsum_B = db; p.s_colsum = sOut;
+        EpiScaleF32 epi{dW, p.N, sOut, 1.0f};
+        return gemm_tn(p, epi, batch, s);
+    }
+    const long long MN = (long long)p.M * p.N;
+    p.split = split; p.k_chunk = k_chunk;
+    p.colsum_B = w.SPLITKB; p.s_colsum = p.N;
+    EpiScaleF32 epi{w.SPLITK, p.N, MN, 1.0f};
+    TRY(gemm_tn(p, epi, batch, s));
+    splitk_sum_kernel<<<dim3((unsigned)((MN / 4 + 255) / 256), (unsigned)batch), 256, 0, s>>>(w.SPLITK, MN, split, dW, sOut);
+    TRY(hipGetLastError());
+    splitk_sum_kernel<<<dim3((unsigned)((p.N / 4 + 255) / 256), (unsigned)batch), 256, 0, s>>>(w.SPLITKB, p.N, split, db, sOut);
+    return hipGetLastError();
+}
+
 hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g, const float *teacher,
                               void *ws, float *loss, const DevState *st, hipStream_t s)
 {
@@ -678,9 +731,8 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
         const long long ow = (long long)l * d * dh;
         // W2 and b2:  dW2 = a^T dx, db2 = column sums of dx (by-product of the same GEMM)
         {
-            GemmNT p{w.A + (long long)l * Mdh, w.DXb, dh, d, M, dh, d, w.sA, w.sDXb, g + ob2, P, w.ZERO};
-            EpiScaleF32 epi{g + oW2, d, P, 1.0f};
-            TRY(gemm_tn(p, epi, K, s));
+            GemmNT p{w.A + (long long)l * Mdh, w.DXb, dh, d, M, dh, d, w.sA, w.sDXb};
+            TRY(wgrad(p, g + oW2, g + ob2, P, w, K, s));
         }
         // dh = (dx W2^T) * gelu'(h)
         {
@@ -690,9 +742,8 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
         }
         // W1 and b1:  dW1 = u^T dh, db1 = column sums of dh
         {
-            GemmNT p{w.U + (long long)sub * Md, w.DH, d, dh, M, d, dh, w.sU, w.sDH, g + ob1, P, w.ZERO};
-            EpiScaleF32 epi{g + oW1, dh, P, 1.0f};
-            TRY(gemm_tn(p, epi, K, s));
+            GemmNT p{w.U + (long long)sub * Md, w.DH, d, dh, M, d, dh, w.sU, w.sDH};
+            TRY(wgrad(p, g + oW1, g + ob1, P, w, K, s));
         }
         // du = dh W1^T, then LayerNorm backward + residual
         {
@@ -708,9 +759,8 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
             bf16_t *QKVl = w.QKV + (long long)l * M * 3 * d, *Ol = w.O + (long long)l * Md;
             // Wo and bo:  dWo = o^T dx, dbo = column sums of dx
             {
-                GemmNT p{Ol, w.DXb, d, d, M, d, d, w.sO, w.sDXb, g + obo, P, w.ZERO};
-                EpiScaleF32 epi{g + oWo, d, P, 1.0f};
-                TRY(gemm_tn(p, epi, K, s));
+                GemmNT p{Ol, w.DXb, d, d, M, d, d, w.sO, w.sDXb};
+                TRY(wgrad(p, g + oWo, g + obo, P, w, K, s));
             }
             // do = dx Wo^T
             {
@@ -722,9 +772,8 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
             TRY(launch_attn_bwd(att, heads, K, s));
             // Wqkv and bqkv:  dWqkv = u^T dqkv, dbqkv = column sums of dqkv
             {
-                GemmNT p{w.U + (long long)sub * Md, w.DQKV, d, 3 * d, M, d, 3LL * d, w.sU, w.sDQKV, g + obq, P, w.ZERO};
-                EpiScaleF32 epi{g + oWq, 3LL * d, P, 1.0f};
-                TRY(gemm_tn(p, epi, K, s));
+                GemmNT p{w.U + (long long)sub * Md, w.DQKV, d, 3 * d, M, d, 3LL * d, w.sU, w.sDQKV};
+                TRY(wgrad(p, g + oWq, g + obq, P, w, K, s));
             }
             // du = dqkv Wqkv^T, then LayerNorm backward + residual
             {
