@@ -30,7 +30,7 @@ def test_strerror():
     assert L.qsr_strerror(-99) == b"unknown error"
 
 
-@pytest.mark.parametrize("name", ["lsq", "mlp", "flat60m", "resmlp", "flat350m"])
+@pytest.mark.parametrize("name", ["lsq", "mlp", "flat60m", "resmlp", "vit", "flat350m"])
 def test_named_workloads_validate(name):
     cfg, keep = make_config(workloads.get(name))
     assert qsr.validate(cfg) == (0, "ok")
@@ -66,6 +66,20 @@ def test_model_shape_checks():
     cfg, _ = make_config(workloads.get("lsq"))
     cfg.d_in = 1000
     assert qsr.validate(cfg)[0] == -1
+
+
+def test_attention_shape_checks():
+    """Heads are 64 wide, sequences have 1..224 tokens and divide the local batch; the parameter
+    count includes the attention arrays."""
+    ok = workloads.get("vit")
+    assert qsr.validate(make_config(ok)[0]) == (0, "ok")
+    for bad in (dict(n_heads=6), dict(seq_len=0), dict(seq_len=225), dict(seq_len=200), dict(n_heads=-1)):
+        cfg, _ = make_config(dict(ok, **bad))
+        assert qsr.validate(cfg)[0] == -1, bad
+    cfg, _ = make_config(dict(ok, P=workloads.get("resmlp")["P"]))
+    assert qsr.validate(cfg)[0] == -1
+    # the workspace grows by the q|k|v, attention-output and split-reduction buffers
+    assert qsr.workspace_bytes(make_config(ok)[0]) > qsr.workspace_bytes(make_config(workloads.get("resmlp"))[0])
 
 
 def test_null_arguments():
