@@ -30,9 +30,9 @@ BYTES_PER_AVERAGE = 8
 PMC_TRAFFIC = {"flat60m": {"sources": ["update.hip", "opt_elem.h"], "sha256_16": "79a601e2bc8f7857", "bytes": 26.870e9}}
 
 
-def measured_traffic(workload):
+def measured_traffic(workload, fused_gradient):
     import hashlib
-    ent = PMC_TRAFFIC.get(workload)
+    ent = PMC_TRAFFIC.get(workload + ("+fuse_gradient" if fused_gradient else ""))
     if not ent:
         return None
     h = hashlib.sha256()
@@ -74,14 +74,18 @@ def cpu_baseline(w, cpu_seconds_target=20.0):
                       "every step, double precision, %.1f s wall" % (w["K"], P, w["P"], steps, dt)}
 
 
-def run_workload(name, steps, warmup, kernel_timing=True):
+def run_workload(name, steps, warmup, kernel_timing=True, fuse_gradient=True):
     """Runs `steps` iterations of one workload (after `warmup` untimed ones and a restart at
-    t = 0) and returns the fields of the JSON line that depend on the workload."""
+    t = 0) and returns the fields of the JSON line that depend on the workload.  The
+    optimizer-only workloads run with the gradient drawn inside the update kernel unless
+    fuse_gradient is False (then a fill kernel writes it first, as a model's backward pass would)."""
     import torch
     import workloads
     import paper_2310_14423_amd as qsr
 
     w = workloads.get(name)
+    if w["model"] == "noise" and fuse_gradient and w["P"] % 4 == 0:
+        w["fuse_gradient"] = 2                 # drawn in registers, never written: 24 B per update
     K, P, T = w["K"], w["P"], w["T"]
     if steps is None:
         steps = T
@@ -118,7 +122,8 @@ def run_workload(name, steps, warmup, kernel_timing=True):
         collect()
     ctx.timing(False)
 
-    upd_bytes = BYTES_PER_UPDATE[w["opt"]] * K * P
+    # the update that draws its own gradient neither reads nor writes the gradient buffer
+    upd_bytes = (BYTES_PER_UPDATE[w["opt"]] - (4 if w.get("fuse_gradient") == 2 else 0)) * K * P
     roofline = None
     kernels = {}
     if cnt[0] > 0:
@@ -153,9 +158,10 @@ def run_workload(name, steps, warmup, kernel_timing=True):
                     "launches": cnt[0], "flops_per_launch": flops}
     elif cnt[1] > 0:
         ach = kernels["update_GBs"]
-        roofline = {"kernel": "update_%s_kernel" % w["opt"], "bound": "hbm", "achieved": ach,
+        roofline = {"kernel": "update_%s_kernel%s" % (w["opt"], " (gradient drawn inside, never in memory: 12 B read + 12 B written)" if w.get("fuse_gradient") else ""),
+                    "bound": "hbm", "achieved": ach,
                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
-                    "traffic": measured_traffic(name),
+                    "traffic": measured_traffic(name, bool(w.get("fuse_gradient"))),
                     "avg_ms": kernels["update_ms_avg"], "launches": cnt[1],
                     "bytes_per_launch": upd_bytes}
 
@@ -175,7 +181,8 @@ def run_workload(name, steps, warmup, kernel_timing=True):
         "value": K * P * steps / dt, "steps": steps, "ms_per_step": dt * 1e3 / steps,
         "dtype": "bf16" if w["model"] == "resmlp" else "f32",
         "config": {"workload": name, "K": K, "P": P, "T": T, "optimizer": w["opt"],
-                   "gradient": w["model"], "H_base": w["H_base"], "alpha": w["alpha"],
+                   "gradient": w["model"] + (" (drawn inside the update kernel, not stored)" if w.get("fuse_gradient") else ""),
+                   "H_base": w["H_base"], "alpha": w["alpha"],
                    "lr": w["lr"], "eta_max": w["eta_max"]},
         "sync_rounds": rounds,
         "hbm_GBs_update": kernels.get("update_GBs"),
@@ -254,6 +261,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="flat60m", choices=["flat60m", "flat350m", "lsq", "mlp", "resmlp", "vit"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-fuse-gradient", action="store_true",
+                    help="optimizer-only workloads: fill the gradient buffer with a kernel of its own "
+                         "instead of drawing the gradient inside the update kernel")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="skip the per-kernel HIP events (the roofline object is then null)")
     ap.add_argument("--headline-only", action="store_true",
@@ -269,7 +279,8 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
 
-    res, w = run_workload(args.workload, args.steps, args.warmup, not args.no_kernel_timing)
+    res, w = run_workload(args.workload, args.steps, args.warmup, not args.no_kernel_timing,
+                          not args.no_fuse_gradient)
     out = {"metric": "replica-param updates/s", "value": res["value"], "unit": "updates/s",
            "n_gpus": 1, "steps": res["steps"], "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -289,6 +300,10 @@ def main():
                 per[name] = {"error": "%s: %s" % (type(e).__name__, e)}
         out["per_workload"] = per
         if w["model"] in ("noise", "external"):
+            if w.get("fuse_gradient"):
+                # the same workload with the gradient written by a fill kernel first (500 iterations)
+                r, _ = run_workload(args.workload, 500, 5, True, False)
+                out["separate_gradient_fill"] = {k: r[k] for k in ("value", "steps", "ms_per_step", "kernels", "roofline")}
             out["fused_sync"] = fused_sync_probe(args.workload)
             out["gradient_clipping"] = clip_probe(args.workload)
     out["cpu_baseline"] = None if args.no_cpu_baseline else cpu_baseline(w)

@@ -87,6 +87,13 @@ typedef struct {
     int32_t n_heads;      /* QSR_MODEL_RESMLP: > 0 puts a multi-head self-attention sub-block (heads of
                              width 64, so d_in = 64 n_heads) in front of every MLP sub-block: the
                              encoder block of the paper's ViT-B (App. C.2).  0 = MLP sub-blocks only */
+    int32_t fuse_gradient;/* QSR_MODEL_NOISE: the gradient is drawn inside the update kernel: one pass instead
+                             of a fill and an update, parameters and optimizer state the same bit for
+                             bit.  1 = the draw is also written to `grads` (28 B per replica-parameter as
+                             before); 2 = `grads` is left untouched, the gradient never exists in memory
+                             (24 B).  Needs P % 4 == 0; not with parallel, fuse_sync or clip_norm.
+                             0 = off                                                          */
+    int32_t reserved;     /* must be 0                                                    */
     int64_t P;            /* parameters per worker, >= 1                                   */
     int64_t T;            /* total iterations, eta_t is defined for t in 0..T-1, >= 1      */
     int64_t T_warm;       /* linear warm-up 0 -> eta_max over the first T_warm iterations  */

@@ -33,7 +33,7 @@ class Config(C.Structure):
         ("K", C.c_int32), ("opt", C.c_int32), ("model", C.c_int32), ("lr_kind", C.c_int32),
         ("H_base", C.c_int32), ("n_milestones", C.c_int32), ("n_blocks", C.c_int32),
         ("power", C.c_int32), ("parallel", C.c_int32), ("average_state", C.c_int32),
-        ("fuse_sync", C.c_int32), ("n_heads", C.c_int32),
+        ("fuse_sync", C.c_int32), ("n_heads", C.c_int32), ("fuse_gradient", C.c_int32), ("reserved", C.c_int32),
         ("P", C.c_int64), ("T", C.c_int64), ("T_warm", C.c_int64), ("t_local_start", C.c_int64),
         ("t_swap_start", C.c_int64), ("B_loc", C.c_int64),
         ("d_in", C.c_int64), ("d_hidden", C.c_int64), ("d_out", C.c_int64), ("seq_len", C.c_int64),
@@ -85,6 +85,7 @@ def make_config(w, stream=0, eta_table=None):
     c.B_loc = w.get("B_loc", 0); c.d_in = w.get("d_in", 0); c.d_hidden = w.get("d_hidden", 0)
     c.d_out = w.get("d_out", 0); c.n_blocks = w.get("n_blocks", 0)
     c.n_heads = w.get("n_heads", 0); c.seq_len = w.get("seq_len", 0)
+    c.fuse_gradient = int(w.get("fuse_gradient", 0))
     c.momentum = w.get("mu", 0.0); c.beta1 = w.get("beta1", 0.9); c.beta2 = w.get("beta2", 0.999)
     c.eps = w.get("eps", 1e-8); c.weight_decay = w.get("lam", 0.0)
     c.grad_sigma = w.get("grad_sigma", 0.0); c.data_sigma = w.get("data_sigma", 0.0)

@@ -89,6 +89,10 @@ extern "C" int qsr_validate(const qsr_config *c, const char **why)
     else if (c->fuse_sync != 0 && c->fuse_sync != 1) w = "fuse_sync";
     else if (c->fuse_sync == 1 && (c->parallel == 1 || c->average_state == 1)) w = "fuse_sync with parallel or average_state";
     else if (c->n_heads < 0 || (c->n_heads > 0 && c->model != QSR_MODEL_RESMLP)) w = "n_heads";
+    else if (c->reserved != 0) w = "reserved";
+    else if (c->fuse_gradient < 0 || c->fuse_gradient > 2) w = "fuse_gradient";
+    else if (c->fuse_gradient && (c->model != QSR_MODEL_NOISE || c->parallel || c->fuse_sync || c->clip_norm > 0.0 || c->P % 4 != 0))
+        w = "fuse_gradient needs the noise model, P % 4 = 0, no parallel, fuse_sync or clip_norm";
     else if (!finite_ge0(c->clip_norm)) w = "clip_norm";
     else if (c->power < 0 || c->power > 8) w = "power";
     else if (c->parallel != 0 && c->parallel != 1) w = "parallel";
@@ -382,7 +386,7 @@ extern "C" int qsr_local_step(qsr_ctx *c)
     if (c->t_host >= c->cfg.T || c->need_sync_call) return QSR_ESTATE;
     const qsr_config &cfg = c->cfg;
 
-    if (cfg.model != QSR_MODEL_EXTERNAL) {             // Eq. (1): every worker's local gradient
+    if (cfg.model != QSR_MODEL_EXTERNAL && !cfg.fuse_gradient) {   // Eq. (1): every worker's local gradient
         Bracket br(c, 0);
         if (br.rc != QSR_OK) return br.rc;
         switch (cfg.model) {
@@ -421,7 +425,16 @@ extern "C" int qsr_local_step(qsr_ctx *c)
         if (cfg.clip_norm > 0.0)                        // App. C: per-worker factors min(1, c / (||g_k|| + 1e-6))
             HIP_TRY(launch_clip_coef(c->grads, cfg.K, cfg.P, (float)cfg.clip_norm, c->d_clip_part,
                                      c->d_clip_coef, c->d_clip_coef + cfg.K, c->stream));
-        if (cfg.opt == QSR_OPT_SGDM)
+        if (cfg.fuse_gradient && cfg.opt == QSR_OPT_SGDM)   // Eq. (1) and OPT in one pass (noise model)
+            HIP_TRY(launch_update_sgdm_noise(c->params, c->grads, c->state0, cfg.K, cfg.P, c->d_state, c->d_scal,
+                                             (float)cfg.momentum, (float)cfg.weight_decay, (float)cfg.grad_sigma,
+                                             cfg.seed, cfg.fuse_gradient == 1, c->stream));
+        else if (cfg.fuse_gradient)
+            HIP_TRY(launch_update_adamw_noise(c->params, c->grads, c->state0, c->state1, cfg.K, cfg.P, c->d_state,
+                                              c->d_scal, (float)(1.0 - cfg.beta1), (float)(1.0 - cfg.beta2),
+                                              (float)cfg.eps, (float)cfg.grad_sigma, cfg.seed, cfg.fuse_gradient == 1,
+                                              c->stream));
+        else if (cfg.opt == QSR_OPT_SGDM)
             HIP_TRY(launch_update_sgdm(c->params, c->grads, c->state0, cfg.K, cfg.P, c->d_state, c->d_scal,
                                        (float)cfg.momentum, (float)cfg.weight_decay, fused, c->d_clip_coef,
                                        c->stream));

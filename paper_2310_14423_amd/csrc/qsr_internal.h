@@ -62,12 +62,20 @@ hipError_t launch_sched_next_round(DevState *st, SchedParams sp, hipStream_t s);
 
 // fused_sync: leave the step that completes a round to launch_update_*_sync.
 // row_coef: K clipping factors the gradient rows are multiplied by as they are read, or nullptr.
-hipError_t launch_update_sgdm(float *theta, const float *g, float *buf, int K, long long P,
+hipError_t launch_update_sgdm(float *theta, float *g, float *buf, int K, long long P,
                               const DevState *st, const StepScalars *sc, float mu, float lambda,
                               bool fused_sync, const float *row_coef, hipStream_t s);
-hipError_t launch_update_adamw(float *theta, const float *g, float *m, float *v, int K, long long P,
+hipError_t launch_update_adamw(float *theta, float *g, float *m, float *v, int K, long long P,
                                const DevState *st, const StepScalars *sc, float c1, float c2,
                                float eps, bool fused_sync, const float *row_coef, hipStream_t s);
+// the same updates with the optimizer-only workloads' gradient g = sigma * N(0,1) drawn inside the
+// kernel (and written to g if store_g); P must be a multiple of 4
+hipError_t launch_update_sgdm_noise(float *theta, float *g, float *buf, int K, long long P, const DevState *st,
+                                    const StepScalars *sc, float mu, float lambda, float sigma, uint64_t seed,
+                                    bool store_g, hipStream_t s);
+hipError_t launch_update_adamw_noise(float *theta, float *g, float *m, float *v, int K, long long P,
+                                     const DevState *st, const StepScalars *sc, float c1, float c2, float eps,
+                                     float sigma, uint64_t seed, bool store_g, hipStream_t s);
 // update + averaging in one pass over the [K][P] buffers, only on the step that completes a round
 hipError_t launch_update_sgdm_sync(float *theta, const float *g, float *buf, int K, long long P,
                                    const DevState *st, const StepScalars *sc, float mu, float lambda,

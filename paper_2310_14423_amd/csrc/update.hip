@@ -8,6 +8,7 @@
 // 5.0-5.1 TB/s for 256-thread blocks in a capped persistent grid and 5.77 TB/s for a plain
 // copy kernel; non-temporal loads and stores were each worth 3-5 %.
 #include "opt_elem.h"
+#include "philox.h"
 #include "qsr_internal.h"
 
 namespace qsr {
@@ -22,21 +23,33 @@ __device__ __forceinline__ void stg_nt(float4 *p, float4 v) { st_nt4(p, v); }
 // *_sync kernels below), so the plain update leaves that step alone.
 // CLIP: the launch has one grid row per worker (blockIdx.y), n4 and n are one worker's row, and
 // the gradient is multiplied by that worker's clipping factor as it is read.
-template <bool CLIP>
+// NOISE (optimizer-only workloads): the gradient is not read but drawn here, g = sigma * N(0,1)
+// from the same Philox counters and with the same arithmetic as fill_normal_kernel.  The separate
+// fill is bound by its arithmetic (about 220 vector instructions per four normals), this kernel by
+// HBM, and the draw hides completely behind the loads of theta, m and v (timed on MI355X at
+// 16 x 60e6: 4.02 ms against 4.63 ms for the update that reads g plus 1.01 ms for the fill).
+// One grid row per worker, like CLIP.  With `store` the draw is also written to the gradient
+// buffer (4 B written in place of the 4 B read: 28 B per element as before, but the write-heavier
+// mix runs at 5.5 TB/s instead of 5.8: 4.91 ms); without, the gradient never exists in HBM and
+// the kernel moves 12 B read + 12 B written = 24 B per element.
+struct NoiseDraw { float sigma; uint64_t seed; int store; };
+
+template <bool CLIP, bool NOISE>
 __global__ __launch_bounds__(UPD_THREADS) void update_adamw_kernel(
-    float4 *__restrict__ theta, const float4 *__restrict__ g, float4 *__restrict__ m,
+    float4 *__restrict__ theta, float4 *__restrict__ g, float4 *__restrict__ m,
     float4 *__restrict__ v, long long n4, long long n, const DevState *__restrict__ st,
     const StepScalars *__restrict__ sc, float c1, float c2, float eps, int fused_sync,
-    const float *__restrict__ row_coef)
+    const float *__restrict__ row_coef, NoiseDraw nd)
 {
     if (fused_sync && st->h + 1 == st->H) return;
     float gs = 1.0f;
-    if (CLIP) {
+    if (CLIP || NOISE) {
         const long long off = (long long)blockIdx.y * n4;      // rows are 16-byte aligned here
         theta += off; g += off; m += off; v += off;
-        gs = row_coef[blockIdx.y];
+        if (CLIP) gs = row_coef[blockIdx.y];
     }
-    const StepScalars s = sc[st->t];
+    const long long t = st->t;
+    const StepScalars s = sc[t];
     const long long stride = (long long)gridDim.x * UPD_THREADS * UPD_UNROLL;
     long long base = (long long)blockIdx.x * UPD_THREADS * UPD_UNROLL + threadIdx.x;
     for (; base < n4; base += stride) {
@@ -44,8 +57,28 @@ __global__ __launch_bounds__(UPD_THREADS) void update_adamw_kernel(
 #pragma unroll
         for (int u = 0; u < UPD_UNROLL; ++u) {
             long long i = base + (long long)u * UPD_THREADS;
-            if (i < n4) { a[u] = ldg_nt(theta + i); b[u] = ldg_nt(g + i); c[u] = ldg_nt(m + i); d[u] = ldg_nt(v + i); }
+            if (i < n4) {
+                a[u] = ldg_nt(theta + i); c[u] = ldg_nt(m + i); d[u] = ldg_nt(v + i);
+                if (!NOISE) b[u] = ldg_nt(g + i);
+            }
             if (CLIP) { b[u].x *= gs; b[u].y *= gs; b[u].z *= gs; b[u].w *= gs; }
+        }
+        if (NOISE) {
+#pragma unroll
+            for (int u = 0; u < UPD_UNROLL; ++u) {
+                long long i = base + (long long)u * UPD_THREADS;
+                if (i < n4) {
+                    b[u] = normal4(nd.seed, STREAM_GRAD, blockIdx.y, (uint32_t)t, (uint32_t)i);
+                    b[u].x *= nd.sigma; b[u].y *= nd.sigma; b[u].z *= nd.sigma; b[u].w *= nd.sigma;
+                }
+            }
+            if (nd.store) {
+#pragma unroll
+                for (int u = 0; u < UPD_UNROLL; ++u) {
+                    long long i = base + (long long)u * UPD_THREADS;
+                    if (i < n4) stg_nt(g + i, b[u]);
+                }
+            }
         }
 #pragma unroll
         for (int u = 0; u < UPD_UNROLL; ++u) {
@@ -60,7 +93,7 @@ __global__ __launch_bounds__(UPD_THREADS) void update_adamw_kernel(
         }
     }
     // ragged tail (n not a multiple of 4): at most 3 elements, done by the first threads
-    if (!CLIP && blockIdx.x == 0 && threadIdx.x < (int)(n - n4 * 4)) {
+    if (!CLIP && !NOISE && blockIdx.x == 0 && threadIdx.x < (int)(n - n4 * 4)) {
         long long i = n4 * 4 + threadIdx.x;
         float *th = (float *)theta, *mm = (float *)m, *vv = (float *)v;
         const float *gg = (const float *)g;
@@ -70,21 +103,22 @@ __global__ __launch_bounds__(UPD_THREADS) void update_adamw_kernel(
     }
 }
 
-template <bool CLIP>
+template <bool CLIP, bool NOISE>
 __global__ __launch_bounds__(UPD_THREADS) void update_sgdm_kernel(
-    float4 *__restrict__ theta, const float4 *__restrict__ g, float4 *__restrict__ buf,
+    float4 *__restrict__ theta, float4 *__restrict__ g, float4 *__restrict__ buf,
     long long n4, long long n, const DevState *__restrict__ st,
     const StepScalars *__restrict__ sc, float mu, float lambda, int fused_sync,
-    const float *__restrict__ row_coef)
+    const float *__restrict__ row_coef, NoiseDraw nd)
 {
     if (fused_sync && st->h + 1 == st->H) return;
     float gs = 1.0f;
-    if (CLIP) {
+    if (CLIP || NOISE) {
         const long long off = (long long)blockIdx.y * n4;
         theta += off; g += off; buf += off;
-        gs = row_coef[blockIdx.y];
+        if (CLIP) gs = row_coef[blockIdx.y];
     }
-    const float eta = sc[st->t].x;
+    const long long t = st->t;
+    const float eta = sc[t].x;
     const long long stride = (long long)gridDim.x * UPD_THREADS * UPD_UNROLL;
     long long base = (long long)blockIdx.x * UPD_THREADS * UPD_UNROLL + threadIdx.x;
     for (; base < n4; base += stride) {
@@ -92,8 +126,28 @@ __global__ __launch_bounds__(UPD_THREADS) void update_sgdm_kernel(
 #pragma unroll
         for (int u = 0; u < UPD_UNROLL; ++u) {
             long long i = base + (long long)u * UPD_THREADS;
-            if (i < n4) { a[u] = ldg_nt(theta + i); b[u] = ldg_nt(g + i); c[u] = ldg_nt(buf + i); }
+            if (i < n4) {
+                a[u] = ldg_nt(theta + i); c[u] = ldg_nt(buf + i);
+                if (!NOISE) b[u] = ldg_nt(g + i);
+            }
             if (CLIP) { b[u].x *= gs; b[u].y *= gs; b[u].z *= gs; b[u].w *= gs; }
+        }
+        if (NOISE) {
+#pragma unroll
+            for (int u = 0; u < UPD_UNROLL; ++u) {
+                long long i = base + (long long)u * UPD_THREADS;
+                if (i < n4) {
+                    b[u] = normal4(nd.seed, STREAM_GRAD, blockIdx.y, (uint32_t)t, (uint32_t)i);
+                    b[u].x *= nd.sigma; b[u].y *= nd.sigma; b[u].z *= nd.sigma; b[u].w *= nd.sigma;
+                }
+            }
+            if (nd.store) {
+#pragma unroll
+                for (int u = 0; u < UPD_UNROLL; ++u) {
+                    long long i = base + (long long)u * UPD_THREADS;
+                    if (i < n4) stg_nt(g + i, b[u]);
+                }
+            }
         }
 #pragma unroll
         for (int u = 0; u < UPD_UNROLL; ++u) {
@@ -107,7 +161,7 @@ __global__ __launch_bounds__(UPD_THREADS) void update_sgdm_kernel(
             }
         }
     }
-    if (!CLIP && blockIdx.x == 0 && threadIdx.x < (int)(n - n4 * 4)) {
+    if (!CLIP && !NOISE && blockIdx.x == 0 && threadIdx.x < (int)(n - n4 * 4)) {
         long long i = n4 * 4 + threadIdx.x;
         float *th = (float *)theta, *bb = (float *)buf;
         const float *gg = (const float *)g;
@@ -316,18 +370,19 @@ hipError_t launch_update_sgdm_sync(float *theta, const float *g, float *buf, int
 }
 
 // row_coef != nullptr: clipped update, one grid row per worker
-hipError_t launch_update_adamw(float *theta, const float *g, float *m, float *v, int K, long long P,
+hipError_t launch_update_adamw(float *theta, float *g, float *m, float *v, int K, long long P,
                                const DevState *st, const StepScalars *sc, float c1, float c2,
                                float eps, bool fused_sync, const float *row_coef, hipStream_t s)
 {
     const int fs = fused_sync ? 1 : 0;
+    const NoiseDraw none{0.f, 0, 0};
     if (row_coef == nullptr) {
         const long long n = (long long)K * P, n4 = n / 4;
-        update_adamw_kernel<false><<<update_grid(n4), UPD_THREADS, 0, s>>>(
-            (float4 *)theta, (const float4 *)g, (float4 *)m, (float4 *)v, n4, n, st, sc, c1, c2, eps, fs, nullptr);
+        update_adamw_kernel<false, false><<<update_grid(n4), UPD_THREADS, 0, s>>>(
+            (float4 *)theta, (float4 *)g, (float4 *)m, (float4 *)v, n4, n, st, sc, c1, c2, eps, fs, nullptr, none);
     } else if ((P & 3) == 0) {
-        update_adamw_kernel<true><<<dim3((unsigned)update_grid(P / 4), (unsigned)K), UPD_THREADS, 0, s>>>(
-            (float4 *)theta, (const float4 *)g, (float4 *)m, (float4 *)v, P / 4, P, st, sc, c1, c2, eps, fs, row_coef);
+        update_adamw_kernel<true, false><<<dim3((unsigned)update_grid(P / 4), (unsigned)K), UPD_THREADS, 0, s>>>(
+            (float4 *)theta, (float4 *)g, (float4 *)m, (float4 *)v, P / 4, P, st, sc, c1, c2, eps, fs, row_coef, none);
     } else {
         update_clip_scalar_kernel<<<dim3((unsigned)sync_grid(P), (unsigned)K), SYNC_THREADS, 0, s>>>(
             theta, g, m, v, P, st, sc, c1, c2, eps, fs, row_coef);
@@ -335,22 +390,46 @@ hipError_t launch_update_adamw(float *theta, const float *g, float *m, float *v,
     return hipGetLastError();
 }
 
-hipError_t launch_update_sgdm(float *theta, const float *g, float *buf, int K, long long P,
+hipError_t launch_update_sgdm(float *theta, float *g, float *buf, int K, long long P,
                               const DevState *st, const StepScalars *sc, float mu, float lambda,
                               bool fused_sync, const float *row_coef, hipStream_t s)
 {
     const int fs = fused_sync ? 1 : 0;
+    const NoiseDraw none{0.f, 0, 0};
     if (row_coef == nullptr) {
         const long long n = (long long)K * P, n4 = n / 4;
-        update_sgdm_kernel<false><<<update_grid(n4), UPD_THREADS, 0, s>>>(
-            (float4 *)theta, (const float4 *)g, (float4 *)buf, n4, n, st, sc, mu, lambda, fs, nullptr);
+        update_sgdm_kernel<false, false><<<update_grid(n4), UPD_THREADS, 0, s>>>(
+            (float4 *)theta, (float4 *)g, (float4 *)buf, n4, n, st, sc, mu, lambda, fs, nullptr, none);
     } else if ((P & 3) == 0) {
-        update_sgdm_kernel<true><<<dim3((unsigned)update_grid(P / 4), (unsigned)K), UPD_THREADS, 0, s>>>(
-            (float4 *)theta, (const float4 *)g, (float4 *)buf, P / 4, P, st, sc, mu, lambda, fs, row_coef);
+        update_sgdm_kernel<true, false><<<dim3((unsigned)update_grid(P / 4), (unsigned)K), UPD_THREADS, 0, s>>>(
+            (float4 *)theta, (float4 *)g, (float4 *)buf, P / 4, P, st, sc, mu, lambda, fs, row_coef, none);
     } else {
         update_clip_scalar_kernel<<<dim3((unsigned)sync_grid(P), (unsigned)K), SYNC_THREADS, 0, s>>>(
             theta, g, buf, nullptr, P, st, sc, mu, lambda, 0.f, fs, row_coef);
     }
+    return hipGetLastError();
+}
+
+// The optimizer-only workloads' gradient g = sigma * N(0,1) drawn inside the update (P a multiple of 4)
+hipError_t launch_update_adamw_noise(float *theta, float *g, float *m, float *v, int K, long long P,
+                                     const DevState *st, const StepScalars *sc, float c1, float c2, float eps,
+                                     float sigma, uint64_t seed, bool store_g, hipStream_t s)
+{
+    if ((P & 3) != 0) return hipErrorInvalidValue;
+    update_adamw_kernel<false, true><<<dim3((unsigned)update_grid(P / 4), (unsigned)K), UPD_THREADS, 0, s>>>(
+        (float4 *)theta, (float4 *)g, (float4 *)m, (float4 *)v, P / 4, P, st, sc, c1, c2, eps, 0, nullptr,
+        NoiseDraw{sigma, seed, store_g ? 1 : 0});
+    return hipGetLastError();
+}
+
+hipError_t launch_update_sgdm_noise(float *theta, float *g, float *buf, int K, long long P, const DevState *st,
+                                    const StepScalars *sc, float mu, float lambda, float sigma, uint64_t seed,
+                                    bool store_g, hipStream_t s)
+{
+    if ((P & 3) != 0) return hipErrorInvalidValue;
+    update_sgdm_kernel<false, true><<<dim3((unsigned)update_grid(P / 4), (unsigned)K), UPD_THREADS, 0, s>>>(
+        (float4 *)theta, (float4 *)g, (float4 *)buf, P / 4, P, st, sc, mu, lambda, 0, nullptr,
+        NoiseDraw{sigma, seed, store_g ? 1 : 0});
     return hipGetLastError();
 }
 

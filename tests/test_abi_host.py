@@ -42,7 +42,7 @@ def test_named_workloads_validate(name):
     ("opt", 2, "opt"), ("model", 5, "model"), ("lr_kind", 5, "lr_kind"), ("H_base", 0, "H_base"),
     ("alpha", -0.1, "alpha"), ("alpha", float("nan"), "alpha"), ("eta_max", 0.0, "eta_max"),
     ("eta_min", 1.0, "eta_min"), ("beta2", 1.0, "beta1/beta2"), ("eps", 0.0, "eps"),
-    ("weight_decay", -1.0, "weight_decay"), ("grad_sigma", -1.0, "grad_sigma"), ("average_state", 2, "average_state"), ("fuse_sync", 2, "fuse_sync"), ("n_heads", 1, "n_heads"), ("clip_norm", -1.0, "clip_norm"),
+    ("weight_decay", -1.0, "weight_decay"), ("grad_sigma", -1.0, "grad_sigma"), ("average_state", 2, "average_state"), ("fuse_sync", 2, "fuse_sync"), ("n_heads", 1, "n_heads"), ("reserved", 1, "reserved"), ("fuse_gradient", 3, "fuse_gradient"), ("clip_norm", -1.0, "clip_norm"),
     ("power", -1, "power"), ("power", 9, "power"), ("parallel", 2, "parallel"),
     ("parallel", 1, "parallel needs H_base = 1, power = 0"), ("t_local_start", -5, "t_local_start"), ("t_swap_start", 9999, "t_swap_start"),
 ])

@@ -90,6 +90,42 @@ def test_noise_gradient_stream_matches_the_oracle():
     ctx.close()
 
 
+@pytest.mark.parametrize("opt,kw", [("adamw", {}), ("sgdm", dict(mu=0.9, lam=5e-4))])
+@pytest.mark.parametrize("K,P", [(3, 40004), (16, 65536 + 4), (1, 8), (5, 4 * (128 * 37 + 1))])
+def test_gradient_drawn_inside_the_update_is_bit_identical(opt, kw, K, P):
+    """fuse_gradient: the optimizer-only workloads' gradient drawn inside the update kernel, written
+    to the gradient buffer (1) or not (2).  Same Philox counters, same arithmetic: parameters and
+    optimizer state (and, for 1, the gradients) equal bit for bit to the two-kernel path over
+    several rounds; the gradient stream matches the oracle's; 2 leaves the buffer untouched."""
+    import torch
+    w = workloads.get("flat60m", K=K, P=P, T=60, H_base=3, alpha=0.0, power=0, opt=opt, eta_max=1e-2, **kw)
+    a = gpu_ctx(w)
+    b = gpu_ctx(dict(w, fuse_gradient=1))
+    c = gpu_ctx(dict(w, fuse_gradient=2))
+    c.grads.fill_(7.0)
+    orc = oracle_run(w)
+    for t in range(14):
+        a.local_step(); b.local_step(); c.local_step()
+        ga, gb = a.grads.cpu().numpy(), b.grads.cpu().numpy()
+        assert np.array_equal(ga, gb), "grads t=%d" % t
+        if t < 2:
+            for k in range(K):
+                assert np.max(np.abs(gb[k] - orc.grad(k, t)[0])) <= 2e-6 * 1e-3
+        a.maybe_sync(); b.maybe_sync(); c.maybe_sync()
+        pa = a.params.cpu().numpy()
+        assert np.array_equal(pa, b.params.cpu().numpy()), "params (1) t=%d" % t
+        assert np.array_equal(pa, c.params.cpu().numpy()), "params (2) t=%d" % t
+    for x in (b, c):
+        assert np.array_equal(a.state0.cpu().numpy(), x.state0.cpu().numpy())
+        if opt == "adamw":
+            assert np.array_equal(a.state1.cpu().numpy(), x.state1.cpu().numpy())
+        assert x.read_sync_log()[0].tolist() == [3, 6, 9, 12]
+    assert bool(torch.all(c.grads == 7.0))
+    orc.step(14)
+    assert_params_close(c.params.cpu().numpy(), orc.theta, what="fused gradient draw")
+    a.close(); b.close(); c.close()
+
+
 @pytest.mark.parametrize("name", ["lsq", "mlp", "flat60m", "resmlp", "flat350m"])
 def test_schedule_is_bit_exact_for_the_full_run(name):
     """The H sequence and averaging points do not depend on P: run every workload's schedule
@@ -108,11 +144,13 @@ def test_schedule_is_bit_exact_for_the_full_run(name):
     ctx.close()
 
 
-def test_flat_adamw_full_schedule_sampled_elements():
+@pytest.mark.parametrize("fuse_gradient", [0, 1, 2])
+def test_flat_adamw_full_schedule_sampled_elements(fuse_gradient):
     """Optimizer-only workload, all 5000 iterations and 8 rounds, P shrunk to 2^20 + 4; the
     oracle follows 2048 sampled parameters (the update is element-wise and the draws are keyed
-    by the global parameter index)."""
-    w = workloads.get("flat60m", P=(1 << 20) + 4)
+    by the global parameter index).  With the gradient filled by its own kernel and drawn inside
+    the update."""
+    w = workloads.get("flat60m", P=(1 << 20) + 4, fuse_gradient=fuse_gradient)
     rng = np.random.default_rng(0)
     idx = np.sort(rng.choice(w["P"], 2048, replace=False)).astype(np.int64)
     idx[0], idx[-1] = 0, w["P"] - 1
@@ -128,11 +166,13 @@ def test_flat_adamw_full_schedule_sampled_elements():
     ctx.close()
 
 
-def test_flat60m_full_size_sampled():
-    """The benchmark's own shape (K = 16, P = 60e6, same launch configuration): the first 310
-    iterations, which include the first averaging at t = 306, on 4096 sampled parameters plus
+@pytest.mark.parametrize("fuse_gradient", [2, 0])
+def test_flat60m_full_size_sampled(fuse_gradient):
+    """The benchmark's own shape (K = 16, P = 60e6, same launch configurations: gradient drawn
+    inside the update and never written, as bench.py's headline run has it, and filled by its own kernel): the first
+    310 iterations, which include the first averaging at t = 306, on 4096 sampled parameters plus
     the two ends of the vector."""
-    w = workloads.get("flat60m")
+    w = workloads.get("flat60m", fuse_gradient=fuse_gradient)
     rng = np.random.default_rng(1)
     idx = np.sort(rng.choice(w["P"], 4096, replace=False)).astype(np.int64)
     idx[0], idx[-1] = 0, w["P"] - 1
@@ -151,12 +191,14 @@ def test_flat60m_full_size_sampled():
     ctx.close()
 
 
-def test_flat350m_full_size_sampled():
+@pytest.mark.parametrize("fuse_gradient", [2, 0])
+def test_flat350m_full_size_sampled(fuse_gradient):
     """The largest workload (K = 32, P = 350e6, 179 GB of state): three iterations and one
-    stand-alone averaging of the full buffer, on sampled parameters."""
+    stand-alone averaging of the full buffer, on sampled parameters; with the gradient drawn
+    inside the update (bench.py's configuration) and filled by its own kernel."""
     import torch
     import paper_2310_14423_amd as qsr
-    w = workloads.get("flat350m")
+    w = workloads.get("flat350m", fuse_gradient=fuse_gradient)
     free, total = torch.cuda.mem_get_info()
     if free < 200e9:
         pytest.skip("needs 200 GB of free HBM, have %.0f GB" % (free / 1e9))
