@@ -504,6 +504,23 @@ def test_vit_block_gradient_single_step(dims):
     ctx.close()
 
 
+def test_vit_block_gradient_full_width():
+    """The paper's width and head count (768, 12 heads) and sequence length (197) on two sequences:
+    the q|k|v projection and its gradients in their real GEMM shapes (N = 2304 is nine 256-wide
+    tiles, the data gradient reduces over 2304), all 12 head offsets of the attention core."""
+    dims = dict(d_in=768, n_heads=12, seq_len=197, B_loc=394, d_hidden=768, n_blocks=1, K=1)
+    w = workloads.get("vit", T=4, T_warm=1, **dims)
+    th0 = _vit_theta0(w, 13, 0.02)
+    ctx = gpu_ctx(w, theta0=th0)
+    orc = oracle_run(w, theta0=th0, n_threads=1)
+    ctx.local_step()
+    g = ctx.grads.cpu().numpy()
+    want, wl = orc.grad(0, 0, th0.astype(np.float64))
+    assert ctx.read_loss()[0] == pytest.approx(wl, rel=1e-2)
+    _assert_groups_close(w, g[0], want, "vit full width", tail=VIT_TAIL, weights_only_tail=True)
+    ctx.close()
+
+
 def test_vit_block_gradient_with_sharp_attention():
     """Scores of standard deviation about 2 (the largest of a row near 6, probabilities spread over
     several orders of magnitude): the maximum subtraction, the masking of the ragged tail and the
