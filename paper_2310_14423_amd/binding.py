@@ -127,36 +127,42 @@ def average_rows(buf, stream=None):
 
 
 def _allocate_state(torch, dev, K, P, second_moment, placement):
-    """The [K][P] arrays params, grads, state0, state1 (torch tensors, zero-initialized grads).
+    """The [K][P] arrays params, grads, state0, state1 (torch tensors; grads zero-initialized).
 
     placement = "spread": MI355X's 288 GiB are three physical ranges of 96 GiB (the three ranks of its
     12-high HBM3E stacks).  The update streams through params, state0 and state1 in lockstep, and
     while all of them lie in one such range they compete for its banks: timed at K*P = 0.96e9, the
     same kernel runs at 5.6-5.9 TB/s with the arrays adjacent and at 6.4-6.5 TB/s with at least one of
-    them in another range (single-array kernels do not care).  A fresh process gets physical memory
-    in allocation order, so two temporary fillers push state0 and state1 one range further each;
-    they are freed again at once.  Only done where it can matter and can work: arrays of at least
-    512 MiB that would all fit one range, and enough free memory for the fillers.
+    them in another range (single-array kernels do not care).  Physical addresses cannot be asked
+    for, but equal-sized allocations made in a row are handed out in physical order, cyclically from
+    wherever the driver's free list happens to start: so nearly all free memory is taken in chunks
+    of one array's size, the arrays are the chunks at 0, 1/3 and 2/3 of that sequence (which cannot
+    all share a range, whatever the starting point), and the other chunks are given back at once.
+    (Large fillers between the arrays are not placed in order and did not work reliably.)  Only done
+    where it matters: arrays of at least 512 MiB that would all fit one range, most memory free.
     """
     f32 = dict(dtype=torch.float32, device=dev)
     n = K * P * 4
-    fillers = []
-    spread = False
+    m = 0
     if placement == "spread":
         free, total = torch.cuda.mem_get_info(dev)
-        region = total // 3
-        spread = n >= (512 << 20) and 4 * n <= region and free >= 2 * region + 4 * n + (8 << 30)
-    params = torch.empty((K, P), **f32)
-    grads = torch.zeros((K, P), **f32)
-    if spread:
-        fillers.append(torch.empty(region - 2 * n, dtype=torch.uint8, device=dev))
-    state0 = torch.empty((K, P), **f32)
-    if spread:
-        fillers.append(torch.empty(region - n, dtype=torch.uint8, device=dev))
-    state1 = torch.empty((K, P), **f32) if second_moment else None
-    if fillers:
-        del fillers
-        torch.cuda.empty_cache()
+        if n >= (512 << 20) and 4 * n <= total // 3:
+            m = int((free - (8 << 30)) // (n + (2 << 20)))
+    if m < 12:
+        params = torch.empty((K, P), **f32)
+        grads = torch.zeros((K, P), **f32)
+        state0 = torch.empty((K, P), **f32)
+        state1 = torch.empty((K, P), **f32) if second_moment else None
+        return params, grads, state0, state1
+    chunks = [torch.empty((K, P), **f32) for _ in range(m)]
+    params, grads = chunks[0], chunks[1]
+    if second_moment:
+        state0, state1 = chunks[m // 3], chunks[(2 * m) // 3]
+    else:
+        state0, state1 = chunks[m // 2], None
+    grads.zero_()
+    del chunks
+    torch.cuda.empty_cache()
     return params, grads, state0, state1
 
 
