@@ -830,6 +830,31 @@ def test_gradient_clipping(opt, K, P, extra):
     ctx.close()
 
 
+def test_array_placement_does_not_change_results():
+    """The binding spreads large [K][P] arrays over the physical ranges of the HBM (a matter of speed
+    only): a run on arrays placed that way equals, bit for bit, the run on plainly allocated ones,
+    the four arrays are distinct allocations, and small problems are left alone."""
+    import torch
+    import paper_2310_14423_amd as qsr
+    w = workloads.get("flat60m", K=4, P=40_000_000, T=40, H_base=3, alpha=0.0, power=0)   # 640 MB per array
+    free, _ = torch.cuda.mem_get_info()
+    if free < 250e9:
+        pytest.skip("placement needs most of the memory free, have %.0f GB" % (free / 1e9))
+    outs = []
+    for placement in ("spread", "plain"):
+        ctx = qsr.Context(w, theta0=workloads.theta0(w), placement=placement)
+        ptrs = {t.data_ptr() for t in (ctx.params, ctx.grads, ctx.state0, ctx.state1)}
+        assert len(ptrs) == 4
+        ctx.step(7)
+        outs.append([t.cpu().numpy() for t in (ctx.params, ctx.grads, ctx.state0, ctx.state1)])
+        assert list(ctx.read_sync_log()[0]) == [3, 6]
+        ctx.close(); del ctx
+        torch.cuda.empty_cache()
+    for a, b in zip(*outs):
+        assert np.array_equal(a, b)
+    assert torch.cuda.mem_get_info()[0] > free - 4e9        # the probe chunks were given back
+
+
 def test_checkpoint_and_resume():
     """Stop after 700 of 2000 iterations (inside a round), restore buffers and scheduler state in a
     fresh context, finish: bit-identical to the uninterrupted run, and the log continues."""
