@@ -1,8 +1,9 @@
-// sgemm.h -- batched single-precision GEMM on the vector ALUs, LDS-tiled, for the small fp32
-// model workload (two-layer perceptron).  C[b] = op(A[b]) * op(B[b]) with optional epilogue;
-// one launch covers all K workers (blockIdx.z).  64x64 output tile, 16-deep k-slabs, 256
-// threads, 4x4 outputs per thread, global loads three slabs ahead in registers.  Every global
-// access is bounds-checked, so any M, N, Kd is accepted.  fp32 accumulation in a fixed order: deterministic.
+// sgemm.h -- batched single-precision GEMM, LDS-tiled, for the small fp32 model workload
+// (two-layer perceptron).  C[b] = op(A[b]) * op(B[b]) with optional epilogue; one launch covers
+// all K workers (blockIdx.z).  64x64 output tile, 16-deep k-slabs, 256 threads: four wavefronts,
+// each a 32x32 block on the fp32 matrix cores (v_mfma_f32_32x32x2_f32: fp32 operands, fp32
+// accumulation, two k per instruction), global loads three slabs ahead in registers.  Every
+// global access is bounds-checked, so any M, N, Kd is accepted.  Fixed order: deterministic.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -24,39 +25,44 @@ struct GemmArgs {
 template <bool TA, bool TB, int EPI>
 __global__ __launch_bounds__(256) void sgemm_kernel(GemmArgs a)
 {
-    constexpr int TM = 64, TN = 64, TK = 16, PAD = 4;
+    constexpr int TM = 64, TN = 64, TK = 16, PAD = 32;   // rows k and k+1 of a slab 32 banks apart
     __shared__ float As[TK][TM + PAD];
     __shared__ float Bs[TK][TN + PAD];
     const int tid = threadIdx.x;
-    const int tx = tid & 15, ty = tid >> 4;
+    const int lane = tid & 63, wm = tid >> 7, wn = (tid >> 6) & 1;   // wavefront (wm, wn) owns a 32x32 block
     const int m0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
     const long long bz = blockIdx.z;
     const float *A = a.A + bz * a.sA;
     const float *B = a.B + bz * a.sB;
-    float acc[4][4] = {};
+    typedef float f32x16_t __attribute__((ext_vector_type(16)));
+    f32x16_t acc;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0.f;
 
     // Global loads run PF slabs ahead of the multiplication, in registers: these problems have few
     // workgroups per compute unit (the batch is 128 rows), so a slab's load latency is not hidden
     // by other wavefronts and, unprefetched, every one of the Kd/16 steps paid it in full
-    // (timed on MI355X, 128 x 784 x 1024, 8 workers: 178 us per launch without, 98 us with).
-    // The order of the additions into acc is unchanged.
+    // (timed on MI355X, 128 x 784 x 1024, 8 workers, with the products still on the vector ALUs:
+    // 178 us per launch without, 98 us with; 46 us with the products on the matrix cores.  Six
+    // slabs ahead or 32-deep slabs timed the same to slower).
     constexpr int PF = 3;
-    float ra[PF][4], rb[PF][4];
-    auto gload = [&](int k0, float (&xa)[4], float (&xb)[4]) {
+    constexpr int R = TK / 4;                       // elements of each operand per thread and slab
+    float ra[PF][R], rb[PF][R];
+    auto gload = [&](int k0, float (&xa)[R], float (&xb)[R]) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
+        for (int r = 0; r < R; ++r) {
             int kk, m;
             if (TA) { m = tid & 63; kk = (tid >> 6) + 4 * r; }
-            else    { kk = tid & 15; m = (tid >> 4) + 16 * r; }
+            else    { kk = tid % TK; m = tid / TK + (256 / TK) * r; }
             int gm = m0 + m, gk = k0 + kk;
             float v = 0.f;
             if (gm < a.M && gk < a.Kd) v = TA ? A[(long long)gk * a.lda + gm] : A[(long long)gm * a.lda + gk];
             xa[r] = v;
         }
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
+        for (int r = 0; r < R; ++r) {
             int kk, n;
-            if (TB) { kk = tid & 15; n = (tid >> 4) + 16 * r; }
+            if (TB) { kk = tid % TK; n = tid / TK + (256 / TK) * r; }
             else    { n = tid & 63; kk = (tid >> 6) + 4 * r; }
             int gn = n0 + n, gk = k0 + kk;
             float v = 0.f;
@@ -64,12 +70,12 @@ __global__ __launch_bounds__(256) void sgemm_kernel(GemmArgs a)
             xb[r] = v;
         }
     };
-    auto sstore = [&](const float (&xa)[4], const float (&xb)[4]) {
+    auto sstore = [&](const float (&xa)[R], const float (&xb)[R]) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
+        for (int r = 0; r < R; ++r) {
             if (TA) As[(tid >> 6) + 4 * r][tid & 63] = xa[r];
-            else    As[tid & 15][(tid >> 4) + 16 * r] = xa[r];
-            if (TB) Bs[tid & 15][(tid >> 4) + 16 * r] = xb[r];
+            else    As[tid % TK][tid / TK + (256 / TK) * r] = xa[r];
+            if (TB) Bs[tid % TK][tid / TK + (256 / TK) * r] = xb[r];
             else    Bs[(tid >> 6) + 4 * r][tid & 63] = xb[r];
         }
     };
@@ -85,37 +91,30 @@ __global__ __launch_bounds__(256) void sgemm_kernel(GemmArgs a)
                 sstore(ra[u], rb[u]);
                 if (sl + PF < nslab) gload((sl + PF) * TK, ra[u], rb[u]);
                 __syncthreads();
+                // lane l supplies A[row l%32][k l/32] and B[k l/32][column l%32] of the instruction
 #pragma unroll
-                for (int kk = 0; kk < TK; ++kk) {
-                    float4 av = *(const float4 *)&As[kk][ty * 4];
-                    float4 bv = *(const float4 *)&Bs[kk][tx * 4];
-                    float ar[4] = {av.x, av.y, av.z, av.w};
-                    float br[4] = {bv.x, bv.y, bv.z, bv.w};
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(ar[i], br[j], acc[i][j]);
+                for (int kk = 0; kk < TK; kk += 2) {
+                    const float av = As[kk + (lane >> 5)][wm * 32 + (lane & 31)];
+                    const float bv = Bs[kk + (lane >> 5)][wn * 32 + (lane & 31)];
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc, 0, 0, 0);
                 }
                 __syncthreads();
             }
         }
     }
 
+    // accumulator element i of lane l is C[(i/4)*8 + (l/32)*4 + i%4][l%32] of the wavefront's block
     float *C = a.C + bz * a.sC;
+    const int gn = n0 + wn * 32 + (lane & 31);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        int gm = m0 + ty * 4 + i;
-        if (gm >= a.M) continue;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            int gn = n0 + tx * 4 + j;
-            if (gn >= a.N) continue;
-            float v = acc[i][j];
-            if (EPI == EPI_BIAS_RELU || EPI == EPI_BIAS) v += a.bias[bz * a.sBias + gn];
-            if (EPI == EPI_BIAS_RELU) v = v > 0.f ? v : 0.f;
-            if (EPI == EPI_MASK_POS) v = a.aux[bz * a.sC + (long long)gm * a.ldc + gn] > 0.f ? v : 0.f;
-            C[(long long)gm * a.ldc + gn] = v;
-        }
+    for (int i = 0; i < 16; ++i) {
+        const int gm = m0 + wm * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
+        if (gm >= a.M || gn >= a.N) continue;
+        float v = acc[i];
+        if (EPI == EPI_BIAS_RELU || EPI == EPI_BIAS) v += a.bias[bz * a.sBias + gn];
+        if (EPI == EPI_BIAS_RELU) v = v > 0.f ? v : 0.f;
+        if (EPI == EPI_MASK_POS) v = a.aux[bz * a.sC + (long long)gm * a.ldc + gn] > 0.f ? v : 0.f;
+        C[(long long)gm * a.ldc + gn] = v;
     }
 }
 

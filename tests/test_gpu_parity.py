@@ -837,6 +837,7 @@ def test_array_placement_does_not_change_results():
     import torch
     import paper_2310_14423_amd as qsr
     w = workloads.get("flat60m", K=4, P=40_000_000, T=40, H_base=3, alpha=0.0, power=0)   # 640 MB per array
+    torch.cuda.empty_cache()
     free, _ = torch.cuda.mem_get_info()
     if free < 250e9:
         pytest.skip("placement needs most of the memory free, have %.0f GB" % (free / 1e9))
