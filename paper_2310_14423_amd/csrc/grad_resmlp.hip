@@ -31,7 +31,7 @@ static inline size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 constexpr float LN_EPS = 1e-5f;
 constexpr int WGRAD_SPLIT = 4;          // most ranges a weight gradient's token reduction is cut into
-constexpr int LN_ROWS_PER_WAVE = 16;
+constexpr int LN_ROWS_PER_WAVE = 16;     // least token rows per wavefront of the LayerNorm backward pass
 
 struct ResWs {
     // per-replica strides are the element counts of one replica's array
@@ -234,7 +234,7 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const float *__restrict__ X
     if (lane == 0) { MU[(long long)z * sStat + row] = mean; RSTD[(long long)z * sStat + row] = rstd; }
 }
 
-// Backward of LayerNorm plus the residual path, one wavefront per LN_ROWS_PER_WAVE token rows,
+// Backward of LayerNorm plus the residual path, one wavefront per rows_per_wave token rows,
 // VPL float4 per lane:
 //   dn = du*gamma; dx_out = dx_in + rstd*(dn - mean(dn) - xhat*mean(dn*xhat))
 // and per-wavefront partial sums of dgamma = sum_m du*xhat, dbeta = sum_m du (reduced by
@@ -249,7 +249,7 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const float *__restrict__ D
                                                      float *__restrict__ DXout, long long sDX,
                                                      bf16_t *__restrict__ DXb, long long sDXb,
                                                      float *__restrict__ PART, long long sPART,
-                                                     int wave_rows, int M, int d)
+                                                     int wave_rows, int rows_per_wave, int M, int d)
 {
     const int z = blockIdx.y;
     const int wr = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -264,8 +264,8 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const float *__restrict__ D
 #pragma unroll
         for (int e = 0; e < 4; ++e) { dg[c][e] = 0.f; db[c][e] = 0.f; }
     }
-    const int r_end = min(M, (wr + 1) * LN_ROWS_PER_WAVE);
-    for (int row = wr * LN_ROWS_PER_WAVE; row < r_end; ++row) {
+    const int r_end = min(M, (wr + 1) * rows_per_wave);
+    for (int row = wr * rows_per_wave; row < r_end; ++row) {
         const long long o = (long long)row * d;
         const float mean = MU[(long long)z * sStat + row], rstd = RSTD[(long long)z * sStat + row];
         float xh[VPL][4], dn[VPL][4];
@@ -604,7 +604,14 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
     if (heads > 0 && !attn_supports(d, heads, S, M)) return hipErrorInvalidValue;
     ResWs w = carve(dm, ws, nullptr);
     const long long Md = (long long)M * d, Mdh = (long long)M * dh;
-    const int wave_rows = (M + LN_ROWS_PER_WAVE - 1) / LN_ROWS_PER_WAVE;
+    // Rows per wavefront of the LayerNorm backward pass: enough that all wavefronts of the launch
+    // are resident at once (a launch of 1.5 times the chip's wavefront slots runs as one full wave of
+    // workgroups and a half-empty one).  Resident wavefronts per CU follow from the kernel's registers.
+    const int vpl_ln = (d + 255) / 256;
+    const int ln_slots = gemm_pp_cu_count() * (vpl_ln <= 1 ? 28 : vpl_ln == 2 ? 20 : vpl_ln == 3 ? 16 : 12);
+    int rows_per_wave = (int)(((long long)K * M + ln_slots - 1) / ln_slots);
+    if (rows_per_wave < LN_ROWS_PER_WAVE) rows_per_wave = LN_ROWS_PER_WAVE;
+    const int wave_rows = (M + rows_per_wave - 1) / rows_per_wave;
 
     AttnArgs att{};
     if (heads > 0) {
@@ -633,7 +640,7 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
         const float *DXc = w.DX + (long long)cur * Md;
         float *DXn = w.DX + (long long)(cur ^ 1) * Md;
 #define LN_BWD(VPL) ln_bwd_kernel<VPL><<<grid, 256, 0, s>>>(w.DU, w.sDU, w.X + (long long)sub * Md, w.sX, w.MU + (long long)sub * M, \
-                        w.RSTD + (long long)sub * M, w.sStat, theta, P, off_gamma, DXc, DXn, w.sDX, w.DXb, w.sDXb, w.PART, w.sPART, wave_rows, M, d)
+                        w.RSTD + (long long)sub * M, w.sStat, theta, P, off_gamma, DXc, DXn, w.sDX, w.DXb, w.sDXb, w.PART, w.sPART, wave_rows, rows_per_wave, M, d)
         const int vpl = (d + 255) / 256;
         if (vpl <= 1) LN_BWD(1); else if (vpl <= 2) LN_BWD(2); else if (vpl <= 3) LN_BWD(3); else LN_BWD(4);
 #undef LN_BWD
