@@ -132,23 +132,26 @@ size_t resmlp_workspace_bytes(const ModelDims &d)
 // ---------------------------------------------------------------------------------------------
 
 // in [R][C] (row stride ld_in) -> out [R][C] bf16 (optional) and outT [C][R] bf16 (row stride
-// ld_t), 64x64 tiles through LDS; batch index z with element strides.
+// ld_t), 64x64 tiles through LDS.  Batch index blockIdx.z = z * n_inner + l: z with the element
+// strides s_in, s_out, s_t (workers), l with the strides l_in, l_out (the blocks of the model, whose
+// matrices are R*C apart in both outputs), so that one launch converts a weight of all blocks.
 template <class TIn>
 __global__ __launch_bounds__(256) void cvt_transpose_kernel(const TIn *__restrict__ in, long long ld_in,
-                                                            long long s_in, bf16_t *__restrict__ out,
+                                                            long long s_in, long long l_in, bf16_t *__restrict__ out,
                                                             long long s_out, bf16_t *__restrict__ outT,
-                                                            long long ld_t, long long s_t, int R, int C)
+                                                            long long ld_t, long long s_t, int R, int C, int n_inner)
 {
     __shared__ bf16_t tile[64][66];
-    const int z = blockIdx.z;
+    const int z = blockIdx.z / n_inner, l = blockIdx.z - z * n_inner;
     const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    in += (long long)z * s_in;
+    const long long l_out = (long long)l * R * C;
+    in += (long long)z * s_in + (long long)l * l_in;
     for (int r = ty; r < 64; r += 4) {
         bf16_t v = (bf16_t)0.0f;
         if (r0 + r < R && c0 + tx < C) {
             v = (bf16_t)in[(long long)(r0 + r) * ld_in + c0 + tx];
-            if (out) out[(long long)z * s_out + (long long)(r0 + r) * C + c0 + tx] = v;
+            if (out) out[(long long)z * s_out + l_out + (long long)(r0 + r) * C + c0 + tx] = v;
         }
         tile[r][tx] = v;
     }
@@ -156,17 +159,18 @@ __global__ __launch_bounds__(256) void cvt_transpose_kernel(const TIn *__restric
     if (outT) {
         for (int c = ty; c < 64; c += 4)
             if (c0 + c < C && r0 + tx < R)
-                outT[(long long)z * s_t + (long long)(c0 + c) * ld_t + r0 + tx] = tile[tx][c];
+                outT[(long long)z * s_t + l_out + (long long)(c0 + c) * ld_t + r0 + tx] = tile[tx][c];
     }
 }
 
 template <class TIn>
-static hipError_t launch_cvt_transpose(const TIn *in, long long ld_in, long long s_in, bf16_t *out,
+static hipError_t launch_cvt_transpose(const TIn *in, long long ld_in, long long s_in, long long l_in, bf16_t *out,
                                        long long s_out, bf16_t *outT, long long ld_t, long long s_t,
-                                       int R, int C, int batch, hipStream_t s)
+                                       int R, int C, int batch, int n_inner, hipStream_t s)
 {
-    dim3 grid((unsigned)((C + 63) / 64), (unsigned)((R + 63) / 64), (unsigned)batch);
-    cvt_transpose_kernel<TIn><<<grid, 256, 0, s>>>(in, ld_in, s_in, out, s_out, outT, ld_t, s_t, R, C);
+    if ((long long)batch * n_inner > 65535) return hipErrorInvalidValue;
+    dim3 grid((unsigned)((C + 63) / 64), (unsigned)((R + 63) / 64), (unsigned)(batch * n_inner));
+    cvt_transpose_kernel<TIn><<<grid, 256, 0, s>>>(in, ld_in, s_in, l_in, out, s_out, outT, ld_t, s_t, R, C, n_inner);
     return hipGetLastError();
 }
 
@@ -652,19 +656,19 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
     };
 
     TRY(launch_fill_zero((float *)w.ZERO, 64, s));
-    // bf16 copies of the weights in both orientations (the master weights changed last step)
-    for (int l = 0; l < L; ++l) {
-        const long long oW1 = l * per_block + per_attn + 2LL * d, oW2 = oW1 + (long long)d * dh + dh;
-        const long long ow = (long long)l * d * dh;
-        TRY(launch_cvt_transpose<float>(theta + oW1, dh, P, w.W1b + ow, w.sW, w.W1Tb + ow, d, w.sW, d, dh, K, s));
-        TRY(launch_cvt_transpose<float>(theta + oW2, d, P, w.W2b + ow, w.sW, w.W2Tb + ow, dh, w.sW, dh, d, K, s));
+    // bf16 copies of the weights in both orientations (the master weights changed last step): one
+    // launch per kind of weight, over all blocks and workers
+    {
+        const long long oW1 = per_attn + 2LL * d, oW2 = oW1 + (long long)d * dh + dh;
+        TRY(launch_cvt_transpose<float>(theta + oW1, dh, P, per_block, w.W1b, w.sW, w.W1Tb, d, w.sW, d, dh, K, L, s));
+        TRY(launch_cvt_transpose<float>(theta + oW2, d, P, per_block, w.W2b, w.sW, w.W2Tb, dh, w.sW, dh, d, K, L, s));
         if (heads > 0) {
-            const long long oWq = l * per_block + 2LL * d, oWo = oWq + 3 * dd + 3LL * d;
-            TRY(launch_cvt_transpose<float>(theta + oWq, 3LL * d, P, w.Wqb + l * 3 * dd, w.sWq, w.WqTb + l * 3 * dd, d, w.sWq, d, 3 * d, K, s));
-            TRY(launch_cvt_transpose<float>(theta + oWo, d, P, w.Wob + l * dd, w.sWo, w.WoTb + l * dd, d, w.sWo, d, d, K, s));
+            const long long oWq = 2LL * d, oWo = oWq + 3 * dd + 3LL * d;
+            TRY(launch_cvt_transpose<float>(theta + oWq, 3LL * d, P, per_block, w.Wqb, w.sWq, w.WqTb, d, w.sWq, d, 3 * d, K, L, s));
+            TRY(launch_cvt_transpose<float>(theta + oWo, d, P, per_block, w.Wob, w.sWo, w.WoTb, d, w.sWo, d, d, K, L, s));
         }
     }
-    TRY(launch_cvt_transpose<float>(teacher, d, 0, nullptr, 0, w.WTt, d, 0, d, d, 1, s));
+    TRY(launch_cvt_transpose<float>(teacher, d, 0, 0, nullptr, 0, w.WTt, d, 0, d, d, 1, 1, s));
 
     // Sample(): tokens x_0 (fp32 in X[0], bf16 in U), teacher targets y = x_0 W_T / sqrt(d)
     TRY(launch_fill_normal(w.X, w.sX, K, Md, 1.0f, STREAM_X, dm.seed, st, s));
