@@ -21,8 +21,8 @@ constexpr int AVG_KU = 16;
 // 8-20 % above 256-thread blocks in a capped grid and above the chunked variant below.
 // THREADS: 64 for the stand-alone entry point (fastest); the predicated in-run launch, which is
 // skipped on the device in all but a handful of iterations, uses 256 so that a skipped launch
-// has four times fewer workgroups to retire (0.013 ms instead of 0.05 ms at P = 60e6) at the
-// price of 3 % on the launches that do average.
+// has fewer workgroups to retire (0.013 ms instead of 0.05 ms at P = 60e6 with one trip each;
+// the launcher caps the grid further) at the price of a few per cent on the launches that do average.
 template <int KMAX, int THREADS>
 __global__ __launch_bounds__(THREADS) void average_rows_full_kernel(
     float *__restrict__ buf, int K, long long P4, const DevState *__restrict__ st)
@@ -110,7 +110,11 @@ hipError_t launch_average_rows(float *buf, int K, long long P, const DevState *s
     if ((P & 3) == 0) {
         const long long P4 = P / 4;
         const int grid = avg_grid(P4, AVG_THREADS);
-        const int grid256 = avg_grid(P4, 256);
+        // predicated in-run launches: a capped grid walked with a stride loop.  In a QSR run nearly
+        // all of them are skipped on the device, and retiring 4096 workgroups costs 0.006 ms where
+        // the 58 594 one-trip ones of P = 60e6 cost 0.016 ms; the few launches that do average run
+        // 5 % slower for it
+        const int grid256 = avg_grid(P4, 256) < 4096 ? avg_grid(P4, 256) : 4096;
         if (K <= 8) {
             if (st) average_rows_full_kernel<8, 256><<<grid256, 256, 0, s>>>(buf, K, P4, st);
             else average_rows_full_kernel<8, AVG_THREADS><<<grid, AVG_THREADS, 0, s>>>(buf, K, P4, st);
