@@ -42,7 +42,7 @@ struct ResWs {
     bf16_t *U;     long long sU;       // [sub][M][d] LayerNorm output
     bf16_t *A;     long long sA;       // [L][M][dh]  GELU output
     float *Y;      long long sY;       // [M][d]
-    float *DX;     long long sDX;      // [2][M][d]
+    float *DX;     long long sDX;      // [M][d]
     bf16_t *DXb;   long long sDXb;     // [M][d]
     bf16_t *DH;    long long sDH;      // [M][dh]
     float *DU;     long long sDU;      // [M][d]
@@ -86,7 +86,7 @@ static ResWs carve(const ModelDims &dm, void *ws, size_t *total)
     w.sU = padded(sub * M * d, 2);       w.U = (bf16_t *)take(w.sU, 2, K);
     w.sA = padded(L * M * dh, 2);        w.A = (bf16_t *)take(w.sA, 2, K);
     w.sY = padded(M * d, 4);             w.Y = (float *)take(w.sY, 4, K);
-    w.sDX = padded(2 * M * d, 4);        w.DX = (float *)take(w.sDX, 4, K);
+    w.sDX = padded(M * d, 4);            w.DX = (float *)take(w.sDX, 4, K);
     w.sDXb = padded(M * d, 2);           w.DXb = (bf16_t *)take(w.sDXb, 2, K);
     w.sDH = padded(M * dh, 2);           w.DH = (bf16_t *)take(w.sDH, 2, K);
     w.sDU = padded(M * d, 4);            w.DU = (float *)take(w.sDU, 4, K);
@@ -241,6 +241,8 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const float *__restrict__ X
 // Backward of LayerNorm plus the residual path, one wavefront per rows_per_wave token rows,
 // VPL float4 per lane:
 //   dn = du*gamma; dx_out = dx_in + rstd*(dn - mean(dn) - xhat*mean(dn*xhat))
+// dx_out may be dx_in (each element is read and then written by the same lane): the launcher does
+// that, so the update of dx is one stream of addresses instead of two.
 // and per-wavefront partial sums of dgamma = sum_m du*xhat, dbeta = sum_m du (reduced by
 // colsum_final_kernel).
 template <int VPL>
@@ -249,8 +251,8 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const float *__restrict__ D
                                                      const float *__restrict__ MU,
                                                      const float *__restrict__ RSTD, long long sStat,
                                                      const float *__restrict__ theta, long long sTh,
-                                                     long long off_gamma, const float *__restrict__ DXin,
-                                                     float *__restrict__ DXout, long long sDX,
+                                                     long long off_gamma, const float *DXin,
+                                                     float *DXout, long long sDX,
                                                      bf16_t *__restrict__ DXb, long long sDXb,
                                                      float *__restrict__ PART, long long sPART,
                                                      int wave_rows, int rows_per_wave, int M, int d)
@@ -636,22 +638,18 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
 #undef LN_FWD
         return hipGetLastError();
     };
-    // its backward pass plus the residual path: DX[cur] (d loss / d state sub+1) and DU -> DX[cur^1]
+    // its backward pass plus the residual path: DX (d loss / d state sub+1) and DU -> DX in place
     // (d loss / d state sub, also in bf16), and the LayerNorm parameter gradients
-    int cur = 0;
     auto ln_bwd = [&](int sub, long long off_gamma) -> hipError_t {
         dim3 grid((unsigned)((wave_rows + 3) / 4), (unsigned)K);
-        const float *DXc = w.DX + (long long)cur * Md;
-        float *DXn = w.DX + (long long)(cur ^ 1) * Md;
 #define LN_BWD(VPL) ln_bwd_kernel<VPL><<<grid, 256, 0, s>>>(w.DU, w.sDU, w.X + (long long)sub * Md, w.sX, w.MU + (long long)sub * M, \
-                        w.RSTD + (long long)sub * M, w.sStat, theta, P, off_gamma, DXc, DXn, w.sDX, w.DXb, w.sDXb, w.PART, w.sPART, wave_rows, rows_per_wave, M, d)
+                        w.RSTD + (long long)sub * M, w.sStat, theta, P, off_gamma, w.DX, w.DX, w.sDX, w.DXb, w.sDXb, w.PART, w.sPART, wave_rows, rows_per_wave, M, d)
         const int vpl = (d + 255) / 256;
         if (vpl <= 1) LN_BWD(1); else if (vpl <= 2) LN_BWD(2); else if (vpl <= 3) LN_BWD(3); else LN_BWD(4);
 #undef LN_BWD
         TRY(hipGetLastError());
         colsum_final_kernel<<<dim3((unsigned)((d + 63) / 64), (unsigned)K, 2), 256, 0, s>>>(
             w.PART, w.sPART, g + off_gamma, P, wave_rows, d);
-        cur ^= 1;
         return hipGetLastError();
     };
 
@@ -734,7 +732,7 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
         TRY(hipGetLastError());
     }
 
-    // backward; DX[cur] (and its bf16 copy DXb) holds d loss / d (output of the sub-block at hand)
+    // backward; DX (and its bf16 copy DXb) holds d loss / d (output of the sub-block at hand)
     for (int l = L - 1; l >= 0; --l) {
         int sub = nsub * l + nsub - 1;
         const long long og = l * per_block + per_attn, oW1 = og + 2LL * d, ob1 = oW1 + (long long)d * dh,
