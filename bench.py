@@ -99,11 +99,20 @@ def run_workload(name, steps, warmup, kernel_timing=True, fuse_gradient=True):
     cnt = [0] * 4
     rounds = 0
 
+    best = [None] * 4                       # shortest bracket of each kind over the timed region
+    median = [None] * 4                     # median of each kind, from the read with the most brackets
+    median_n = [0] * 4
+
     def collect():
         nonlocal ms, cnt, rounds
         if kernel_timing:
-            m, c = ctx.read_timing()
+            m, c, lo, med = ctx.read_timing_stats()
             ms = [a + b for a, b in zip(ms, m)]; cnt = [a + b for a, b in zip(cnt, c)]
+            for i in range(4):
+                if c[i] > 0:
+                    best[i] = lo[i] if best[i] is None else min(best[i], lo[i])
+                    if c[i] > median_n[i]:
+                        median[i], median_n[i] = med[i], c[i]
         rounds += ctx.get_H()[1]
 
     torch.cuda.synchronize()
@@ -156,6 +165,7 @@ def run_workload(name, steps, warmup, kernel_timing=True, fuse_gradient=True):
         roofline = {"kernel": "gradient stage: gemm_nt_bf16_kernel / gemm_pp_tn_kernel%s + helpers" % (" / attn_*_kernel" if w.get("n_heads", 0) else ""),
                     "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "avg_ms": g_ms,
+                    "median_ms": median[0], "min_ms": best[0],
                     "launches": cnt[0], "flops_per_launch": flops}
     elif cnt[1] > 0:
         ach = kernels["update_GBs"]
@@ -163,8 +173,8 @@ def run_workload(name, steps, warmup, kernel_timing=True, fuse_gradient=True):
                     "bound": "hbm", "achieved": ach,
                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
                     "traffic": measured_traffic(name, bool(w.get("fuse_gradient"))),
-                    "avg_ms": kernels["update_ms_avg"], "launches": cnt[1],
-                    "bytes_per_launch": upd_bytes}
+                    "avg_ms": kernels["update_ms_avg"], "median_ms": median[1], "min_ms": best[1],
+                    "launches": cnt[1], "bytes_per_launch": upd_bytes}
 
     # the averaging kernel runs only a handful of times per run: time it in a loop of its own
     reps = 20

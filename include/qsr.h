@@ -195,6 +195,9 @@ int qsr_restart(qsr_ctx *ctx);
  * and 3 uses the log of the current run. */
 int qsr_timing(qsr_ctx *ctx, int enable);
 int qsr_read_timing(qsr_ctx *ctx, double ms[4], int64_t count[4]);
+/* The same read with the shortest and the median bracket of each kind as well (0 where count is 0);
+ * ms_min and ms_median may be NULL. */
+int qsr_read_timing_stats(qsr_ctx *ctx, double ms[4], int64_t count[4], double ms_min[4], double ms_median[4]);
 
 int qsr_destroy(qsr_ctx *ctx);
 

@@ -11,7 +11,7 @@ _lib = None
 
 EXPORTS = ["qsr_validate", "qsr_workspace_bytes", "qsr_init", "qsr_local_step", "qsr_maybe_sync",
            "qsr_get_H", "qsr_get_state", "qsr_set_state", "qsr_read_sync_log", "qsr_eta_table", "qsr_read_loss", "qsr_restart",
-           "qsr_timing", "qsr_read_timing", "qsr_destroy", "qsr_average_rows", "qsr_strerror",
+           "qsr_timing", "qsr_read_timing", "qsr_read_timing_stats", "qsr_destroy", "qsr_average_rows", "qsr_strerror",
            "qsr_last_hip_error"]
 
 OPTS = {"sgdm": 0, "adamw": 1}
@@ -280,6 +280,12 @@ class Context:
         ms = (C.c_double * 4)(); cnt = (C.c_int64 * 4)()
         _check(lib().qsr_read_timing(self._ctx, ms, cnt), "qsr_read_timing")
         return list(ms), list(cnt)
+
+    def read_timing_stats(self):
+        """(sum ms, count, min ms, median ms) per kind of bracket since the last read."""
+        ms = (C.c_double * 4)(); cnt = (C.c_int64 * 4)(); lo = (C.c_double * 4)(); med = (C.c_double * 4)()
+        _check(lib().qsr_read_timing_stats(self._ctx, ms, cnt, lo, med), "qsr_read_timing_stats")
+        return list(ms), list(cnt), list(lo), list(med)
 
     def close(self):
         if self._ctx:

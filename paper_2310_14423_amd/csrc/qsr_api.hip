@@ -4,6 +4,7 @@
 #include <cmath>
 #include <cstring>
 #include <new>
+#include <algorithm>
 #include <vector>
 
 #include "qsr_internal.h"
@@ -568,7 +569,8 @@ extern "C" int qsr_timing(qsr_ctx *c, int enable)
     return QSR_OK;
 }
 
-extern "C" int qsr_read_timing(qsr_ctx *c, double ms[4], int64_t count[4])
+extern "C" int qsr_read_timing_stats(qsr_ctx *c, double ms[4], int64_t count[4], double ms_min[4],
+                                     double ms_median[4])
 {
     if (!c || !ms || !count) return QSR_EINVAL;
     for (int i = 0; i < 4; ++i) { ms[i] = 0.0; count[i] = 0; }
@@ -579,6 +581,7 @@ extern "C" int qsr_read_timing(qsr_ctx *c, double ms[4], int64_t count[4])
     std::vector<long long> log((size_t)rounds);
     if (rounds > 0) HIP_TRY(hipMemcpy(log.data(), c->d_log_t, (size_t)rounds * sizeof(long long), hipMemcpyDeviceToHost));
     size_t li = 0;
+    std::vector<float> each[4];
     for (auto &p : c->pairs) {
         float e = 0.f;
         HIP_TRY(hipEventElapsedTime(&e, p.a, p.b));
@@ -589,11 +592,28 @@ extern "C" int qsr_read_timing(qsr_ctx *c, double ms[4], int64_t count[4])
             slot = ran ? 2 : 3;
         }
         ms[slot] += (double)e; count[slot] += 1;
+        if (ms_min || ms_median) each[slot].push_back(e);
         c->free_events.push_back(p.a);
         c->free_events.push_back(p.b);
     }
     c->pairs.clear();
+    for (int i = 0; i < 4; ++i) {
+        std::vector<float> &v = each[i];
+        double lo = 0.0, med = 0.0;
+        if (!v.empty()) {
+            std::sort(v.begin(), v.end());
+            lo = v.front();
+            med = v.size() % 2 ? v[v.size() / 2] : 0.5 * ((double)v[v.size() / 2 - 1] + (double)v[v.size() / 2]);
+        }
+        if (ms_min) ms_min[i] = lo;
+        if (ms_median) ms_median[i] = med;
+    }
     return QSR_OK;
+}
+
+extern "C" int qsr_read_timing(qsr_ctx *c, double ms[4], int64_t count[4])
+{
+    return qsr_read_timing_stats(c, ms, count, nullptr, nullptr);
 }
 
 extern "C" int qsr_average_rows(float *buf, int32_t K, int64_t P, void *stream)

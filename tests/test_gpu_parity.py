@@ -891,6 +891,21 @@ def torch_equal(a, b):
     return bool(torch.equal(a, b))
 
 
+def test_timing_statistics():
+    """qsr_read_timing_stats: sums and counts as qsr_read_timing gives them, plus the shortest and
+    the median bracket of each kind."""
+    w = workloads.get("flat60m", K=2, P=4096, T=40, H_base=4, alpha=0.0, power=0)
+    ctx = gpu_ctx(w)
+    ctx.timing(True)
+    ctx.step(9)
+    ms, cnt, lo, med = ctx.read_timing_stats()
+    assert cnt == [9, 9, 2, 7]                       # averaging ran after iterations 4 and 8
+    for i in range(4):
+        assert 0 < lo[i] <= med[i] and lo[i] * cnt[i] <= ms[i] * (1 + 1e-6)
+    assert ctx.read_timing() == ([0.0] * 4, [0] * 4)   # the pairs were consumed
+    ctx.close()
+
+
 def test_protocol_errors():
     import paper_2310_14423_amd as qsr
     w = _ext_workload("sgdm", 2, 8, 2, mu=0.5, lam=0.0)
