@@ -55,24 +55,28 @@ def cpu_baseline(w, cpu_seconds_target=20.0):
     if w["model"] != "noise":
         return None
 
-    def run(steps):
+    def run(steps, n_threads):
         eta = oracle.lr_cosine(w["T"], w.get("T_warm", 0), w["eta_max"], w.get("eta_min", 0.0))
         r = oracle.Run(K=w["K"], n=P, eta=eta, T_warm=w.get("T_warm", 0), opt=w["opt"],
                        beta1=w["beta1"], beta2=w["beta2"], eps=w["eps"], lam=w["lam"],
                        H_base=1, alpha=0.0, model="noise", seed=w["seed"],
-                       grad_sigma=w["grad_sigma"], n_threads=threads)
+                       grad_sigma=w["grad_sigma"], n_threads=n_threads)
         t0 = time.perf_counter()
         r.step(steps)                 # H = 1: every step also averages, like the GPU's worst case
         return time.perf_counter() - t0
 
-    t1 = run(2)
+    t1 = run(2, threads)
     # about 20 s of CPU work in total: wall time per step times the threads it keeps busy
     steps = int(max(2, min(200, cpu_seconds_target / max(t1 / 2 * threads, 1e-3))))
-    dt = run(steps)
+    dt = run(steps, threads)
+    steps1 = max(2, steps // 8)       # and a few seconds on one core
+    dt1 = run(steps1, 1)
     return {"value": w["K"] * P * steps / dt, "unit": "replica-param updates/s", "cores": threads,
             "kind": "oracle",
             "sample": "K=%d, P=%d (of %d), %d iterations of noise gradient + AdamW + averaging "
-                      "every step, double precision, %.1f s wall" % (w["K"], P, w["P"], steps, dt)}
+                      "every step, double precision, %.1f s wall" % (w["K"], P, w["P"], steps, dt),
+            "value_one_core": w["K"] * P * steps1 / dt1,
+            "sample_one_core": "the same, %d iterations on one thread, %.1f s wall" % (steps1, dt1)}
 
 
 def run_workload(name, steps, warmup, kernel_timing=True, fuse_gradient=True):
