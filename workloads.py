@@ -7,7 +7,7 @@ the regression target w*, class means, the teacher map).  Per-iteration data
 are drawn inside each implementation from Philox4x32-10, keyed
 (seed; group, stream, worker, iteration).
 
-The five workloads stand in for the paper's ImageNet runs (Sec. 4, App. C of
+The six workloads stand in for the paper's ImageNet runs (Sec. 4, App. C of
 arXiv 2310.14423), which need a dataset and trained models that are not
 available: "lsq" and "mlp" carry the ResNet recipe's optimizer (SGD, momentum
 0.9, step or cosine decay), "flat60m"/"flat350m" carry the ViT recipe's
