@@ -157,6 +157,16 @@ int qsr_local_step(qsr_ctx *ctx);
  * Asynchronous. */
 int qsr_maybe_sync(qsr_ctx *ctx);
 
+/* n global iterations of Alg. 2, each a qsr_local_step followed by its qsr_maybe_sync, with the
+ * same results bit for bit.  Every kernel reads t, h, H and the averaging decision from device
+ * memory, so the launches of an iteration do not depend on t: on a stream other than the null
+ * stream, with qsr_timing off and n large enough to pay for it, they are recorded once into a
+ * HIP graph (kernel nodes only) that is replayed, which removes most of the launch cost of the
+ * short iterations of small models; otherwise the iterations are enqueued one by one.
+ * Asynchronous.  n >= 0; QSR_ESTATE if a qsr_maybe_sync is pending or fewer than n iterations
+ * are left before T. */
+int qsr_run(qsr_ctx *ctx, int64_t n);
+
 /* Synchronises the stream and reads the scheduler state: period of the current round (0 once
  * t == T), number of finished rounds, iteration counter.  Any pointer may be NULL. */
 int qsr_get_H(qsr_ctx *ctx, int64_t *H, int64_t *round, int64_t *t);

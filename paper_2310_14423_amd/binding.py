@@ -10,7 +10,7 @@ _LIB = os.path.join(_HERE, "libqsr.so")
 _lib = None
 
 EXPORTS = ["qsr_validate", "qsr_workspace_bytes", "qsr_init", "qsr_local_step", "qsr_maybe_sync",
-           "qsr_get_H", "qsr_get_state", "qsr_set_state", "qsr_read_sync_log", "qsr_eta_table", "qsr_read_loss", "qsr_restart",
+           "qsr_run", "qsr_get_H", "qsr_get_state", "qsr_set_state", "qsr_read_sync_log", "qsr_eta_table", "qsr_read_loss", "qsr_restart",
            "qsr_timing", "qsr_read_timing", "qsr_read_timing_stats", "qsr_destroy", "qsr_average_rows", "qsr_strerror",
            "qsr_last_hip_error"]
 
@@ -239,6 +239,11 @@ class Context:
         for _ in range(n):
             _check(L.qsr_local_step(ctx), "qsr_local_step")
             _check(L.qsr_maybe_sync(ctx), "qsr_maybe_sync")
+
+    def run(self, n):
+        """n iterations in one call; replays a captured HIP graph when the context was made on a
+        stream other than the null stream (`with torch.cuda.stream(s): Context(...)`)."""
+        _check(lib().qsr_run(self._ctx, C.c_int64(n)), "qsr_run")
 
     # ---- the rest of the ABI
     def read_sync_log(self):

@@ -56,6 +56,9 @@ struct qsr_ctx {
     bool timing;
     std::vector<TimedPair> pairs;
     std::vector<hipEvent_t> free_events;
+    // replay: the launches of graph_iters iterations, captured once (qsr_run)
+    hipGraphExec_t graph_exec;
+    int graph_iters;
 };
 
 // ------------------------------------------------------------------------------------------
@@ -254,6 +257,7 @@ static void free_ctx(qsr_ctx *c)
     if (c->d_clip_part) (void)hipFree(c->d_clip_part);
     if (c->d_clip_coef) (void)hipFree(c->d_clip_coef);
     if (c->h_state) (void)hipHostFree(c->h_state);
+    if (c->graph_exec) (void)hipGraphExecDestroy(c->graph_exec);
     delete c;
 }
 
@@ -333,6 +337,9 @@ extern "C" int qsr_init(const qsr_config *cfg, float *params, float *grads, floa
     c->d_log_H = nullptr; c->d_loss = nullptr; c->h_state = nullptr;
     c->d_clip_part = nullptr; c->d_clip_coef = nullptr;
     c->t_host = 0; c->need_sync_call = false; c->timing = false;
+    c->graph_exec = nullptr;
+    // iterations per captured graph: several where an iteration is a handful of short launches
+    c->graph_iters = cfg->model == QSR_MODEL_RESMLP ? 1 : 8;
     c->dims = make_dims(cfg);
     rc = init_impl(c, theta0);
     c->cfg.milestones = nullptr;
@@ -484,6 +491,51 @@ extern "C" int qsr_maybe_sync(qsr_ctx *c)
     HIP_TRY(launch_sched_next_round(c->d_state, c->sp, c->stream));
     c->need_sync_call = false;
     return QSR_OK;
+}
+
+static int run_one_by_one(qsr_ctx *c, long long n)
+{
+    for (long long i = 0; i < n; ++i) {
+        int rc = qsr_local_step(c);
+        if (rc == QSR_OK) rc = qsr_maybe_sync(c);
+        if (rc != QSR_OK) return rc;
+    }
+    return QSR_OK;
+}
+
+// Every kernel of an iteration takes t, h, H and the averaging decision from device memory, and
+// launch shapes depend on the configuration only: the launches of one iteration are the same for
+// every t, so they are recorded once into a HIP graph (kernel nodes only) and replayed.
+extern "C" int qsr_run(qsr_ctx *c, int64_t n)
+{
+    if (!c || n < 0) return QSR_EINVAL;
+    if (c->need_sync_call || n > c->cfg.T - c->t_host) return QSR_ESTATE;
+    const long long per = c->graph_iters;
+    // the null stream cannot be captured; with timing on every launch gets its own event bracket
+    if (c->timing || c->stream == nullptr || n < 1 + 2 * per) return run_one_by_one(c, n);
+    if (!c->graph_exec) {
+        // whatever a kernel sets up at its first launch happens here, outside the capture
+        int rc = run_one_by_one(c, 1);
+        if (rc != QSR_OK) return rc;
+        n -= 1;
+        const long long t_keep = c->t_host;
+        HIP_TRY(hipStreamBeginCapture(c->stream, hipStreamCaptureModeRelaxed));
+        rc = run_one_by_one(c, per);                  // recorded, not run
+        hipGraph_t g = nullptr;
+        hipError_t e = hipStreamEndCapture(c->stream, &g);
+        c->t_host = t_keep;
+        c->need_sync_call = false;
+        if (rc == QSR_OK && e == hipSuccess) e = hipGraphInstantiate(&c->graph_exec, g, nullptr, nullptr, 0);
+        if (g) (void)hipGraphDestroy(g);
+        if (rc != QSR_OK) return rc;
+        if (e != hipSuccess) { c->graph_exec = nullptr; g_last_hip = (int)e; return QSR_EHIP; }
+    }
+    while (n >= per) {
+        HIP_TRY(hipGraphLaunch(c->graph_exec, c->stream));
+        c->t_host += per;
+        n -= per;
+    }
+    return run_one_by_one(c, n);
 }
 
 static int fetch_state(qsr_ctx *c)

@@ -1,0 +1,92 @@
+"""qsr_run: iterations replayed from a captured HIP graph give, bit for bit, what the same
+iterations enqueued one by one give.  Each case replays the graph several times, with iterations
+enqueued one by one, synchronizing reads and a restart between the replays."""
+import numpy as np
+import pytest
+
+import workloads
+from util import gpu_ctx
+
+pytestmark = pytest.mark.gpu
+
+CASES = {
+    "lsq": dict(name="lsq"),
+    "mlp": dict(name="mlp", d_in=72, d_hidden=96, d_out=10, B_loc=48, K=3, T=150, milestones=(60, 100),
+                eta_max=0.1, alpha=0.04),
+    "adamw": dict(name="flat60m", K=4, P=20003, T=150, alpha=0.004),
+    "adamw, gradient drawn inside": dict(name="flat60m", K=4, P=20004, T=150, alpha=0.004, fuse_gradient=2),
+    "adamw, clipping, state averaged": dict(name="flat60m", K=3, P=9001, T=150, alpha=0.004, clip_norm=0.05,
+                                            average_state=True),
+    "adamw, averaging fused": dict(name="flat60m", K=4, P=20003, T=150, alpha=0.004, fuse_sync=1),
+    "parallel sgd": dict(name="flat60m", K=4, P=5003, T=150, opt="sgdm", mu=0.9, lam=1e-4, parallel=True,
+                         H_base=1, power=0),
+    "resmlp": dict(name="resmlp", d_in=64, d_hidden=128, n_blocks=2, B_loc=100, K=2, T=60, T_warm=4,
+                   eta_max=8e-4, alpha=0.0035),
+    "vit": dict(name="vit", d_in=64, n_heads=1, seq_len=25, d_hidden=128, n_blocks=2, B_loc=100, K=2, T=60,
+                T_warm=4, eta_max=8e-4, alpha=0.0035),
+}
+
+
+def _drive(ctx, T, one_by_one):
+    """The same T iterations in the same pieces; the pieces of 20 or more go through qsr_run."""
+    go = (lambda n: ctx.step(n)) if one_by_one else (lambda n: ctx.run(n))
+    out = []
+    go(T // 2)                              # first call: one iteration by itself, the capture, replays
+    out.append(ctx.get_H())                 # synchronizes
+    ctx.step(3)                             # iterations enqueued one by one between replays
+    go(T - T // 2 - 3 - 2)                  # replays of the graph made before
+    out.append(ctx.get_state())
+    go(2)                                   # too few for a replay
+    out.append(ctx.read_sync_log())
+    out.append([x.clone() for x in (ctx.params, ctx.state0) + ((ctx.state1,) if ctx.state1 is not None else ())])
+    ctx.restart()                           # a second run from t = 0 over the same buffers
+    go(T // 3)
+    out.append(ctx.get_H())
+    out.append(ctx.params.clone())
+    return out
+
+
+@pytest.mark.parametrize("case", list(CASES))
+def test_replayed_iterations_are_bit_identical(case):
+    import torch
+    kw = dict(CASES[case])
+    w = workloads.get(kw.pop("name"), **kw)
+    T = w["T"]
+    ref_ctx = gpu_ctx(w)                                    # null stream: never captured
+    ref = _drive(ref_ctx, T, one_by_one=True)
+    ref_ctx.close()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        ctx = gpu_ctx(w)
+        assert ctx.stream.cuda_stream != 0
+        got = _drive(ctx, T, one_by_one=False)
+        side.synchronize()
+    assert got[0] == ref[0] and got[1] == ref[1] and got[4] == ref[4]
+    assert ref[0][2] == T // 2 and ref[1][0] == T - 2 and len(ref[2][0]) >= 2
+    for a, b in zip(got[2], ref[2]):
+        assert np.array_equal(a, b)
+    for a, b in zip(got[3] + [got[5]], ref[3] + [ref[5]]):
+        assert torch.equal(a, b)
+    ctx.close()
+
+
+def test_run_protocol():
+    import torch
+    import paper_2310_14423_amd as qsr
+    w = workloads.get("flat60m", K=2, P=1024, T=50, alpha=0.004)
+    with torch.cuda.stream(torch.cuda.Stream()):
+        ctx = gpu_ctx(w)
+        ctx.run(0)
+        ctx.local_step()
+        with pytest.raises(qsr.QSRError):
+            ctx.run(1)                      # qsr_maybe_sync pending
+        ctx.maybe_sync()
+        with pytest.raises(qsr.QSRError):
+            ctx.run(50)                     # only 49 iterations left
+        with pytest.raises(qsr.QSRError):
+            ctx.run(-1)
+        ctx.run(49)
+        assert ctx.get_H()[2] == 50
+        with pytest.raises(qsr.QSRError):
+            ctx.run(1)
+        ctx.close()
