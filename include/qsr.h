@@ -9,6 +9,7 @@
  *     qsr_maybe_sync   -- if the round's H-th local step has just run: parameter averaging
  *                         (the All-Reduce line of Alg. 2) and the next round's H from
  *                         Eq. (2), H = max{H_base, floor((alpha/eta_t)^2)}
+ *     qsr_run          -- n such iterations in one call
  *
  * The scheduler state (t, s, h, H), the learning-rate table and the log of averaging
  * points live in device memory; the two calls above only enqueue kernels on the caller's
