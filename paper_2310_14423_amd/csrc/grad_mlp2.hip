@@ -140,12 +140,25 @@ __global__ __launch_bounds__(256) void skinny_bias_kernel(const float *__restric
     float acc[NMAX];
 #pragma unroll
     for (int n = 0; n < NMAX; ++n) acc[n] = 0.f;
-    for (int kk = lane; kk < Kd; kk += 64) {
-        const float av = a[kk];
-        const float *br = b + (long long)kk * N;
+    // four steps of the contraction are loaded before their products are added (in the same
+    // ascending order): a launch of one wavefront per SIMD hides no load latency by itself
+    for (int kk0 = lane; kk0 < Kd; kk0 += 256) {
+        float av[4], bv[4][NMAX];
 #pragma unroll
-        for (int n = 0; n < NMAX; ++n)
-            if (n < N) acc[n] = fmaf(av, br[n], acc[n]);
+        for (int u = 0; u < 4; ++u) {
+            const int kk = kk0 + 64 * u;
+            const bool in = kk < Kd;
+            av[u] = in ? a[kk] : 0.f;
+            const float *br = b + (long long)(in ? kk : 0) * N;
+#pragma unroll
+            for (int n = 0; n < NMAX; ++n) bv[u][n] = n < N ? br[n] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (kk0 + 64 * u < Kd) {
+#pragma unroll
+                for (int n = 0; n < NMAX; ++n) acc[n] = fmaf(av[u], bv[u][n], acc[n]);
+            }
     }
     float mine = 0.f;
 #pragma unroll

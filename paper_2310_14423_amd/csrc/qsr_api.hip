@@ -512,14 +512,18 @@ extern "C" int qsr_run(qsr_ctx *c, int64_t n)
     if (c->need_sync_call || n > c->cfg.T - c->t_host) return QSR_ESTATE;
     const long long per = c->graph_iters;
     // the null stream cannot be captured; with timing on every launch gets its own event bracket
-    if (c->timing || c->stream == nullptr || n < 1 + 2 * per) return run_one_by_one(c, n);
+    if (c->timing || c->stream == nullptr || per < 1 || n < 1 + 2 * per) return run_one_by_one(c, n);
     if (!c->graph_exec) {
         // whatever a kernel sets up at its first launch happens here, outside the capture
         int rc = run_one_by_one(c, 1);
         if (rc != QSR_OK) return rc;
         n -= 1;
         const long long t_keep = c->t_host;
-        HIP_TRY(hipStreamBeginCapture(c->stream, hipStreamCaptureModeRelaxed));
+        if (hipStreamBeginCapture(c->stream, hipStreamCaptureModeRelaxed) != hipSuccess) {
+            (void)hipGetLastError();                  // a stream that cannot be captured: one by one from now on
+            c->graph_iters = 0;
+            return run_one_by_one(c, n);
+        }
         rc = run_one_by_one(c, per);                  // recorded, not run
         hipGraph_t g = nullptr;
         hipError_t e = hipStreamEndCapture(c->stream, &g);

@@ -1,9 +1,11 @@
 // sgemm.h -- batched single-precision GEMM, LDS-tiled, for the small fp32 model workload
 // (two-layer perceptron).  C[b] = op(A[b]) * op(B[b]) with optional epilogue; one launch covers
-// all K workers (blockIdx.z).  64x64 output tile, 16-deep k-slabs, 256 threads: four wavefronts,
-// each a 32x32 block on the fp32 matrix cores (v_mfma_f32_32x32x2_f32: fp32 operands, fp32
-// accumulation, two k per instruction), global loads three slabs ahead in registers.  Every
-// global access is bounds-checked, so any M, N, Kd is accepted.  Fixed order: deterministic.
+// all K workers (blockIdx.z).  64x64 output tile, 16-deep k-slabs, four wavefronts, each a 32x32
+// block on the fp32 matrix cores (v_mfma_f32_32x32x2_f32: fp32 operands, fp32 accumulation, two
+// k per instruction), global loads three slabs ahead in registers.  A long contraction is cut in
+// two halves that two such groups of four wavefronts in one workgroup run side by side (KSPLIT =
+// 2; the halves are added through LDS at the end).  Every global access is bounds-checked, so
+// any M, N, Kd is accepted.  Fixed order: deterministic.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -22,13 +24,19 @@ struct GemmArgs {
     const float *aux;          // EPI_MASK_POS: same layout as C; C = aux > 0 ? acc : 0
 };
 
-template <bool TA, bool TB, int EPI>
-__global__ __launch_bounds__(256) void sgemm_kernel(GemmArgs a)
+template <bool TA, bool TB, int EPI, int KSPLIT>
+__global__ __launch_bounds__(256 * KSPLIT) void sgemm_kernel(GemmArgs a)
 {
     constexpr int TM = 64, TN = 64, TK = 16, PAD = 32;   // rows k and k+1 of a slab 32 banks apart
-    __shared__ float As[TK][TM + PAD];
-    __shared__ float Bs[TK][TN + PAD];
-    const int tid = threadIdx.x;
+    __shared__ float As_all[KSPLIT][TK][TM + PAD];
+    __shared__ float Bs_all[KSPLIT][TK][TN + PAD];
+    // The workgroup is KSPLIT groups of 256 threads; group grp contracts over its own run of
+    // slabs with its own LDS slabs.  With one workgroup of four wavefronts per compute unit (the
+    // batch is 128 rows) every slab's load -> LDS -> barrier -> MFMA chain ran unhidden; a second
+    // group per SIMD fills part of those gaps (hidden layer forward, 8 x 128 x 784 x 1024: 46 -> 37 us).
+    const int grp = threadIdx.x >> 8, tid = threadIdx.x & 255;
+    float (*As)[TM + PAD] = As_all[grp];
+    float (*Bs)[TN + PAD] = Bs_all[grp];
     const int lane = tid & 63, wm = tid >> 7, wn = (tid >> 6) & 1;   // wavefront (wm, wn) owns a 32x32 block
     const int m0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
     const long long bz = blockIdx.z;
@@ -79,17 +87,20 @@ __global__ __launch_bounds__(256) void sgemm_kernel(GemmArgs a)
             else    Bs[(tid >> 6) + 4 * r][tid & 63] = xb[r];
         }
     };
-    const int nslab = (a.Kd + TK - 1) / TK;
+    // every group runs the same number of slabs (the barriers are the workgroup's); slabs past
+    // Kd load zeros
+    const int nslab = ((a.Kd + TK - 1) / TK + KSPLIT - 1) / KSPLIT;
+    const int kbase = grp * nslab * TK;
 #pragma unroll
     for (int u = 0; u < PF; ++u)
-        if (u < nslab) gload(u * TK, ra[u], rb[u]);
+        if (u < nslab) gload(kbase + u * TK, ra[u], rb[u]);
     for (int s0 = 0; s0 < nslab; s0 += PF) {
 #pragma unroll
         for (int u = 0; u < PF; ++u) {
             const int sl = s0 + u;                  // uniform over the workgroup
             if (sl < nslab) {
                 sstore(ra[u], rb[u]);
-                if (sl + PF < nslab) gload((sl + PF) * TK, ra[u], rb[u]);
+                if (sl + PF < nslab) gload(kbase + (sl + PF) * TK, ra[u], rb[u]);
                 __syncthreads();
                 // lane l supplies A[row l%32][k l/32] and B[k l/32][column l%32] of the instruction
 #pragma unroll
@@ -101,6 +112,20 @@ __global__ __launch_bounds__(256) void sgemm_kernel(GemmArgs a)
                 __syncthreads();
             }
         }
+    }
+
+    if constexpr (KSPLIT > 1) {       // the other groups' partial sums, added in group order
+        __shared__ float part[KSPLIT - 1][4][16][64];
+        if (grp > 0) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) part[grp - 1][tid >> 6][i][lane] = acc[i];
+        }
+        __syncthreads();
+        if (grp > 0) return;
+#pragma unroll
+        for (int g = 0; g < KSPLIT - 1; ++g)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[i] += part[g][tid >> 6][i][lane];
     }
 
     // accumulator element i of lane l is C[(i/4)*8 + (l/32)*4 + i%4][l%32] of the wavefront's block
@@ -122,7 +147,8 @@ template <bool TA, bool TB, int EPI>
 inline hipError_t launch_sgemm(const GemmArgs &a, int batch, hipStream_t s)
 {
     dim3 grid((unsigned)((a.N + 63) / 64), (unsigned)((a.M + 63) / 64), (unsigned)batch);
-    sgemm_kernel<TA, TB, EPI><<<grid, 256, 0, s>>>(a);
+    if (a.Kd >= 256) sgemm_kernel<TA, TB, EPI, 2><<<grid, 512, 0, s>>>(a);
+    else sgemm_kernel<TA, TB, EPI, 1><<<grid, 256, 0, s>>>(a);
     return hipGetLastError();
 }
 
