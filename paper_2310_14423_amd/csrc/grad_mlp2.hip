@@ -39,45 +39,73 @@ size_t mlp2_workspace_bytes(const ModelDims &d)
     return total;
 }
 
-__global__ __launch_bounds__(256) void mlp2_labels_kernel(int *__restrict__ label, long long B,
-                                                          uint32_t classes, uint64_t seed,
-                                                          const DevState *__restrict__ st)
+// Sample() in one pass: label c_i uniform over the classes, x_i = mu_{c_i} + sigma z.  One thread
+// per group of four consecutive elements of a worker's [B][d_in] batch (the group is the Philox
+// counter of the normal draws); the label of a row comes from word i % 4 of the label stream's
+// group i / 4 and is recomputed by every thread that needs it, which is cheaper than a kernel of
+// its own; the thread that holds a row's first element also stores the label for the loss.
+__global__ __launch_bounds__(64) void mlp2_sample_kernel(float *__restrict__ X, int *__restrict__ label,
+                                                         const float *__restrict__ means, long long B,
+                                                         long long d_in, uint32_t classes, float sigma,
+                                                         uint64_t seed, const DevState *__restrict__ st)
 {
+    const uint32_t t = (uint32_t)st->t;
     const uint32_t k = blockIdx.y;
-    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (i >= B) return;
-    U4 r = draw4(seed, STREAM_LABEL, k, (uint32_t)st->t, (uint32_t)(i >> 2));
-    uint32_t w = (i & 3) == 0 ? r.x : (i & 3) == 1 ? r.y : (i & 3) == 2 ? r.z : r.w;
-    label[(long long)k * B + i] = (int)index_from_word(w, classes);
-}
-
-// X holds sigma*z on entry; add the class mean of each sample's label
-__global__ __launch_bounds__(256) void mlp2_add_means_kernel(float *__restrict__ X,
-                                                             const int *__restrict__ label,
-                                                             const float *__restrict__ means,
-                                                             long long B, long long d_in)
-{
-    const int k = blockIdx.y;
-    const long long n = B * d_in;
-    const long long stride = (long long)gridDim.x * 256;
-    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < n; e += stride) {
-        long long i = e / d_in, j = e - i * d_in;
-        int c = label[(long long)k * B + i];
-        X[(long long)k * n + e] += means[(long long)c * d_in + j];
+    const long long n = B * d_in, groups = (n + 3) / 4;
+    float *x = X + (long long)k * n;
+    int *lab = label + (long long)k * B;
+    auto label_of = [&](long long i) {
+        const U4 r = draw4(seed, STREAM_LABEL, k, t, (uint32_t)(i >> 2));
+        const uint32_t w = (i & 3) == 0 ? r.x : (i & 3) == 1 ? r.y : (i & 3) == 2 ? r.z : r.w;
+        return (int)index_from_word(w, classes);
+    };
+    const long long stride = (long long)gridDim.x * 64;
+    for (long long q = (long long)blockIdx.x * 64 + threadIdx.x; q < groups; q += stride) {
+        const float4 z4 = normal4(seed, STREAM_X, k, t, (uint32_t)q);
+        const float z[4] = {z4.x, z4.y, z4.z, z4.w};
+        const long long p = q * 4;
+        long long i = p / d_in, j = p - i * d_in;
+        int c = label_of(i);
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (p + e < n) {
+                if (j == 0) lab[i] = c;
+                v[e] = z[e] * sigma + means[(long long)c * d_in + j];
+                if (++j == d_in) {
+                    j = 0; ++i;
+                    if (e < 3 && p + e + 1 < n) c = label_of(i);
+                }
+            }
+        }
+        if ((n & 3) == 0) {
+            *(float4 *)(x + p) = make_float4(v[0], v[1], v[2], v[3]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (p + e < n) x[p + e] = v[e];
+        }
     }
 }
 
-// per sample: logits -> (softmax - onehot)/B in place; per worker: mean cross-entropy.
-// One block per worker, samples strided over its threads (d_out is small).
+// per sample: logits -> (softmax - onehot)/B in place; per worker: mean cross-entropy and, for at
+// most CMAX classes, the output bias gradient (the column sums of the new logits array), which
+// would otherwise be a launch of its own.  One block per worker, samples strided over its
+// threads (d_out is small).
+template <int CMAX>
 __global__ __launch_bounds__(256) void mlp2_softmax_ce_kernel(float *__restrict__ logit,
                                                               const int *__restrict__ label,
                                                               float *__restrict__ loss,
+                                                              float *__restrict__ gbias, long long sG,
                                                               long long B, int C)
 {
-    __shared__ float red[4];
+    __shared__ float red[4][CMAX + 1];
     const int k = blockIdx.x;
     const float invB = 1.0f / (float)B;
     float lsum = 0.f;
+    float cs[CMAX > 0 ? CMAX : 1];
+#pragma unroll
+    for (int o = 0; o < CMAX; ++o) cs[o] = 0.f;
     for (long long i = threadIdx.x; i < B; i += 256) {
         float *z = logit + ((long long)k * B + i) * C;
         const int y = label[(long long)k * B + i];
@@ -87,13 +115,33 @@ __global__ __launch_bounds__(256) void mlp2_softmax_ce_kernel(float *__restrict_
         for (int o = 0; o < C; ++o) se += expf(z[o] - mx);
         lsum += (mx + logf(se)) - z[y];
         const float inv = 1.0f / se;
-        for (int o = 0; o < C; ++o) z[o] = (expf(z[o] - mx) * inv - (o == y ? 1.f : 0.f)) * invB;
+        if (CMAX > 0) {
+#pragma unroll
+            for (int o = 0; o < CMAX; ++o)
+                if (o < C) {
+                    const float dz = (expf(z[o] - mx) * inv - (o == y ? 1.f : 0.f)) * invB;
+                    z[o] = dz;
+                    cs[o] += dz;
+                }
+        } else {
+            for (int o = 0; o < C; ++o) z[o] = (expf(z[o] - mx) * inv - (o == y ? 1.f : 0.f)) * invB;
+        }
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) lsum += __shfl_down(lsum, o, 64);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = lsum;
+#pragma unroll
+    for (int c = 0; c < CMAX; ++c)
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) cs[c] += __shfl_down(cs[c], o, 64);
+    if ((threadIdx.x & 63) == 0) {
+        red[threadIdx.x >> 6][CMAX] = lsum;
+#pragma unroll
+        for (int c = 0; c < CMAX; ++c) red[threadIdx.x >> 6][c] = cs[c];
+    }
     __syncthreads();
-    if (threadIdx.x == 0) loss[k] = (red[0] + red[1] + red[2] + red[3]) * invB;
+    if (threadIdx.x == 0) loss[k] = (red[0][CMAX] + red[1][CMAX] + red[2][CMAX] + red[3][CMAX]) * invB;
+    if (CMAX > 0 && (int)threadIdx.x < C)
+        gbias[(long long)k * sG + threadIdx.x] = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
 }
 
 // out[k][j] = sum_i A[k][i][j]   (bias gradients).  One thread per column, rows added in ascending
@@ -180,15 +228,12 @@ hipError_t launch_mlp2_grad(const ModelDims &d, const float *theta, float *g, co
     const long long oW1 = 0, ob1 = di * dh, oW2 = ob1 + dh, ob2 = oW2 + dh * dz;
     hipError_t e;
 
-    // Sample(): labels, then inputs
-    mlp2_labels_kernel<<<dim3((unsigned)((B + 255) / 256), (unsigned)K), 256, 0, s>>>(
-        w.label, B, (uint32_t)dz, d.seed, st);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    if ((e = launch_fill_normal(w.X, B * di, K, B * di, d.data_sigma, STREAM_X, d.seed, st, s)) != hipSuccess) return e;
+    // Sample(): labels and inputs
     {
-        long long bx = (B * di + 255) / 256;
-        if (bx > 4096) bx = 4096;
-        mlp2_add_means_kernel<<<dim3((unsigned)bx, (unsigned)K), 256, 0, s>>>(w.X, w.label, means, B, di);
+        long long bx = ((B * di + 3) / 4 + 63) / 64;
+        if (bx > 0x7FFFFFFFll) bx = 0x7FFFFFFFll;
+        mlp2_sample_kernel<<<dim3((unsigned)bx, (unsigned)K), 64, 0, s>>>(w.X, w.label, means, B, di, (uint32_t)dz,
+                                                                        (float)d.data_sigma, d.seed, st);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     // forward
@@ -210,7 +255,9 @@ hipError_t launch_mlp2_grad(const ModelDims &d, const float *theta, float *g, co
         if ((e = hipGetLastError()) != hipSuccess) return e;
     } else if ((e = launch_sgemm<false, false, EPI_BIAS>(a, K, s)) != hipSuccess) return e;
 
-    mlp2_softmax_ce_kernel<<<K, 256, 0, s>>>(w.logit, w.label, loss, B, (int)dz);
+    const bool bias_grad_in_loss = dz <= 16;
+    if (bias_grad_in_loss) mlp2_softmax_ce_kernel<16><<<K, 256, 0, s>>>(w.logit, w.label, loss, g + ob2, P, B, (int)dz);
+    else mlp2_softmax_ce_kernel<0><<<K, 256, 0, s>>>(w.logit, w.label, loss, nullptr, 0, B, (int)dz);
     if ((e = hipGetLastError()) != hipSuccess) return e;
 
     // backward; w.logit now holds d loss / d logits
@@ -220,9 +267,11 @@ hipError_t launch_mlp2_grad(const ModelDims &d, const float *theta, float *g, co
     a.C = g + oW2; a.ldc = dz; a.sC = P;
     a.M = (int)dh; a.N = (int)dz; a.Kd = (int)B;
     if ((e = launch_sgemm<true, false, EPI_NONE>(a, K, s)) != hipSuccess) return e;
-    colsum_kernel<<<dim3((unsigned)((dz + 255) / 256), (unsigned)K), 256, 0, s>>>(
-        w.logit, g + ob2, B, dz, B * dz, P);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (!bias_grad_in_loss) {
+        colsum_kernel<<<dim3((unsigned)((dz + 255) / 256), (unsigned)K), 256, 0, s>>>(
+            w.logit, g + ob2, B, dz, B * dz, P);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
 
     a = GemmArgs{};                                        // dhid = (dlogits W2^T) * [hid > 0]
     a.A = w.logit; a.lda = dz; a.sA = B * dz;

@@ -255,7 +255,11 @@ def test_lsq_gradient_and_loss_single_step():
 
 
 @pytest.mark.parametrize("dims", [dict(d_in=13, d_hidden=17, d_out=5, B_loc=11, K=2),
-                                  dict(d_in=70, d_hidden=130, d_out=10, B_loc=67, K=3)])
+                                  dict(d_in=70, d_hidden=130, d_out=10, B_loc=67, K=3),
+                                  # rows shorter than a group of four draws; more classes than the
+                                  # loss kernel sums bias gradients for; a contraction cut in two
+                                  dict(d_in=3, d_hidden=9, d_out=20, B_loc=10, K=2),
+                                  dict(d_in=300, d_hidden=40, d_out=16, B_loc=32, K=2)])
 def test_mlp2_gradient_single_step(dims):
     w = workloads.get("mlp", T=4, **dims)
     ctx = gpu_ctx(w)
