@@ -90,3 +90,25 @@ def test_run_protocol():
         with pytest.raises(qsr.QSRError):
             ctx.run(1)
         ctx.close()
+
+
+def test_run_with_timing_on_goes_one_by_one():
+    """With event brackets on, qsr_run enqueues the iterations one by one (every launch is timed), also
+    after a graph has been captured, and the results do not depend on which way an iteration went."""
+    import torch
+    w = workloads.get("flat60m", K=2, P=4096, T=120, H_base=4, alpha=0.0, power=0)
+    ref = gpu_ctx(w)
+    ref.step(120)
+    with torch.cuda.stream(torch.cuda.Stream()):
+        ctx = gpu_ctx(w)
+        ctx.run(40)                          # captured and replayed
+        ctx.timing(True)
+        ctx.run(40)
+        ms, cnt = ctx.read_timing()
+        assert cnt == [40, 40, 10, 30]
+        ctx.timing(False)
+        ctx.run(40)                          # replays again
+        assert ctx.get_H()[1:] == (30, 120)
+        assert torch.equal(ctx.params, ref.params) and torch.equal(ctx.state1, ref.state1)
+        ctx.close()
+    ref.close()
