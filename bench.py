@@ -75,6 +75,9 @@ def cpu_baseline(w, cpu_seconds_target=20.0):
             "kind": "oracle",
             "sample": "K=%d, P=%d (of %d), %d iterations of noise gradient + AdamW + averaging "
                       "every step, double precision, %.1f s wall" % (w["K"], P, w["P"], steps, dt),
+            # the same 28 + 8 algorithmic bytes per replica-parameter as the GPU's two-kernel step with
+            # averaging (the oracle's arrays are double precision: what it really moves is about twice that)
+            "GBs_at_gpu_byte_count": w["K"] * P * steps / dt * (BYTES_PER_UPDATE[w["opt"]] + BYTES_PER_AVERAGE) / 1e9,
             "value_one_core": w["K"] * P * steps1 / dt1,
             "sample_one_core": "the same, %d iterations on one thread, %.1f s wall" % (steps1, dt1)}
 
