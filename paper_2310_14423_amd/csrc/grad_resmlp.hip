@@ -650,10 +650,10 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
     };
     // The gradient with respect to a LayerNorm's output comes out of a bf16 GEMM.  In the MLP-only
     // model it is stored in bf16, like the activations (2 B instead of 4 written by the GEMM and
-    // read by the pass below: 2-3 % of an iteration at the benchmark size).  With
-    // attention sub-blocks the chain of sub-blocks is twice as long and that extra rounding per
-    // sub-block moved the first block's query-weight gradients past the tested bound, so there it
-    // stays in fp32; the buffer is the same.
+    // read by the pass below: 2-3 % of an iteration at the benchmark size).  With attention
+    // sub-blocks it stays in fp32: the query-weight gradients, sums of small softmax-gradient
+    // terms, sit at the tested error bound already, and this one more rounding (in the MLP
+    // sub-block alone) moved an entry past it.  The buffer is the same.
     const bool du16 = heads == 0;
     bf16_t *const DU16 = (bf16_t *)w.DU;
     const long long sDU16 = 2 * w.sDU;
