@@ -174,11 +174,19 @@ static hipError_t launch_cvt_transpose(const TIn *in, long long ld_in, long long
     return hipGetLastError();
 }
 
-__global__ __launch_bounds__(256) void f32_to_bf16_kernel(const float *__restrict__ in,
-                                                          bf16_t *__restrict__ out, long long n)
+// out[z][0..4*n4) = bf16(in[z][0..4*n4)), four elements per lane and trip; blockIdx.y = worker
+__global__ __launch_bounds__(256) void f32_to_bf16_kernel(const float *__restrict__ in, long long s_in,
+                                                          bf16_t *__restrict__ out, long long s_out,
+                                                          long long n4)
 {
+    const float4 *src = (const float4 *)(in + (long long)blockIdx.y * s_in);
+    bf16x4 *dst = (bf16x4 *)(out + (long long)blockIdx.y * s_out);
     const long long stride = (long long)gridDim.x * 256;
-    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) out[i] = (bf16_t)in[i];
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
+        const float4 v = src[i];
+        const bf16x4 b = {(bf16_t)v.x, (bf16_t)v.y, (bf16_t)v.z, (bf16_t)v.w};
+        dst[i] = b;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -692,9 +700,9 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
 
     // Sample(): tokens x_0 (fp32 in X[0], bf16 in U), teacher targets y = x_0 W_T / sqrt(d)
     TRY(launch_fill_normal(w.X, w.sX, K, Md, 1.0f, STREAM_X, dm.seed, st, s));
-    for (int k = 0; k < K; ++k) {
-        long long blocks = (Md + 255) / 256; if (blocks > 65535) blocks = 65535;
-        f32_to_bf16_kernel<<<(unsigned)blocks, 256, 0, s>>>(w.X + k * w.sX, w.U + k * w.sU, Md);
+    {
+        long long blocks = (Md / 4 + 255) / 256; if (blocks > 65535) blocks = 65535;   // d is a multiple of 64
+        f32_to_bf16_kernel<<<dim3((unsigned)blocks, (unsigned)K), 256, 0, s>>>(w.X, w.sX, w.U, w.sU, Md / 4);
         TRY(hipGetLastError());
     }
     {
