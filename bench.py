@@ -2,10 +2,13 @@
 """Benchmark of the QSR hot path on one MI355X.
 
 One "step" = one global iteration of Local OPT for all K workers: local gradients, the fused
-optimizer update, the device-side scheduler tick, and -- when the round's H-th step has run --
-the K-axis replica averaging and the next H from the quadratic rule.  The default workload is
-the optimizer-only 60 M-parameter, 16-replica Local AdamW run (T = 5000, 8 rounds): with the
-default --steps the timed region is exactly one complete run, all averaging rounds included.
+optimizer update, the device-side scheduler, and -- when the round's H-th step has run -- the
+K-axis replica averaging and the next H from the quadratic rule.  The default workload is the
+largest one that fits one GPU: the optimizer-only 350 M-parameter, 32-replica Local AdamW run
+(179 GB of state, T = 2000, 4 averaging rounds).  Without --steps the timed region is exactly one
+complete run; with fewer steps than a run has, the timed window is placed around the run's first
+averaging round (the scheduler state is set to the window's first iteration), so that all four
+parts of the path are inside it.
 
 After the headline run, the five other workloads are run briefly and reported under
 "per_workload" (--headline-only skips them).  Prints ONE JSON line.
@@ -25,11 +28,11 @@ BYTES_PER_UPDATE = {"adamw": 28, "sgdm": 20}   # algorithmic HBM bytes per repli
 BYTES_PER_AVERAGE = 8
 
 # HBM bytes per launch of the update kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE (scaled by a
-# kernel of known size; profiles/flat60m_hbm_traffic_pmc.md).  Valid only for the kernel source
-# the counters were taken on: keyed by the first 16 hex digits of its SHA-256.
+# kernel of known size; profiles/*_hbm_traffic_pmc.md).  Valid only for the kernel source the
+# counters were taken on: keyed by the first 16 hex digits of its SHA-256; null otherwise.
 PMC_SOURCES = ["update.hip", "opt_elem.h", "philox.h"]
-PMC_TRAFFIC = {"flat60m": {"sha256_16": "89d287d57b69beea", "bytes": 26.870e9},                 # gradient read from its buffer
-               "flat60m+fuse_gradient": {"sha256_16": "89d287d57b69beea", "bytes": 23.033e9}}  # drawn inside, never stored
+PMC_TRAFFIC = {}
+
 
 def measured_traffic(workload, fused_gradient):
     import hashlib
@@ -45,46 +48,111 @@ def measured_traffic(workload, fused_gradient):
     return ent["bytes"] if h.hexdigest()[:16] == ent["sha256_16"] else None
 
 
+# ------------------------------------------------------------------------------------------------
+# the CPU oracle beside it
+# ------------------------------------------------------------------------------------------------
+def _oracle_eta(oracle, w):
+    if w["lr"] == "step":
+        return oracle.lr_step(w["T"], w.get("T_warm", 0), w["eta_max"], list(w["milestones"]), w["factor"])
+    return oracle.lr_cosine(w["T"], w.get("T_warm", 0), w["eta_max"], w.get("eta_min", 0.0))
+
+
 def cpu_baseline(w, cpu_seconds_target=20.0):
-    """The CPU oracle, as it stands, on a bounded sample of the same workload."""
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: gradient, update and
+    averaging after every step (H = 1), all K workers, in double precision.  The optimizer-only
+    workloads are sampled in P; the block models in depth and tokens (one block, one sequence of
+    197 tokens per worker at the full layer width), with the figure extrapolated to the full shape
+    given beside the measured one; the two small models run at their full shape."""
     import numpy as np
     import oracle
+    import workloads
     oracle.build()
-    threads = max(1, min(w["K"], os.cpu_count() or 1, 16))
-    P = min(w["P"], 1 << 18)
-    if w["model"] != "noise":
-        return None
+    K = w["K"]
+    threads = max(1, min(K, os.cpu_count() or 1, 16))
+    ws = dict(w)
+    scale_to_full = 1.0
+    if w["model"] == "noise":
+        ws["P"] = min(w["P"], 1 << 20 if K > 16 else 1 << 18)
+        what = "K=%d, P=%d (of %d), noise gradient + %s" % (K, ws["P"], w["P"], w["opt"])
+    elif w["model"] == "resmlp":
+        tokens = 197
+        ws = workloads.get("vit" if w.get("n_heads", 0) else "resmlp", n_blocks=1, B_loc=tokens)
+        # time is proportional to blocks x tokens, the parameter count to blocks
+        scale_to_full = tokens / w["B_loc"]
+        what = ("K=%d, one block of %d/%d%s on %d tokens per worker (of %d blocks on %d tokens), "
+                "gradient by plain loops + AdamW" % (K, w["d_in"], w["d_hidden"],
+                                                   " with its attention sub-block" if w.get("n_heads", 0) else "",
+                                                   tokens, w["n_blocks"], w["B_loc"]))
+    else:
+        what = "K=%d, P=%d, B_loc=%d (the full shape), gradient by plain loops + %s" % (K, w["P"], w["B_loc"], w["opt"])
+    P = ws["P"]
+    eta = _oracle_eta(oracle, ws)
+    const = workloads.model_const(ws)
+    th0 = workloads.theta0(ws)
 
-    def run(steps, n_threads):
-        eta = oracle.lr_cosine(w["T"], w.get("T_warm", 0), w["eta_max"], w.get("eta_min", 0.0))
-        r = oracle.Run(K=w["K"], n=P, eta=eta, T_warm=w.get("T_warm", 0), opt=w["opt"],
-                       beta1=w["beta1"], beta2=w["beta2"], eps=w["eps"], lam=w["lam"],
-                       H_base=1, alpha=0.0, model="noise", seed=w["seed"],
-                       grad_sigma=w["grad_sigma"], n_threads=n_threads)
+    def run(steps, n_threads, Kr=K):
+        r = oracle.Run(K=Kr, n=P, eta=eta, T_warm=ws.get("T_warm", 0), opt=ws["opt"], mu=ws.get("mu", 0.0),
+                       beta1=ws.get("beta1", 0.9), beta2=ws.get("beta2", 0.999), eps=ws.get("eps", 1e-8),
+                       lam=ws.get("lam", 0.0), H_base=1, alpha=0.0, model=ws["model"], seed=ws["seed"],
+                       grad_sigma=ws.get("grad_sigma", 0.0), data_sigma=ws.get("data_sigma", 0.0),
+                       B_loc=ws.get("B_loc", 0), d_in=ws.get("d_in", 0), d_hidden=ws.get("d_hidden", 0),
+                       d_out=ws.get("d_out", 0), n_blocks=ws.get("n_blocks", 0), n_heads=ws.get("n_heads", 0),
+                       seq_len=ws.get("seq_len", 0), model_const=const, theta0=th0, n_threads=n_threads)
+        steps = min(steps, ws["T"])
         t0 = time.perf_counter()
         r.step(steps)                 # H = 1: every step also averages, like the GPU's worst case
-        return time.perf_counter() - t0
+        return time.perf_counter() - t0, steps
 
-    t1 = run(2, threads)
-    # about 20 s of CPU work in total: wall time per step times the threads it keeps busy
-    steps = int(max(2, min(200, cpu_seconds_target / max(t1 / 2 * threads, 1e-3))))
-    dt = run(steps, threads)
-    steps1 = max(2, steps // 8)       # and a few seconds on one core
-    dt1 = run(steps1, 1)
-    return {"value": w["K"] * P * steps / dt, "unit": "replica-param updates/s", "cores": threads,
-            "kind": "oracle",
-            "sample": "K=%d, P=%d (of %d), %d iterations of noise gradient + AdamW + averaging "
-                      "every step, double precision, %.1f s wall" % (w["K"], P, w["P"], steps, dt),
-            # the same 28 + 8 algorithmic bytes per replica-parameter as the GPU's two-kernel step with
-            # averaging (the oracle's arrays are double precision: what it really moves is about twice that)
-            "GBs_at_gpu_byte_count": w["K"] * P * steps / dt * (BYTES_PER_UPDATE[w["opt"]] + BYTES_PER_AVERAGE) / 1e9,
-            "value_one_core": w["K"] * P * steps1 / dt1,
-            "sample_one_core": "the same, %d iterations on one thread, %.1f s wall" % (steps1, dt1)}
+    t1, _ = run(1, threads)
+    # about cpu_seconds_target of CPU work in total: wall time per step times the threads it keeps busy
+    steps = int(max(1, min(200, cpu_seconds_target / max(t1 * threads, 1e-3))))
+    dt, steps = run(steps, threads)
+    # and a few seconds on one core (the block models: one worker only, their gradient takes seconds)
+    K1 = 1 if w["model"] == "resmlp" else K
+    dt1, steps1 = run(max(1, steps // 8), 1, K1)
+    out = {"value": K * P * steps / dt, "unit": "replica-param updates/s", "cores": threads, "kind": "oracle",
+           "sample": "%s + averaging every step, double precision, %d iteration%s, %.1f s wall"
+                     % (what, steps, "s" if steps > 1 else "", dt),
+           "value_one_core": K1 * P * steps1 / dt1,
+           "sample_one_core": "the same%s, %d iteration%s on one thread, %.1f s wall"
+                              % ("" if K1 == K else " with one worker", steps1, "s" if steps1 > 1 else "", dt1)}
+    if w["model"] == "noise":
+        # the same 28 + 8 algorithmic bytes per replica-parameter as the GPU's two-kernel step with
+        # averaging (the oracle's arrays are double precision: what it really moves is about twice that)
+        out["GBs_at_gpu_byte_count"] = out["value"] * (BYTES_PER_UPDATE[w["opt"]] + BYTES_PER_AVERAGE) / 1e9
+    if scale_to_full != 1.0:
+        out["value_extrapolated_to_full_shape"] = out["value"] * scale_to_full
+        out["extrapolation"] = "linear in blocks x tokens: measured value x %d / %d" % (197, w["B_loc"])
+    return out
 
 
-def run_workload(name, steps, warmup, kernel_timing=True, fuse_gradient=True, **overrides):
-    """Runs `steps` iterations of one workload (after `warmup` untimed ones and a restart at
-    t = 0) and returns the fields of the JSON line that depend on the workload.  The
+# ------------------------------------------------------------------------------------------------
+# the GPU runs
+# ------------------------------------------------------------------------------------------------
+def schedule_of_full_run(w):
+    """Averaging points and periods of one complete run of the workload's schedule, taken from the
+    device-side scheduler on a tiny optimizer-only problem: the schedule depends on the learning
+    rates, alpha and H_base only (Eq. (2)), not on P or the model."""
+    import torch
+    import numpy as np
+    import paper_2310_14423_amd as qsr
+    keep = ("opt", "T", "T_warm", "lr", "eta_max", "eta_min", "milestones", "factor", "H_base", "alpha", "mu", "lam",
+            "beta1", "beta2", "eps", "power", "t_local_start", "t_swap_start", "seed")
+    w2 = {k: w[k] for k in keep if k in w}
+    w2.update(model="noise", K=2, P=8, grad_sigma=1e-3)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        ctx = qsr.Context(w2, theta0=np.zeros(8, np.float32))
+        ctx.run(w2["T"])
+        t_log, H_log = ctx.read_sync_log()
+        ctx.close()
+    return [int(x) for x in t_log], [int(x) for x in H_log]
+
+
+def run_workload(name, steps, warmup, kernel_timing=True, fuse_gradient=True, placement="plain", **overrides):
+    """Runs `steps` iterations of one workload (after `warmup` untimed ones) and returns the fields
+    of the JSON line that depend on the workload.  steps = None: one complete run from t = 0.
+    Fewer steps than a run: the window [t0, t0 + steps) around the first averaging round.  The
     optimizer-only workloads run with the gradient drawn inside the update kernel unless
     fuse_gradient is False (then a fill kernel writes it first, as a model's backward pass would)."""
     import torch
@@ -95,12 +163,22 @@ def run_workload(name, steps, warmup, kernel_timing=True, fuse_gradient=True, **
     if w["model"] == "noise" and fuse_gradient and w["P"] % 4 == 0:
         w["fuse_gradient"] = 2                 # drawn in registers, never written: 24 B per update
     K, P, T = w["K"], w["P"], w["T"]
+    sched_t, sched_H = schedule_of_full_run(w)
     if steps is None:
         steps = T
-    ctx = qsr.Context(w, theta0=workloads.theta0(w), model_const=workloads.model_const(w))
+    t_start = 0
+    if steps < T and sched_t[0] >= steps:
+        t_start = max(0, sched_t[0] - (steps + 1) // 2)
+    ctx = qsr.Context(w, theta0=workloads.theta0(w), model_const=workloads.model_const(w), placement=placement)
+
+    def begin_run():
+        if t_start > 0:
+            ctx.set_state((t_start, 0, t_start, sched_H[0]))
+        else:
+            ctx.restart()
 
     ctx.step(min(warmup, T))
-    ctx.restart()                              # the timed region starts a run at t = 0
+    begin_run()
     ctx.timing(kernel_timing)
     ms = [0.0] * 4
     cnt = [0] * 4
@@ -126,13 +204,13 @@ def run_workload(name, steps, warmup, kernel_timing=True, fuse_gradient=True, **
     t0 = time.perf_counter()
     left = steps
     while left > 0:
-        n = min(left, T)
+        n = min(left, T - t_start)
         ctx.step(n)
         left -= n
         if left > 0 or n == T:                 # a run is complete: collect, start the next one
             collect()
             if left > 0:
-                ctx.restart()
+                begin_run()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     if steps % T != 0:
@@ -201,8 +279,14 @@ def run_workload(name, steps, warmup, kernel_timing=True, fuse_gradient=True, **
         "config": {"workload": name, "K": K, "P": P, "T": T, "optimizer": w["opt"],
                    "gradient": w["model"] + (" (drawn inside the update kernel, not stored)" if w.get("fuse_gradient") else ""),
                    "H_base": w["H_base"], "alpha": w["alpha"],
-                   "lr": w["lr"], "eta_max": w["eta_max"]},
-        "sync_rounds": rounds,
+                   "lr": w["lr"], "eta_max": w["eta_max"],
+                   "placement": ctx.placement,
+                   "timed_window": [t_start, t_start + steps] if steps < T else [0, T]},
+        "sync_rounds": rounds,                       # averaging rounds inside the timed window
+        "sync_rounds_per_run": len(sched_t),         # of one complete run of T iterations
+        "sync_schedule": {"rounds": len(sched_t), "T": T, "communication_volume": len(sched_t) / T,
+                          "H": sched_H if len(sched_H) <= 32 else sched_H[:4] + ["..."] + sched_H[-4:],
+                          "averaging_after_iteration": sched_t if len(sched_t) <= 32 else sched_t[:4] + ["..."] + sched_t[-4:]},
         "hbm_GBs_update": kernels.get("update_GBs"),
         "kernels": kernels,
         "roofline": roofline,
@@ -213,7 +297,7 @@ def run_workload(name, steps, warmup, kernel_timing=True, fuse_gradient=True, **
     if kernel_timing and dt / steps < 1e-3:
         # an iteration this short is launch cost, and the event brackets around its kernels add to
         # it: the same run once more without them, through qsr_run on a stream of its own (the
-        # launches of 8 iterations replayed from a captured HIP graph)
+        # launches of several iterations replayed from a captured HIP graph)
         out["ms_per_step_no_event_brackets"] = replayed_run_ms(w)
     return out, w
 
@@ -236,7 +320,7 @@ def replayed_run_ms(w):
     return dt * 1e3 / T if rounds > 0 else None
 
 
-def fused_sync_probe(name):
+def fused_sync_probe(name, **overrides):
     """The optional fused form (update + averaging of a round's last step in one pass) on the same
     buffers: a short run with a constant period of 4, so that every fourth step synchronizes.
     Bytes per replica-parameter on such a step: AdamW 16 read + 8 (m, v) + 4 (mean) written = 28
@@ -244,7 +328,7 @@ def fused_sync_probe(name):
     import torch
     import workloads
     import paper_2310_14423_amd as qsr
-    w = workloads.get(name, fuse_sync=True, power=0, H_base=4, alpha=0.0)
+    w = workloads.get(name, fuse_sync=True, power=0, H_base=4, alpha=0.0, **overrides)
     K, P = w["K"], w["P"]
     ctx = qsr.Context(w, theta0=workloads.theta0(w), model_const=workloads.model_const(w))
     ctx.step(8)
@@ -264,14 +348,14 @@ def fused_sync_probe(name):
             "GBs": nbytes / (f_ms * 1e-3) / 1e9, "skipped_launch_ms_avg": ms[3] / cnt[3] if cnt[3] else None}
 
 
-def clip_probe(name):
+def clip_probe(name, **overrides):
     """The optional gradient clipping on the same buffers: the norm pass reads the gradients once
     more (4 B per replica-parameter), the factors are applied inside the update kernel; the update
     bracket then covers 28 + 4 = 32 B (AdamW) per replica-parameter."""
     import torch
     import workloads
     import paper_2310_14423_amd as qsr
-    w = workloads.get(name, clip_norm=1.0)
+    w = workloads.get(name, clip_norm=1.0, **overrides)
     K, P = w["K"], w["P"]
     ctx = qsr.Context(w, theta0=workloads.theta0(w), model_const=workloads.model_const(w))
     ctx.step(5)
@@ -292,15 +376,26 @@ def clip_probe(name):
 # short runs of the other workloads, reported next to the headline one
 OTHER_WORKLOADS = {"lsq": dict(steps=None, warmup=5), "mlp": dict(steps=None, warmup=5),
                    "resmlp": dict(steps=20, warmup=5), "vit": dict(steps=20, warmup=5),
-                   "flat350m": dict(steps=100, warmup=5)}
+                   "flat60m": dict(steps=400, warmup=5),
+                   "flat350m": dict(steps=40, warmup=5)}
+PER_WORKLOAD_KEYS = ("value", "steps", "ms_per_step", "ms_per_step_no_event_brackets", "dtype", "sync_rounds",
+                     "sync_rounds_per_run", "sync_schedule", "hbm_GBs_update", "kernels", "roofline")
+
+
+def flat350m_overrides(torch):
+    """The largest workload fills 179 of 288 GB: if another process holds part of the HBM, the
+    largest number of workers that fits is run, and named as such."""
+    free, _ = torch.cuda.mem_get_info()
+    need = lambda K: 4 * K * 350_000_000 * 4 + (6 << 30)
+    return [{} if K == 32 else {"K": K} for K in (32, 24, 16) if free >= need(K)]
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="flat60m", choices=["flat60m", "flat350m", "lsq", "mlp", "resmlp", "vit"])
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="flat350m", choices=["flat60m", "flat350m", "lsq", "mlp", "resmlp", "vit"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fuse-gradient", action="store_true",
                     help="optimizer-only workloads: fill the gradient buffer with a kernel of its own "
@@ -320,45 +415,66 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
 
+    head_over = {}
+    if args.workload == "flat350m":
+        tries = flat350m_overrides(torch)
+        if not tries:
+            print("bench.py: not enough free HBM for flat350m even with 16 workers", file=sys.stderr)
+            sys.exit(1)
+        head_over = tries[0]
     res, w = run_workload(args.workload, args.steps, args.warmup, not args.no_kernel_timing,
-                          not args.no_fuse_gradient)
+                          not args.no_fuse_gradient, **head_over)
     out = {"metric": "replica-param updates/s", "value": res["value"], "unit": "updates/s",
            "n_gpus": 1, "steps": res["steps"], "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": res["dtype"], "data": "synthetic", "config": res["config"],
-           "sync_rounds": res["sync_rounds"], "hbm_GBs_update": res["hbm_GBs_update"],
+           "sync_rounds": res["sync_rounds"], "sync_rounds_per_run": res["sync_rounds_per_run"],
+           "sync_schedule": res["sync_schedule"], "hbm_GBs_update": res["hbm_GBs_update"],
            "kernels": res["kernels"], "roofline": res["roofline"]}
+    if head_over:
+        out["config"]["reduced_to"] = head_over
     if "ms_per_step_no_event_brackets" in res:
         out["ms_per_step_no_event_brackets"] = res["ms_per_step_no_event_brackets"]
+    out["cpu_baseline"] = None if args.no_cpu_baseline else cpu_baseline(w)
     if not args.headline_only:
         per = {}
         for name, kw in OTHER_WORKLOADS.items():
             if name == args.workload:
                 continue
-            # the largest workload fills 179 of 288 GB: if another process holds part of the HBM,
-            # report the largest number of workers that fits, named as such
-            tries = [{}] + ([{"K": 24}, {"K": 16}] if name == "flat350m" else [])
+            tries = flat350m_overrides(torch) if name == "flat350m" else [{}]
             for over in tries:
                 try:
-                    r, _ = run_workload(name, kw["steps"], kw["warmup"], **over)
-                    per[name] = {k: r[k] for k in ("value", "steps", "ms_per_step", "ms_per_step_no_event_brackets",
-                                                   "dtype", "sync_rounds", "hbm_GBs_update", "kernels", "roofline")
-                                 if k in r}
+                    r, wn = run_workload(name, kw["steps"], kw["warmup"], **over)
+                    per[name] = {k: r[k] for k in PER_WORKLOAD_KEYS if k in r}
+                    per[name]["placement"] = r["config"]["placement"]
+                    per[name]["timed_window"] = r["config"]["timed_window"]
                     if over:
                         per[name]["reduced_to"] = over
+                    if not args.no_cpu_baseline:
+                        per[name]["cpu_baseline"] = cpu_baseline(wn, 10.0)
                     break
                 except Exception as e:
                     per[name] = {"error": "%s: %s" % (type(e).__name__, e)}
                     torch.cuda.empty_cache()
         out["per_workload"] = per
-        if w["model"] in ("noise", "external"):
-            if w.get("fuse_gradient"):
-                # the same workload with the gradient written by a fill kernel first (500 iterations)
-                r, _ = run_workload(args.workload, 500, 5, True, False)
-                out["separate_gradient_fill"] = {k: r[k] for k in ("value", "steps", "ms_per_step", "kernels", "roofline")}
-            out["fused_sync"] = fused_sync_probe(args.workload)
-            out["gradient_clipping"] = clip_probe(args.workload)
-    out["cpu_baseline"] = None if args.no_cpu_baseline else cpu_baseline(w)
+        # the update as it looks behind a real model's backward pass: the gradient written by a
+        # kernel of its own first, 28 B per replica-parameter (at the 60 M x 16 size)
+        flat = "flat60m"
+        r, _ = run_workload(flat, 100, 5, True, False)
+        out["separate_gradient_fill"] = dict({k: r[k] for k in ("value", "steps", "ms_per_step", "kernels", "roofline")},
+                                             workload=flat)
+        # the experiment with the state arrays spread over the HBM's three physical ranges (the
+        # binding's opt-in placement): the same kernels, 20 launches, beside the plain figures above
+        try:
+            r, _ = run_workload(flat, 20, 5, True, True, placement="spread")
+            out["placement_spread"] = {"workload": flat, "placement": r["config"]["placement"],
+                                       "timed_window": r["config"]["timed_window"], "ms_per_step": r["ms_per_step"],
+                                       "kernels": r["kernels"], "roofline": r["roofline"]}
+        except Exception as e:
+            out["placement_spread"] = {"error": "%s: %s" % (type(e).__name__, e)}
+            torch.cuda.empty_cache()
+        out["fused_sync"] = dict(fused_sync_probe(flat) or {}, workload=flat)
+        out["gradient_clipping"] = dict(clip_probe(flat), workload=flat)
     print(json.dumps(out))
 
 

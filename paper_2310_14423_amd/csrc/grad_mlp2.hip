@@ -12,6 +12,7 @@ namespace qsr {
 
 struct Mlp2Ws {
     float *X, *hid, *dhid, *logit;
+    double *logit64;       // the logits before the softmax, in double precision (at most 16 classes)
     int *label;
 };
 
@@ -27,6 +28,7 @@ static Mlp2Ws carve(const ModelDims &d, void *ws, size_t *total)
     w.hid = (float *)(p + off);   off += up256(K * B * d.d_hidden * sizeof(float));
     w.dhid = (float *)(p + off);  off += up256(K * B * d.d_hidden * sizeof(float));
     w.logit = (float *)(p + off); off += up256(K * B * d.d_out * sizeof(float));
+    w.logit64 = (double *)(p + off); off += up256(K * B * d.d_out * sizeof(double));
     w.label = (int *)(p + off);   off += up256(K * B * sizeof(int));
     if (total) *total = off;
     return w;
@@ -88,12 +90,15 @@ __global__ __launch_bounds__(64) void mlp2_sample_kernel(float *__restrict__ X, 
     }
 }
 
-// per sample: logits -> (softmax - onehot)/B in place; per worker: mean cross-entropy and, for at
-// most CMAX classes, the output bias gradient (the column sums of the new logits array), which
-// would otherwise be a launch of its own.  One block per worker, samples strided over its
-// threads (d_out is small).
-template <int CMAX>
-__global__ __launch_bounds__(256) void mlp2_softmax_ce_kernel(float *__restrict__ logit,
+// per sample: logits -> (softmax - onehot)/B; per worker: mean cross-entropy and, for at most
+// CMAX classes, the output bias gradient (the column sums of the new array), which would otherwise
+// be a launch of its own.  One block per worker, samples strided over its threads (d_out is small).
+// ZT = double: the logits come in double precision and the maximum is subtracted in double before
+// anything is rounded to fp32.  At the workload's step size the logits grow into the hundreds within
+// a few iterations, where one fp32 ulp of a logit (6e-5 at 600) is the relative error of the
+// probability computed from it; the difference to the largest logit is small and rounds harmlessly.
+template <int CMAX, typename ZT>
+__global__ __launch_bounds__(256) void mlp2_softmax_ce_kernel(const ZT *zin, float *dlogit,   // may alias
                                                               const int *__restrict__ label,
                                                               float *__restrict__ loss,
                                                               float *__restrict__ gbias, long long sG,
@@ -107,24 +112,26 @@ __global__ __launch_bounds__(256) void mlp2_softmax_ce_kernel(float *__restrict_
 #pragma unroll
     for (int o = 0; o < CMAX; ++o) cs[o] = 0.f;
     for (long long i = threadIdx.x; i < B; i += 256) {
-        float *z = logit + ((long long)k * B + i) * C;
+        const ZT *z = zin + ((long long)k * B + i) * C;
+        float *dz_out = dlogit + ((long long)k * B + i) * C;
         const int y = label[(long long)k * B + i];
-        float mx = z[0];
-        for (int o = 1; o < C; ++o) mx = fmaxf(mx, z[o]);
+        ZT mx = z[0];
+        for (int o = 1; o < C; ++o) mx = z[o] > mx ? z[o] : mx;
         float se = 0.f;
-        for (int o = 0; o < C; ++o) se += expf(z[o] - mx);
-        lsum += (mx + logf(se)) - z[y];
+        for (int o = 0; o < C; ++o) se += expf((float)(z[o] - mx));
+        lsum += logf(se) - (float)(z[y] - mx);
         const float inv = 1.0f / se;
         if (CMAX > 0) {
 #pragma unroll
             for (int o = 0; o < CMAX; ++o)
                 if (o < C) {
-                    const float dz = (expf(z[o] - mx) * inv - (o == y ? 1.f : 0.f)) * invB;
-                    z[o] = dz;
+                    const float dz = (expf((float)(z[o] - mx)) * inv - (o == y ? 1.f : 0.f)) * invB;
+                    dz_out[o] = dz;
                     cs[o] += dz;
                 }
         } else {
-            for (int o = 0; o < C; ++o) z[o] = (expf(z[o] - mx) * inv - (o == y ? 1.f : 0.f)) * invB;
+            // also in place (ZT = float, dlogit = zin): an entry is read before it is overwritten
+            for (int o = 0; o < C; ++o) dz_out[o] = (expf((float)(z[o] - mx)) * inv - (o == y ? 1.f : 0.f)) * invB;
         }
     }
 #pragma unroll
@@ -169,14 +176,15 @@ __global__ __launch_bounds__(256) void colsum_kernel(const float *__restrict__ A
 }
 
 // C[k][i][0..N) = A[k][i][:] B[k] + bias[k] for an output of at most NMAX columns (the class
-// logits): one wavefront per row i, lanes strided over the contraction index, butterfly sum over
-// the lanes (a fixed order).  The 64x64-tile kernel would run this shape on M/64 workgroups per
-// worker with Kd/16 dependent steps each.
+// logits), products and sums in double precision, result stored in double (see the loss kernel):
+// one wavefront per row i, lanes strided over the contraction index, butterfly sum over the lanes
+// (a fixed order).  The 64x64-tile kernel would run this shape on M/64 workgroups per worker with
+// Kd/16 dependent steps each.
 template <int NMAX>
 __global__ __launch_bounds__(256) void skinny_bias_kernel(const float *__restrict__ A, long long sA,
                                                           const float *__restrict__ Bm, long long sB,
                                                           const float *__restrict__ bias, long long sBias,
-                                                          float *__restrict__ C, long long sC,
+                                                          double *__restrict__ C, long long sC,
                                                           int M, int N, int Kd)
 {
     const int lane = threadIdx.x & 63;
@@ -185,9 +193,9 @@ __global__ __launch_bounds__(256) void skinny_bias_kernel(const float *__restric
     if (row >= M) return;                                   // whole wavefronts leave together
     const float *a = A + k * sA + (long long)row * Kd;
     const float *b = Bm + k * sB;
-    float acc[NMAX];
+    double acc[NMAX];
 #pragma unroll
-    for (int n = 0; n < NMAX; ++n) acc[n] = 0.f;
+    for (int n = 0; n < NMAX; ++n) acc[n] = 0.0;
     // four steps of the contraction are loaded before their products are added (in the same
     // ascending order): a launch of one wavefront per SIMD hides no load latency by itself
     for (int kk0 = lane; kk0 < Kd; kk0 += 256) {
@@ -205,18 +213,18 @@ __global__ __launch_bounds__(256) void skinny_bias_kernel(const float *__restric
         for (int u = 0; u < 4; ++u)
             if (kk0 + 64 * u < Kd) {
 #pragma unroll
-                for (int n = 0; n < NMAX; ++n) acc[n] = fmaf(av[u], bv[u][n], acc[n]);
+                for (int n = 0; n < NMAX; ++n) acc[n] = fma((double)av[u], (double)bv[u][n], acc[n]);
             }
     }
-    float mine = 0.f;
+    double mine = 0.0;
 #pragma unroll
     for (int n = 0; n < NMAX; ++n) {
-        float v = acc[n];
+        double v = acc[n];
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
         if (lane == n) mine = v;
     }
-    if (lane < N) C[k * sC + (long long)row * N + lane] = mine + bias[k * sBias + lane];
+    if (lane < N) C[k * sC + (long long)row * N + lane] = mine + (double)bias[k * sBias + lane];
 }
 
 hipError_t launch_mlp2_grad(const ModelDims &d, const float *theta, float *g, const float *means,
@@ -242,7 +250,7 @@ hipError_t launch_mlp2_grad(const ModelDims &d, const float *theta, float *g, co
     a.B = theta + oW1; a.ldb = dh; a.sB = P;
     a.C = w.hid; a.ldc = dh; a.sC = B * dh;
     a.M = (int)B; a.N = (int)dh; a.Kd = (int)di; a.bias = theta + ob1; a.sBias = P;
-    if ((e = launch_sgemm<false, false, EPI_BIAS_RELU>(a, K, s)) != hipSuccess) return e;
+    if ((e = launch_sgemm<false, false, EPI_BIAS_RELU, true>(a, K, s)) != hipSuccess) return e;   // double accumulation
 
     a = GemmArgs{};
     a.A = w.hid; a.lda = dh; a.sA = B * dh;
@@ -251,13 +259,15 @@ hipError_t launch_mlp2_grad(const ModelDims &d, const float *theta, float *g, co
     a.M = (int)B; a.N = (int)dz; a.Kd = (int)dh; a.bias = theta + ob2; a.sBias = P;
     if (dz <= 16) {
         skinny_bias_kernel<16><<<dim3((unsigned)((B + 3) / 4), (unsigned)K), 256, 0, s>>>(
-            w.hid, B * dh, theta + oW2, P, theta + ob2, P, w.logit, B * dz, (int)B, (int)dz, (int)dh);
+            w.hid, B * dh, theta + oW2, P, theta + ob2, P, w.logit64, B * dz, (int)B, (int)dz, (int)dh);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     } else if ((e = launch_sgemm<false, false, EPI_BIAS>(a, K, s)) != hipSuccess) return e;
 
     const bool bias_grad_in_loss = dz <= 16;
-    if (bias_grad_in_loss) mlp2_softmax_ce_kernel<16><<<K, 256, 0, s>>>(w.logit, w.label, loss, g + ob2, P, B, (int)dz);
-    else mlp2_softmax_ce_kernel<0><<<K, 256, 0, s>>>(w.logit, w.label, loss, nullptr, 0, B, (int)dz);
+    if (bias_grad_in_loss)
+        mlp2_softmax_ce_kernel<16, double><<<K, 256, 0, s>>>(w.logit64, w.logit, w.label, loss, g + ob2, P, B, (int)dz);
+    else
+        mlp2_softmax_ce_kernel<0, float><<<K, 256, 0, s>>>(w.logit, w.logit, w.label, loss, nullptr, 0, B, (int)dz);
     if ((e = hipGetLastError()) != hipSuccess) return e;
 
     // backward; w.logit now holds d loss / d logits

@@ -6,6 +6,11 @@
 // two halves that two such groups of four wavefronts in one workgroup run side by side (KSPLIT =
 // 2; the halves are added through LDS at the end).  Every global access is bounds-checked, so
 // any M, N, Kd is accepted.  Fixed order: deterministic.
+// F64: the same operands (fp32 in memory and LDS) multiplied and accumulated in double precision on
+// the fp64 matrix cores (v_mfma_f64_16x16x4_f64, four 16x16 blocks per wavefront): products of fp32
+// values are exact in double, so the result is the exact sum rounded once.  Used for the hidden
+// layer's pre-activations, whose rounding errors the output layer and the softmax amplify by two to
+// three orders of magnitude once the logits have grown into the hundreds.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -24,7 +29,9 @@ struct GemmArgs {
     const float *aux;          // EPI_MASK_POS: same layout as C; C = aux > 0 ? acc : 0
 };
 
-template <bool TA, bool TB, int EPI, int KSPLIT>
+typedef double f64x4_t __attribute__((ext_vector_type(4)));
+
+template <bool TA, bool TB, int EPI, int KSPLIT, bool F64 = false>
 __global__ __launch_bounds__(256 * KSPLIT) void sgemm_kernel(GemmArgs a)
 {
     constexpr int TM = 64, TN = 64, TK = 16, PAD = 32;   // rows k and k+1 of a slab 32 banks apart
@@ -46,6 +53,9 @@ __global__ __launch_bounds__(256 * KSPLIT) void sgemm_kernel(GemmArgs a)
     f32x16_t acc;
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+    f64x4_t dacc[2][2];                              // F64: 16x16 block (bi, bj) of the wavefront's 32x32
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { dacc[0][0][e] = 0.0; dacc[0][1][e] = 0.0; dacc[1][0][e] = 0.0; dacc[1][1][e] = 0.0; }
 
     // Global loads run PF slabs ahead of the multiplication, in registers: these problems have few
     // workgroups per compute unit (the batch is 128 rows), so a slab's load latency is not hidden
@@ -102,18 +112,64 @@ __global__ __launch_bounds__(256 * KSPLIT) void sgemm_kernel(GemmArgs a)
                 sstore(ra[u], rb[u]);
                 if (sl + PF < nslab) gload(kbase + (sl + PF) * TK, ra[u], rb[u]);
                 __syncthreads();
-                // lane l supplies A[row l%32][k l/32] and B[k l/32][column l%32] of the instruction
+                if constexpr (F64) {
+                    // lane l supplies A[row l%16][k l/16] and B[k l/16][column l%16] of the instruction
 #pragma unroll
-                for (int kk = 0; kk < TK; kk += 2) {
-                    const float av = As[kk + (lane >> 5)][wm * 32 + (lane & 31)];
-                    const float bv = Bs[kk + (lane >> 5)][wn * 32 + (lane & 31)];
-                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc, 0, 0, 0);
+                    for (int kk = 0; kk < TK; kk += 4) {
+                        const int kr = kk + (lane >> 4), c = lane & 15;
+                        const double a0 = (double)As[kr][wm * 32 + c], a1 = (double)As[kr][wm * 32 + 16 + c];
+                        const double b0 = (double)Bs[kr][wn * 32 + c], b1 = (double)Bs[kr][wn * 32 + 16 + c];
+                        dacc[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, dacc[0][0], 0, 0, 0);
+                        dacc[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, dacc[0][1], 0, 0, 0);
+                        dacc[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, dacc[1][0], 0, 0, 0);
+                        dacc[1][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, dacc[1][1], 0, 0, 0);
+                    }
+                } else {
+                    // lane l supplies A[row l%32][k l/32] and B[k l/32][column l%32] of the instruction
+#pragma unroll
+                    for (int kk = 0; kk < TK; kk += 2) {
+                        const float av = As[kk + (lane >> 5)][wm * 32 + (lane & 31)];
+                        const float bv = Bs[kk + (lane >> 5)][wn * 32 + (lane & 31)];
+                        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc, 0, 0, 0);
+                    }
                 }
                 __syncthreads();
             }
         }
     }
 
+    float *C = a.C + bz * a.sC;
+    if constexpr (F64) {
+        if constexpr (KSPLIT > 1) {   // the other groups' partial sums, added in group order
+            __shared__ double dpart[KSPLIT - 1][4][16][64];
+            if (grp > 0) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) dpart[grp - 1][tid >> 6][i][lane] = dacc[i >> 3][(i >> 2) & 1][i & 3];
+            }
+            __syncthreads();
+            if (grp > 0) return;
+#pragma unroll
+            for (int g = 0; g < KSPLIT - 1; ++g)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) dacc[i >> 3][(i >> 2) & 1][i & 3] += dpart[g][tid >> 6][i][lane];
+        }
+        // accumulator element e of lane l is C[4*e + l/16][l%16] of its 16x16 block
+#pragma unroll
+        for (int bi = 0; bi < 2; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < 2; ++bj)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int gm = m0 + wm * 32 + bi * 16 + 4 * e + (lane >> 4);
+                    const int gn = n0 + wn * 32 + bj * 16 + (lane & 15);
+                    if (gm >= a.M || gn >= a.N) continue;
+                    double v = dacc[bi][bj][e];
+                    if (EPI == EPI_BIAS_RELU || EPI == EPI_BIAS) v += (double)a.bias[bz * a.sBias + gn];
+                    if (EPI == EPI_BIAS_RELU) v = v > 0.0 ? v : 0.0;
+                    if (EPI == EPI_MASK_POS) v = a.aux[bz * a.sC + (long long)gm * a.ldc + gn] > 0.f ? v : 0.0;
+                    C[(long long)gm * a.ldc + gn] = (float)v;
+                }
+    } else {
     if constexpr (KSPLIT > 1) {       // the other groups' partial sums, added in group order
         __shared__ float part[KSPLIT - 1][4][16][64];
         if (grp > 0) {
@@ -129,7 +185,6 @@ __global__ __launch_bounds__(256 * KSPLIT) void sgemm_kernel(GemmArgs a)
     }
 
     // accumulator element i of lane l is C[(i/4)*8 + (l/32)*4 + i%4][l%32] of the wavefront's block
-    float *C = a.C + bz * a.sC;
     const int gn = n0 + wn * 32 + (lane & 31);
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
@@ -141,14 +196,15 @@ __global__ __launch_bounds__(256 * KSPLIT) void sgemm_kernel(GemmArgs a)
         if (EPI == EPI_MASK_POS) v = a.aux[bz * a.sC + (long long)gm * a.ldc + gn] > 0.f ? v : 0.f;
         C[(long long)gm * a.ldc + gn] = v;
     }
+    }
 }
 
-template <bool TA, bool TB, int EPI>
+template <bool TA, bool TB, int EPI, bool F64 = false>
 inline hipError_t launch_sgemm(const GemmArgs &a, int batch, hipStream_t s)
 {
     dim3 grid((unsigned)((a.N + 63) / 64), (unsigned)((a.M + 63) / 64), (unsigned)batch);
-    if (a.Kd >= 256) sgemm_kernel<TA, TB, EPI, 2><<<grid, 512, 0, s>>>(a);
-    else sgemm_kernel<TA, TB, EPI, 1><<<grid, 256, 0, s>>>(a);
+    if (a.Kd >= 256) sgemm_kernel<TA, TB, EPI, 2, F64><<<grid, 512, 0, s>>>(a);
+    else sgemm_kernel<TA, TB, EPI, 1, F64><<<grid, 256, 0, s>>>(a);
     return hipGetLastError();
 }
 

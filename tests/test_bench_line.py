@@ -21,6 +21,8 @@ def test_bench_prints_one_json_line_with_roofline():
                 "scaling", "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
         assert key in d, key
     assert d["n_gpus"] == 1 and d["steps"] == 256 and d["config"]["workload"] == "lsq" and d["sync_rounds"] == 28
+    assert d["sync_rounds_per_run"] == 28 and d["sync_schedule"]["averaging_after_iteration"][-1] == 256
+    assert d["config"]["placement"] == "plain" and d["config"]["timed_window"] == [0, 256]
     assert d["value"] == pytest.approx(4 * 1024 * 256 / (d["ms_per_step"] * 256 * 1e-3), rel=1e-6)
     r = d["roofline"]
     for key in ("bound", "achieved", "peak", "unit", "frac", "traffic", "avg_ms", "median_ms", "min_ms"):

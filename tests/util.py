@@ -70,3 +70,13 @@ def assert_params_close(gpu, orc, rtol=RTOL_F32, what="", tail=None, rms=None):
         frac, factor = tail
         assert ratio.max() <= factor and np.count_nonzero(ratio > 1.0) <= np.ceil(frac * ratio.size), msg
     return float(np.max(err / np.maximum(bound, 1e-300)))
+
+
+def rms_error_ratio(gpu, orc, rms=None):
+    """rms(gpu - oracle) / rms(oracle) of one group (rms, if given, replaces rms(oracle))."""
+    gpu = np.asarray(gpu, dtype=np.float64)
+    orc = np.asarray(orc, dtype=np.float64)
+    if rms is None:
+        rms = np.sqrt(np.mean(orc * orc))
+    err = gpu - orc
+    return float(np.sqrt(np.mean(err * err)) / max(rms, 1e-300))
