@@ -13,7 +13,10 @@
  *
  * The scheduler state (t, s, h, H), the learning-rate table and the log of averaging
  * points live in device memory; the two calls above only enqueue kernels on the caller's
- * stream and never synchronise.  All `float*` / `void*` buffer arguments are DEVICE
+ * stream and never synchronise.  The host keeps a mirror of the four integers, advanced with the
+ * same arithmetic from the same table, which only decides whether an averaging kernel is enqueued
+ * for an iteration; the device takes every decision again, logs the rounds, and any disagreement
+ * between the two is reported as QSR_EMIRROR by the calls that read the state.  All `float*` / `void*` buffer arguments are DEVICE
  * pointers unless marked (host); they stay owned by the caller, who must keep them alive
  * and untouched by other streams until qsr_destroy.  The library allocates only its own
  * small scheduler tables.  Every function returns QSR_OK (0) or a negative QSR_E* code;
@@ -38,7 +41,9 @@ enum {
     QSR_ESTATE = -2,   /* call out of protocol (e.g. a local step after iteration T)    */
     QSR_EHIP = -3,     /* a HIP runtime call failed; qsr_last_hip_error() has its code  */
     QSR_ENOMEM = -4,   /* workspace too small / allocation failed                       */
-    QSR_ENOGPU = -5    /* no usable gfx950 device                                       */
+    QSR_ENOGPU = -5,   /* no usable gfx950 device                                       */
+    QSR_EMIRROR = -6   /* the host's mirror of the schedule and the device scheduler took
+                          different decisions (a defect: results after it are not Alg. 2's) */
 };
 
 enum { QSR_OPT_SGDM = 0, QSR_OPT_ADAMW = 1 };
@@ -132,6 +137,15 @@ int qsr_validate(const qsr_config *cfg, const char **why);
  * bf16 weight copies).  0 for the EXTERNAL and NOISE models.  QSR_EINVAL on a bad config. */
 int qsr_workspace_bytes(const qsr_config *cfg, size_t *bytes);
 
+/* The whole schedule of a configuration, computed on the host alone (no GPU): Eq. (2) with the
+ * truncation and warm-up rules of Sec. 2 (and the variants `power`, `t_local_start`,
+ * `t_swap_start` select) on the configuration's learning-rate table.  t_out[i] = iteration count
+ * after which averaging i runs, H_out[i] = that round's period; writes min(*n, cap) entries, *n =
+ * number of rounds (communication volume relative to Parallel OPT = *n / T, App. F).  It is the
+ * routine the context's mirror uses; the device-side scheduler, which runs must match, is a
+ * separate implementation. */
+int qsr_host_schedule(const qsr_config *cfg, int64_t *t_out, int64_t *H_out, int64_t cap, int64_t *n);
+
 /* Creates a context.  Alg. 2's initialisation: copies theta0 [P] into each of the K rows
  * of `params`, zeroes the optimizer state, sets t = s = h = 0 and computes H^(0).
  *   params, grads, state0 : [K][P] float, 16-byte aligned; state1 likewise for AdamW
@@ -177,6 +191,11 @@ int qsr_get_H(qsr_ctx *ctx, int64_t *H, int64_t *round, int64_t *t);
  * so far.  t_out / H_out may be NULL. */
 int qsr_read_sync_log(qsr_ctx *ctx, int64_t *t_out, int64_t *H_out, int64_t cap, int64_t *n);
 
+/* The rounds the host's mirror of the schedule has counted since qsr_init / qsr_restart (after
+ * qsr_set_state: entries of earlier rounds read as 0), in the format of qsr_read_sync_log, which it
+ * must equal.  Does not synchronise. */
+int qsr_read_host_schedule(qsr_ctx *ctx, int64_t *t_out, int64_t *H_out, int64_t cap, int64_t *n);
+
 /* (host) copy of the learning-rate table eta_0..eta_{T-1} the context uses. */
 int qsr_eta_table(qsr_ctx *ctx, double *eta_out, int64_t cap);
 
@@ -200,10 +219,11 @@ int qsr_restart(qsr_ctx *ctx);
  * gradient stage, update kernel and averaging kernel is bracketed by an event pair;
  * qsr_read_timing synchronises, adds up the pairs recorded since the last read and recycles
  * them.  ms[i] / count[i]: 0 = gradient stage, 1 = update kernel, 2 = averaging launches that
- * averaged, 3 = averaging launches that the device-side decision skipped.  With fuse_sync, 2
- * and 3 are the fused update-and-average launches that acted / were skipped, and 1 also holds
- * the plain update launches skipped on those steps.  Read before qsr_restart: the split of 2
- * and 3 uses the log of the current run. */
+ * averaged, 3 = averaging launches that the device-side decision skipped (none when the
+ * iterations are enqueued one by one: an averaging kernel is then launched only where a round
+ * ends).  With fuse_sync, 2 holds the fused update-and-average launches and 1 the plain updates
+ * of the other steps.  Read before qsr_restart: the split of 2 and 3 uses the log of the
+ * current run. */
 int qsr_timing(qsr_ctx *ctx, int enable);
 int qsr_read_timing(qsr_ctx *ctx, double ms[4], int64_t count[4]);
 /* The same read with the shortest and the median bracket of each kind as well (0 where count is 0);

@@ -9,8 +9,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = os.path.join(_HERE, "libqsr.so")
 _lib = None
 
-EXPORTS = ["qsr_validate", "qsr_workspace_bytes", "qsr_init", "qsr_local_step", "qsr_maybe_sync",
-           "qsr_run", "qsr_get_H", "qsr_get_state", "qsr_set_state", "qsr_read_sync_log", "qsr_eta_table", "qsr_read_loss", "qsr_restart",
+EXPORTS = ["qsr_validate", "qsr_workspace_bytes", "qsr_host_schedule", "qsr_init", "qsr_local_step", "qsr_maybe_sync",
+           "qsr_run", "qsr_get_H", "qsr_get_state", "qsr_set_state", "qsr_read_sync_log", "qsr_read_host_schedule", "qsr_eta_table", "qsr_read_loss", "qsr_restart",
            "qsr_timing", "qsr_read_timing", "qsr_read_timing_stats", "qsr_destroy", "qsr_average_rows", "qsr_strerror",
            "qsr_last_hip_error"]
 
@@ -115,6 +115,16 @@ def workspace_bytes(cfg):
     n = C.c_size_t(0)
     _check(lib().qsr_workspace_bytes(C.byref(cfg), C.byref(n)), "qsr_workspace_bytes")
     return n.value
+
+
+def host_schedule(cfg):
+    """(averaging points, periods) of a whole run, from the library's host-side schedule routine."""
+    n = C.c_int64()
+    _check(lib().qsr_host_schedule(C.byref(cfg), None, None, C.c_int64(0), C.byref(n)), "qsr_host_schedule")
+    t = np.zeros(max(n.value, 1), dtype=np.int64); H = np.zeros_like(t)
+    _check(lib().qsr_host_schedule(C.byref(cfg), t.ctypes.data_as(C.c_void_p), H.ctypes.data_as(C.c_void_p),
+                                   C.c_int64(n.value), C.byref(n)), "qsr_host_schedule")
+    return t[:n.value], H[:n.value]
 
 
 def average_rows(buf, stream=None):
@@ -271,6 +281,16 @@ class Context:
         _check(lib().qsr_read_sync_log(self._ctx, t.ctypes.data_as(C.c_void_p),
                                        H.ctypes.data_as(C.c_void_p), C.c_int64(n.value), C.byref(n)),
                "qsr_read_sync_log")
+        return t[:n.value], H[:n.value]
+
+    def read_host_schedule(self):
+        """The rounds counted by the host's mirror of the schedule, as read_sync_log returns them."""
+        n = C.c_int64()
+        _check(lib().qsr_read_host_schedule(self._ctx, None, None, C.c_int64(0), C.byref(n)), "qsr_read_host_schedule")
+        t = np.zeros(max(n.value, 1), dtype=np.int64); H = np.zeros_like(t)
+        _check(lib().qsr_read_host_schedule(self._ctx, t.ctypes.data_as(C.c_void_p),
+                                            H.ctypes.data_as(C.c_void_p), C.c_int64(n.value), C.byref(n)),
+               "qsr_read_host_schedule")
         return t[:n.value], H[:n.value]
 
     def eta_table(self):

@@ -1,12 +1,29 @@
 // average.hip -- replica averaging: theta_k <- (1/K) sum_k theta_k for every worker k (the
 // All-Reduce line of Alg. 2, arXiv 2310.14423), as a reduction over the K axis of the [K][P]
-// buffer on one GPU.  HBM-bound: 4 B read + 4 B written per replica-parameter.  Each lane owns
-// four consecutive parameters and walks the K rows with 128-bit loads, KU rows in flight at a
-// time; a wavefront therefore reads 1 KiB contiguous from each row.  The sum runs over k in
-// ascending order in fp32 with an error-free transformation of every addition (the rounding
-// error of each partial sum is carried in a second accumulator), so the mean is accurate to
-// about one rounding whatever K is, does not depend on the launch shape, all K rows receive the
-// same bits, and averaging K identical rows returns that row when K is a power of two.
+// buffer on one GPU.  HBM-bound: 4 B read + 4 B written per replica-parameter.
+//
+// K <= 32: a workgroup owns a tile of columns and stages it in LDS as [K][columns]: its wavefronts
+// split the K rows between them (wavefront w copies rows w, w + W, ... with 128-bit loads, 1 or
+// 2 KiB contiguous from each), and after a barrier every lane adds up its columns from LDS and
+// the wavefront writes the mean back to the rows it loaded.  Any K: each lane owns four
+// consecutive parameters and walks the K rows in registers, 16 in flight at a time.
+// Timed on MI355X (HBM3E, 8 TB/s), array inside one allocation:
+//                                  K = 16, P = 60e6   K = 32, P = 60e6   K = 32, P = 350e6
+//   rows in registers, 64 threads      5.72-5.78 TB/s     5.34-5.40          5.25-5.32
+//   LDS tile, 8 wavefronts x 1 KiB     5.97               5.55               5.51
+//   LDS tile, 2 wavefronts x 2 KiB     5.69               5.77               5.59
+//   K split over the lanes of a
+//   wavefront, partial sums combined
+//   with shuffles                      5.05               4.89               5.12
+// (a plain copy kernel reaches 5.77 TB/s on this chip).  The LDS tile wins because a wavefront
+// touches fewer rows with longer runs; the shuffle variant loses because a wavefront then reads
+// only 256 B from each row.
+//
+// In every variant the sum runs over k in ascending order in fp32 with an error-free
+// transformation of every addition (the rounding error of each partial sum is carried in a
+// second accumulator), so the mean is accurate to about one rounding whatever K is, does not
+// depend on the launch shape, all K rows receive the same bits, and averaging K identical rows
+// returns that row when K is a power of two.
 #include "opt_elem.h"
 #include "qsr_internal.h"
 
@@ -15,40 +32,63 @@ namespace qsr {
 constexpr int AVG_THREADS = 64;
 constexpr int AVG_KU = 16;
 
-// K <= KMAX: all K row loads of a column are issued before the first addition (fully unrolled,
-// predicated on k < K), then K stores.  From a sweep on MI355X (K = 16 and 32, P = 60e6):
-// one-wavefront workgroups making one trip each gave 5.7 TB/s (K = 16) and 5.5 TB/s (K = 32),
-// 8-20 % above 256-thread blocks in a capped grid and above the chunked variant below.
-// THREADS: 64 for the stand-alone entry point (fastest); the predicated in-run launch, which is
-// skipped on the device in all but a handful of iterations, uses 256 so that a skipped launch
-// has fewer workgroups to retire (0.013 ms instead of 0.05 ms at P = 60e6 with one trip each;
-// the launcher caps the grid further) at the price of a few per cent on the launches that do average.
-template <int KMAX, int THREADS>
-__global__ __launch_bounds__(THREADS) void average_rows_full_kernel(
+// LDS-staged tile: W wavefronts, RUN x 64 float4 columns (RUN KiB contiguous per row and wavefront)
+template <int KMAX, int W, int RUN>
+__global__ __launch_bounds__(64 * W) void average_rows_tile_kernel(
     float *__restrict__ buf, int K, long long P4, const DevState *__restrict__ st)
 {
-    if (st != nullptr && st->do_sync == 0) return;
-    const float fK = (float)K;
-    const long long stride = (long long)gridDim.x * THREADS;
-    for (long long i = (long long)blockIdx.x * THREADS + threadIdx.x; i < P4; i += stride) {
-        float4 *col = (float4 *)buf + i;
-        float4 r[KMAX];
+    extern __shared__ float4 avg_tile[];            // [K][RUN * 64]
+    if (st != nullptr && st->h + 1 != st->H) return;   // not the step that completes a round
+    constexpr int TC = RUN * 64;
+    constexpr int RPW = (KMAX + W - 1) / W;          // rows per wavefront
+    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const long long c0 = (long long)blockIdx.x * TC;
+    float4 *base = (float4 *)buf;
+    float4 r[RPW][RUN];
 #pragma unroll
-        for (int u = 0; u < KMAX; ++u)
-            if (u < K) r[u] = ld_nt4(col + (long long)u * P4);
+    for (int j = 0; j < RPW; ++j) {
+        const int k = w + j * W;
+        if (k < K) {
+#pragma unroll
+            for (int u = 0; u < RUN; ++u) {
+                const long long c = c0 + u * 64 + lane;
+                if (c < P4) r[j][u] = ld_nt4(base + (long long)k * P4 + c);
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < RPW; ++j) {
+        const int k = w + j * W;
+        if (k < K) {
+#pragma unroll
+            for (int u = 0; u < RUN; ++u) avg_tile[k * TC + u * 64 + lane] = r[j][u];
+        }
+    }
+    __syncthreads();
+    float4 mean[RUN];
+#pragma unroll
+    for (int u = 0; u < RUN; ++u) {
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
         float4 cmp = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int k = 0; k < K; ++k) {
+            const float4 v = avg_tile[k * TC + u * 64 + lane];
+            add_comp(acc.x, cmp.x, v.x); add_comp(acc.y, cmp.y, v.y);
+            add_comp(acc.z, cmp.z, v.z); add_comp(acc.w, cmp.w, v.w);
+        }
+        const float fK = (float)K;
+        mean[u] = make_float4((acc.x + cmp.x) / fK, (acc.y + cmp.y) / fK,
+                              (acc.z + cmp.z) / fK, (acc.w + cmp.w) / fK);
+    }
 #pragma unroll
-        for (int u = 0; u < KMAX; ++u)
-            if (u < K) {
-                add_comp(acc.x, cmp.x, r[u].x); add_comp(acc.y, cmp.y, r[u].y);
-                add_comp(acc.z, cmp.z, r[u].z); add_comp(acc.w, cmp.w, r[u].w);
+    for (int j = 0; j < RPW; ++j) {
+        const int k = w + j * W;
+        if (k < K) {
+#pragma unroll
+            for (int u = 0; u < RUN; ++u) {
+                const long long c = c0 + u * 64 + lane;
+                if (c < P4) st_nt4(base + (long long)k * P4 + c, mean[u]);
             }
-        float4 mean = make_float4((acc.x + cmp.x) / fK, (acc.y + cmp.y) / fK,
-                                  (acc.z + cmp.z) / fK, (acc.w + cmp.w) / fK);
-#pragma unroll
-        for (int u = 0; u < KMAX; ++u)
-            if (u < K) st_nt4(col + (long long)u * P4, mean);
+        }
     }
 }
 
@@ -56,7 +96,7 @@ __global__ __launch_bounds__(THREADS) void average_rows_full_kernel(
 __global__ __launch_bounds__(AVG_THREADS) void average_rows_vec4_kernel(
     float *__restrict__ buf, int K, long long P4, const DevState *__restrict__ st)
 {
-    if (st != nullptr && st->do_sync == 0) return;
+    if (st != nullptr && st->h + 1 != st->H) return;
     const float fK = (float)K;
     const long long stride = (long long)gridDim.x * AVG_THREADS;
     for (long long i = (long long)blockIdx.x * AVG_THREADS + threadIdx.x; i < P4; i += stride) {
@@ -85,7 +125,7 @@ __global__ __launch_bounds__(AVG_THREADS) void average_rows_vec4_kernel(
 __global__ __launch_bounds__(AVG_THREADS) void average_rows_scalar_kernel(
     float *__restrict__ buf, int K, long long P, const DevState *__restrict__ st)
 {
-    if (st != nullptr && st->do_sync == 0) return;
+    if (st != nullptr && st->h + 1 != st->H) return;
     const float fK = (float)K;
     const long long stride = (long long)gridDim.x * AVG_THREADS;
     for (long long i = (long long)blockIdx.x * AVG_THREADS + threadIdx.x; i < P; i += stride) {
@@ -105,25 +145,31 @@ static int avg_grid(long long items, int threads)
     return (int)blocks;
 }
 
+template <int KMAX, int W, int RUN>
+static hipError_t launch_tile(float *buf, int K, long long P4, const DevState *st, hipStream_t s)
+{
+    const size_t lds = (size_t)K * RUN * 64 * sizeof(float4);
+    static bool raised = false;                       // above the default 64 KiB only for K = 32 x 2 KiB
+    if (lds > 48 * 1024 && !raised) {
+        hipError_t e = hipFuncSetAttribute((const void *)average_rows_tile_kernel<KMAX, W, RUN>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, KMAX * RUN * 64 * (int)sizeof(float4));
+        if (e != hipSuccess) return e;
+        raised = true;
+    }
+    average_rows_tile_kernel<KMAX, W, RUN><<<avg_grid(P4, RUN * 64), 64 * W, lds, s>>>(buf, K, P4, st);
+    return hipGetLastError();
+}
+
+// st != nullptr: the launch acts only on the step that completes a round (h + 1 == H in the device's
+// scheduler state, read before the scheduler advances)
 hipError_t launch_average_rows(float *buf, int K, long long P, const DevState *st, hipStream_t s)
 {
     if ((P & 3) == 0) {
         const long long P4 = P / 4;
-        const int grid = avg_grid(P4, AVG_THREADS);
-        // predicated in-run launches: a capped grid walked with a stride loop.  In a QSR run nearly
-        // all of them are skipped on the device, and retiring 4096 workgroups costs 0.006 ms where
-        // the 58 594 one-trip ones of P = 60e6 cost 0.016 ms; the few launches that do average run
-        // 5 % slower for it
-        const int grid256 = avg_grid(P4, 256) < 4096 ? avg_grid(P4, 256) : 4096;
-        if (K <= 8) {
-            if (st) average_rows_full_kernel<8, 256><<<grid256, 256, 0, s>>>(buf, K, P4, st);
-            else average_rows_full_kernel<8, AVG_THREADS><<<grid, AVG_THREADS, 0, s>>>(buf, K, P4, st);
-        } else if (K <= 32) {
-            if (st) average_rows_full_kernel<32, 256><<<grid256, 256, 0, s>>>(buf, K, P4, st);
-            else average_rows_full_kernel<32, AVG_THREADS><<<grid, AVG_THREADS, 0, s>>>(buf, K, P4, st);
-        } else {
-            average_rows_vec4_kernel<<<grid, AVG_THREADS, 0, s>>>(buf, K, P4, st);
-        }
+        if (P4 > 0x7FFFFFFFll * 64) return hipErrorInvalidValue;
+        if (K <= 16) return launch_tile<16, 8, 1>(buf, K, P4, st, s);
+        if (K <= 32) return launch_tile<32, 2, 2>(buf, K, P4, st, s);
+        average_rows_vec4_kernel<<<avg_grid(P4, AVG_THREADS), AVG_THREADS, 0, s>>>(buf, K, P4, st);
     } else {
         average_rows_scalar_kernel<<<avg_grid(P, AVG_THREADS), AVG_THREADS, 0, s>>>(buf, K, P, st);
     }

@@ -50,6 +50,14 @@ struct qsr_ctx {
     DevState *h_state;       // pinned
     long long t_host;        // local steps enqueued
     bool need_sync_call;     // a local step was enqueued and its maybe_sync not yet
+    // Mirror of the device scheduler's integers (t, s, h, H), advanced on the host with the same
+    // arithmetic from the same learning-rate table.  It decides only which kernels are enqueued (an
+    // averaging launch where a round ends, none elsewhere); the device state stays the truth: the
+    // averaging kernels still test it, the advance kernel compares the two decisions and latches a
+    // flag if they ever differ, and every read of the state reports that flag as QSR_EMIRROR.
+    long long m_t, m_s, m_h, m_H;
+    std::vector<long long> m_log_t, m_log_H;
+    bool capturing;          // launches are being recorded into a graph: device-side decisions only
     SchedParams sp;
     ModelDims dims;
     // timing
@@ -240,6 +248,83 @@ static void build_scalars(const qsr_config *c, const std::vector<double> &eta,
     }
 }
 
+// Eq. (2) on the host, for the mirror: the same operations in the same order as the device
+// scheduler's routine (IEEE double division and multiplications, no fused operations, floor), on
+// the same table, so the two integer sequences are equal.
+static long long host_get_H(const SchedParams &sp, const double *eta, long long t)
+{
+#pragma STDC FP_CONTRACT OFF
+    const long long rem = sp.T - t;
+    if (rem <= 0) return 0;
+    if (sp.t_swap_start > 0 && t >= sp.t_swap_start) return rem;
+    if (t < sp.t_local_start) return 1;
+    if (sp.power == 0) return sp.H_base < rem ? sp.H_base : rem;
+    const long long te = t < sp.T_warm ? sp.T_warm : t;
+    if (te >= sp.T) return rem;
+    const volatile double e = eta[te];
+    if (!(e > 0.0)) return rem;
+    const volatile double q = sp.alpha / e;
+    volatile double v = q;
+    for (int i = 1; i < sp.power; ++i) v = v * q;
+    if (!(v < (double)rem)) return rem;
+    long long H = (long long)std::floor(v);
+    if (H < sp.H_base) H = sp.H_base;
+    if (H > rem) H = rem;
+    return H;
+}
+
+static void mirror_reset(qsr_ctx *c, long long t, long long s, long long h, long long H)
+{
+    c->m_t = t; c->m_s = s; c->m_h = h; c->m_H = H;
+    c->m_log_t.assign((size_t)s, 0);
+    c->m_log_H.assign((size_t)s, 0);
+}
+
+// true if the iteration about to run (or just run, before mirror_advance) completes its round
+static inline bool mirror_sync_now(const qsr_ctx *c) { return c->m_h + 1 == c->m_H; }
+
+static void mirror_advance(qsr_ctx *c)
+{
+    c->m_t += 1; c->m_h += 1;
+    if (c->m_h == c->m_H) {
+        c->m_log_t.push_back(c->m_t);
+        c->m_log_H.push_back(c->m_H);
+        c->m_s += 1; c->m_h = 0;
+        c->m_H = host_get_H(c->sp, c->eta.data(), c->m_t);
+    }
+}
+
+static SchedParams sched_params_of(const qsr_config &cfg)
+{
+    SchedParams sp{};
+    sp.T = cfg.T; sp.T_warm = cfg.T_warm; sp.H_base = cfg.H_base; sp.alpha = cfg.alpha;
+    sp.power = cfg.power; sp.t_local_start = cfg.t_local_start; sp.t_swap_start = cfg.t_swap_start;
+    return sp;
+}
+
+extern "C" int qsr_host_schedule(const qsr_config *cfg, int64_t *t_out, int64_t *H_out, int64_t cap, int64_t *n)
+{
+    if (!n || cap < 0) return QSR_EINVAL;
+    int rc = qsr_validate(cfg, nullptr);
+    if (rc != QSR_OK) return rc;
+    std::vector<double> eta;
+    build_eta(cfg, eta);
+    const SchedParams sp = sched_params_of(*cfg);
+    long long t = 0, rounds = 0;
+    while (t < cfg->T) {
+        const long long H = host_get_H(sp, eta.data(), t);
+        if (H < 1) return QSR_EINVAL;
+        t += H;
+        if (rounds < cap) {
+            if (t_out) t_out[rounds] = t;
+            if (H_out) H_out[rounds] = H;
+        }
+        rounds += 1;
+    }
+    *n = rounds;
+    return QSR_OK;
+}
+
 // ------------------------------------------------------------------------------------------
 // life cycle
 // ------------------------------------------------------------------------------------------
@@ -290,9 +375,7 @@ static int init_impl(qsr_ctx *c, const float *theta0)
     HIP_TRY(hipMemcpyAsync(c->d_scal, sc.data(), T * sizeof(StepScalars), hipMemcpyHostToDevice, c->stream));
     HIP_TRY(hipStreamSynchronize(c->stream));
 
-    c->sp.T = cfg.T; c->sp.T_warm = cfg.T_warm; c->sp.H_base = cfg.H_base; c->sp.alpha = cfg.alpha;
-    c->sp.power = cfg.power; c->sp.t_local_start = cfg.t_local_start;
-    c->sp.t_swap_start = cfg.t_swap_start;
+    c->sp = sched_params_of(cfg);
     c->sp.eta = c->d_eta; c->sp.log_t = c->d_log_t; c->sp.log_H = c->d_log_H;
 
     const long long n = (long long)cfg.K * cfg.P;
@@ -302,6 +385,7 @@ static int init_impl(qsr_ctx *c, const float *theta0)
     HIP_TRY(launch_fill_zero(c->d_loss, cfg.K, c->stream));
     HIP_TRY(launch_sched_init(c->d_state, c->sp, c->stream));
     HIP_TRY(hipStreamSynchronize(c->stream));
+    mirror_reset(c, 0, 0, 0, host_get_H(c->sp, c->eta.data(), 0));
     return QSR_OK;
 }
 
@@ -336,10 +420,13 @@ extern "C" int qsr_init(const qsr_config *cfg, float *params, float *grads, floa
     c->d_state = nullptr; c->d_eta = nullptr; c->d_scal = nullptr; c->d_log_t = nullptr;
     c->d_log_H = nullptr; c->d_loss = nullptr; c->h_state = nullptr;
     c->d_clip_part = nullptr; c->d_clip_coef = nullptr;
-    c->t_host = 0; c->need_sync_call = false; c->timing = false;
+    c->t_host = 0; c->need_sync_call = false; c->timing = false; c->capturing = false;
     c->graph_exec = nullptr;
-    // iterations per captured graph: several where an iteration is a handful of short launches
-    c->graph_iters = cfg->model == QSR_MODEL_RESMLP ? 1 : 8;
+    // Iterations per captured graph: several where an iteration is a handful of short launches.
+    // Large problems are never replayed from a graph: their launch cost does not matter, and
+    // enqueued one by one an averaging kernel is launched only where the mirror says a round ends,
+    // while a graph has to hold a launch in every iteration for the device to skip.
+    c->graph_iters = (cfg->model == QSR_MODEL_RESMLP || (long long)cfg->K * cfg->P >= (1ll << 24)) ? 0 : 8;
     c->dims = make_dims(cfg);
     rc = init_impl(c, theta0);
     c->cfg.milestones = nullptr;
@@ -426,10 +513,14 @@ extern "C" int qsr_local_step(qsr_ctx *c)
         int rc = br.close(c->t_host + 1);
         if (rc != QSR_OK) return rc;
     }
-    {                                                   // OPT for all K workers at once
+    // The step that completes a round (h + 1 == H): known to the host from its mirror; under graph
+    // capture every launch is recorded and the device decides.
+    const bool all = c->capturing;
+    const bool sync_now = mirror_sync_now(c);
+    const bool fused = cfg.fuse_sync != 0;
+    if (!fused || all || !sync_now) {                   // OPT for all K workers at once
         Bracket br(c, 1);
         if (br.rc != QSR_OK) return br.rc;
-        const bool fused = cfg.fuse_sync != 0;
         if (cfg.clip_norm > 0.0)                        // App. C: per-worker factors min(1, c / (||g_k|| + 1e-6))
             HIP_TRY(launch_clip_coef(c->grads, cfg.K, cfg.P, (float)cfg.clip_norm, c->d_clip_part,
                                      c->d_clip_coef, c->d_clip_coef + cfg.K, c->stream));
@@ -453,9 +544,12 @@ extern "C" int qsr_local_step(qsr_ctx *c)
         int rc = br.close(c->t_host);
         if (rc != QSR_OK) return rc;
     }
-    if (cfg.fuse_sync) {                                // the round's last step: OPT and All-Reduce in one pass
-        Bracket br(c, 2);                               // timed like an averaging launch: it ran iff the log says so
+    if (fused && (all || sync_now)) {                   // the round's last step: OPT and All-Reduce in one pass
+        Bracket br(c, 2);                               // timed like an averaging launch
         if (br.rc != QSR_OK) return br.rc;
+        if (cfg.clip_norm > 0.0 && !all)                // (under capture the plain launch above has computed them)
+            HIP_TRY(launch_clip_coef(c->grads, cfg.K, cfg.P, (float)cfg.clip_norm, c->d_clip_part,
+                                     c->d_clip_coef, c->d_clip_coef + cfg.K, c->stream));
         if (cfg.opt == QSR_OPT_SGDM)
             HIP_TRY(launch_update_sgdm_sync(c->params, c->grads, c->state0, cfg.K, cfg.P, c->d_state, c->d_scal,
                                             (float)cfg.momentum, (float)cfg.weight_decay, c->d_clip_coef, c->stream));
@@ -466,7 +560,6 @@ extern "C" int qsr_local_step(qsr_ctx *c)
         int rc = br.close(c->t_host + 1);
         if (rc != QSR_OK) return rc;
     }
-    HIP_TRY(launch_sched_tick(c->d_state, c->stream));
     c->t_host += 1;
     c->need_sync_call = true;
     return QSR_OK;
@@ -476,19 +569,22 @@ extern "C" int qsr_maybe_sync(qsr_ctx *c)
 {
     if (!c) return QSR_EINVAL;
     if (!c->need_sync_call) return QSR_ESTATE;
-    if (!c->cfg.parallel && !c->cfg.fuse_sync) {   // Parallel OPT keeps the workers identical, the fused
-                                                   // form has averaged in qsr_local_step already
+    const bool all = c->capturing;
+    const bool sync_now = mirror_sync_now(c);
+    // Parallel OPT keeps the workers identical, the fused form has averaged in qsr_local_step already
+    if (!c->cfg.parallel && !c->cfg.fuse_sync && (all || sync_now)) {
         Bracket br(c, 2);
         if (br.rc != QSR_OK) return br.rc;
         HIP_TRY(launch_average_rows(c->params, c->cfg.K, c->cfg.P, c->d_state, c->stream));
         int rc = br.close(c->t_host);
         if (rc != QSR_OK) return rc;
-        if (c->cfg.average_state) {          // same device-side decision, taken before it is cleared
+        if (c->cfg.average_state) {          // same device-side decision, taken before the scheduler advances
             HIP_TRY(launch_average_rows(c->state0, c->cfg.K, c->cfg.P, c->d_state, c->stream));
             if (c->state1) HIP_TRY(launch_average_rows(c->state1, c->cfg.K, c->cfg.P, c->d_state, c->stream));
         }
     }
-    HIP_TRY(launch_sched_next_round(c->d_state, c->sp, c->stream));
+    HIP_TRY(launch_sched_advance(c->d_state, c->sp, all ? -1 : (sync_now ? 1 : 0), c->stream));
+    mirror_advance(c);
     c->need_sync_call = false;
     return QSR_OK;
 }
@@ -518,17 +614,23 @@ extern "C" int qsr_run(qsr_ctx *c, int64_t n)
         int rc = run_one_by_one(c, 1);
         if (rc != QSR_OK) return rc;
         n -= 1;
-        const long long t_keep = c->t_host;
+        // recorded, not run: the host's counters and its mirror of the schedule are put back afterwards
+        const long long t_keep = c->t_host, m_keep[4] = {c->m_t, c->m_s, c->m_h, c->m_H};
+        const size_t log_keep = c->m_log_t.size();
         if (hipStreamBeginCapture(c->stream, hipStreamCaptureModeRelaxed) != hipSuccess) {
             (void)hipGetLastError();                  // a stream that cannot be captured: one by one from now on
             c->graph_iters = 0;
             return run_one_by_one(c, n);
         }
-        rc = run_one_by_one(c, per);                  // recorded, not run
+        c->capturing = true;
+        rc = run_one_by_one(c, per);
+        c->capturing = false;
         hipGraph_t g = nullptr;
         hipError_t e = hipStreamEndCapture(c->stream, &g);
         c->t_host = t_keep;
         c->need_sync_call = false;
+        c->m_t = m_keep[0]; c->m_s = m_keep[1]; c->m_h = m_keep[2]; c->m_H = m_keep[3];
+        c->m_log_t.resize(log_keep); c->m_log_H.resize(log_keep);
         if (rc == QSR_OK && e == hipSuccess) e = hipGraphInstantiate(&c->graph_exec, g, nullptr, nullptr, 0);
         if (g) (void)hipGraphDestroy(g);
         if (rc != QSR_OK) return rc;
@@ -537,15 +639,21 @@ extern "C" int qsr_run(qsr_ctx *c, int64_t n)
     while (n >= per) {
         HIP_TRY(hipGraphLaunch(c->graph_exec, c->stream));
         c->t_host += per;
+        for (long long i = 0; i < per; ++i) mirror_advance(c);
         n -= per;
     }
     return run_one_by_one(c, n);
 }
 
+// Device scheduler state to the host.  Between qsr_local_step and its qsr_maybe_sync the device has
+// not advanced its counters yet (the advance is the last launch of an iteration): the step just
+// enqueued is added here, so that callers see t and h count it, as the protocol says.
 static int fetch_state(qsr_ctx *c)
 {
     HIP_TRY(hipMemcpyAsync(c->h_state, c->d_state, sizeof(DevState), hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(hipStreamSynchronize(c->stream));
+    if (c->h_state->mismatch) return QSR_EMIRROR;
+    if (c->need_sync_call) { c->h_state->t += 1; c->h_state->h += 1; }
     return QSR_OK;
 }
 
@@ -570,6 +678,19 @@ extern "C" int qsr_read_sync_log(qsr_ctx *c, int64_t *t_out, int64_t *H_out, int
     long long m = rounds < cap ? rounds : cap;
     if (m > 0 && t_out) HIP_TRY(hipMemcpy(t_out, c->d_log_t, (size_t)m * sizeof(long long), hipMemcpyDeviceToHost));
     if (m > 0 && H_out) HIP_TRY(hipMemcpy(H_out, c->d_log_H, (size_t)m * sizeof(long long), hipMemcpyDeviceToHost));
+    return QSR_OK;
+}
+
+extern "C" int qsr_read_host_schedule(qsr_ctx *c, int64_t *t_out, int64_t *H_out, int64_t cap, int64_t *n)
+{
+    if (!c || !n || cap < 0) return QSR_EINVAL;
+    const long long rounds = (long long)c->m_log_t.size();
+    *n = rounds;
+    const long long m = rounds < cap ? rounds : cap;
+    for (long long i = 0; i < m; ++i) {
+        if (t_out) t_out[i] = c->m_log_t[(size_t)i];
+        if (H_out) H_out[i] = c->m_log_H[(size_t)i];
+    }
     return QSR_OK;
 }
 
@@ -606,6 +727,7 @@ extern "C" int qsr_set_state(qsr_ctx *c, const int64_t state[4])
     if (c->need_sync_call) return QSR_ESTATE;
     HIP_TRY(launch_sched_set(c->d_state, c->sp, t, s, h, H, c->stream));
     c->t_host = t;
+    mirror_reset(c, t, s, h, H);
     return QSR_OK;
 }
 
@@ -615,6 +737,7 @@ extern "C" int qsr_restart(qsr_ctx *c)
     HIP_TRY(launch_sched_init(c->d_state, c->sp, c->stream));
     c->t_host = 0;
     c->need_sync_call = false;
+    mirror_reset(c, 0, 0, 0, host_get_H(c->sp, c->eta.data(), 0));
     return QSR_OK;
 }
 
@@ -688,6 +811,7 @@ extern "C" const char *qsr_strerror(int code)
     case QSR_EHIP: return "HIP runtime error";
     case QSR_ENOMEM: return "workspace too small or allocation failed";
     case QSR_ENOGPU: return "no gfx950 device";
+    case QSR_EMIRROR: return "host schedule mirror and device scheduler disagree";
     default: return "unknown error";
     }
 }

@@ -14,7 +14,7 @@ struct DevState {
     long long s;        // finished rounds
     long long h;        // local steps done in the current round
     long long H;        // synchronization period of the current round (0 once t == T)
-    int do_sync;        // 1 between the H-th local step of a round and its averaging
+    int mismatch;       // set (and kept) when the host's mirror of the schedule expected another decision
     int pad;
 };
 
@@ -55,10 +55,12 @@ enum : uint32_t { STREAM_GRAD = 0, STREAM_X = 1, STREAM_NOISE = 2, STREAM_LABEL 
 
 // ---- launchers (each returns the hipError_t of its launch) --------------------------------
 hipError_t launch_sched_init(DevState *st, SchedParams sp, hipStream_t s);
-hipError_t launch_sched_tick(DevState *st, hipStream_t s);
 hipError_t launch_sched_set(DevState *st, SchedParams sp, long long t, long long s_, long long h, long long H,
                             hipStream_t s);
-hipError_t launch_sched_next_round(DevState *st, SchedParams sp, hipStream_t s);
+// end of an iteration: t += 1, h += 1 and, if that was the round's H-th step, the round is logged and
+// the next one opened.  expect_sync: what the host's mirror of the schedule decided (1 / 0), checked
+// against the device's own decision, or -1 for no check (launches replayed from a graph).
+hipError_t launch_sched_advance(DevState *st, SchedParams sp, int expect_sync, hipStream_t s);
 
 // fused_sync: leave the step that completes a round to launch_update_*_sync.
 // row_coef: K clipping factors the gradient rows are multiplied by as they are read, or nullptr.
@@ -90,8 +92,8 @@ int clip_blocks_per_row(long long P);
 hipError_t launch_clip_coef(const float *g, int K, long long P, float max_norm, double *partial, float *coef,
                             float *norm, hipStream_t s);
 
-// mean over the K rows of buf [K][P], written to all rows; skipped on the device when
-// st != nullptr and st->do_sync == 0
+// mean over the K rows of buf [K][P], written to all rows; with st != nullptr the launch acts only
+// if the iteration in progress completes its round (st->h + 1 == st->H, read before the advance)
 hipError_t launch_average_rows(float *buf, int K, long long P, const DevState *st, hipStream_t s);
 
 hipError_t launch_broadcast_rows(float *dst, const float *src, int K, long long P, hipStream_t s);

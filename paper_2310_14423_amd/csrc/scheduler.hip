@@ -43,7 +43,7 @@ __global__ void sched_init_kernel(DevState *st, SchedParams sp)
     if (threadIdx.x != 0 || blockIdx.x != 0) return;
     st->t = 0; st->s = 0; st->h = 0;
     st->H = get_H(sp, 0);
-    st->do_sync = 0; st->pad = 0;
+    st->mismatch = 0; st->pad = 0;
 }
 
 // resume: install a saved (t, s, h, H); log entries of earlier rounds are cleared
@@ -53,31 +53,28 @@ __global__ void sched_set_kernel(DevState *st, SchedParams sp, long long t, long
     for (long long i = threadIdx.x; i < s; i += blockDim.x) { sp.log_t[i] = 0; sp.log_H[i] = 0; }
     if (threadIdx.x != 0) return;
     st->t = t; st->s = s; st->h = h; st->H = H;
-    st->do_sync = 0; st->pad = 0;
+    st->mismatch = 0; st->pad = 0;
 }
 
-// end of a local step (Alg. 2's inner loop counter)
-__global__ void sched_tick_kernel(DevState *st)
+// End of an iteration (Alg. 2's counters): t += 1, h += 1; if that was the round's H-th local step,
+// whose averaging the kernels before this one have done (they test h + 1 == H), the round is logged
+// and round s + 1 opened with its period from Eq. (2) at the new t.
+__global__ void sched_advance_kernel(DevState *st, SchedParams sp, int expect_sync)
 {
     if (threadIdx.x != 0 || blockIdx.x != 0) return;
-    long long h = st->h + 1;
-    st->t = st->t + 1;
-    st->h = h;
-    st->do_sync = (h == st->H) ? 1 : 0;
-}
-
-// after the averaging of round s: log it, open round s+1 (Alg. 2: t already advanced by H)
-__global__ void sched_next_round_kernel(DevState *st, SchedParams sp)
-{
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
-    if (!st->do_sync) return;
-    long long s = st->s, t = st->t;
-    sp.log_t[s] = t;
-    sp.log_H[s] = st->H;
-    st->s = s + 1;
-    st->h = 0;
-    st->H = get_H(sp, t);
-    st->do_sync = 0;
+    const long long t = st->t + 1, h = st->h + 1, s = st->s;
+    const int sync = (h == st->H) ? 1 : 0;
+    if (expect_sync >= 0 && expect_sync != sync) st->mismatch = 1;
+    st->t = t;
+    if (sync) {
+        sp.log_t[s] = t;
+        sp.log_H[s] = st->H;
+        st->s = s + 1;
+        st->h = 0;
+        st->H = get_H(sp, t);
+    } else {
+        st->h = h;
+    }
 }
 
 hipError_t launch_sched_init(DevState *st, SchedParams sp, hipStream_t s)
@@ -91,14 +88,9 @@ hipError_t launch_sched_set(DevState *st, SchedParams sp, long long t, long long
     sched_set_kernel<<<1, 256, 0, s>>>(st, sp, t, s_, h, H);
     return hipGetLastError();
 }
-hipError_t launch_sched_tick(DevState *st, hipStream_t s)
+hipError_t launch_sched_advance(DevState *st, SchedParams sp, int expect_sync, hipStream_t s)
 {
-    sched_tick_kernel<<<1, 64, 0, s>>>(st);
-    return hipGetLastError();
-}
-hipError_t launch_sched_next_round(DevState *st, SchedParams sp, hipStream_t s)
-{
-    sched_next_round_kernel<<<1, 64, 0, s>>>(st, sp);
+    sched_advance_kernel<<<1, 64, 0, s>>>(st, sp, expect_sync);
     return hipGetLastError();
 }
 

@@ -4,6 +4,7 @@ import ctypes as C
 import os
 import re
 
+import numpy as np
 import pytest
 
 import paper_2310_14423_amd as qsr
@@ -25,7 +26,7 @@ def test_library_exports_every_declared_symbol():
 def test_strerror():
     L = qsr.lib()
     assert L.qsr_strerror(0) == b"ok"
-    for code in (-1, -2, -3, -4, -5):
+    for code in (-1, -2, -3, -4, -5, -6):
         assert len(L.qsr_strerror(code)) > 3
     assert L.qsr_strerror(-99) == b"unknown error"
 
@@ -103,3 +104,70 @@ def test_null_arguments():
     cfg, keep = make_config(workloads.get("lsq"))
     assert L.qsr_init(C.byref(cfg), C.c_void_p(16), C.c_void_p(16), C.c_void_p(16), None, None, None, None,
                       C.c_size_t(0), C.byref(out)) == -1
+
+
+# ---- the library's host-side schedule (the routine behind the context's mirror of the device scheduler)
+def _schedule_workload(T, T_warm, lr, eta_max, eta_min, H_base, alpha, power=2, **kw):
+    w = dict(model="noise", K=1, P=4, T=T, T_warm=T_warm, opt="sgdm", mu=0.0, lam=0.0, lr=lr, eta_max=eta_max,
+             eta_min=eta_min, H_base=H_base, alpha=alpha, power=power, grad_sigma=0.0, seed=0)
+    w.update(kw)
+    return w
+
+
+def _golden_rows():
+    from test_oracle_schedule import _rows
+    return _rows()
+
+
+@pytest.mark.parametrize("row", _golden_rows(), ids=lambda r: r["id"])
+def test_host_schedule_reproduces_the_printed_communication_volumes(row):
+    """Every communication volume the paper prints (Tables 1-3, Sec. 4.1, Table 6(a)), from the
+    library's own learning-rate tables and host-side rule, and the same integer sequence as the
+    oracle's."""
+    import oracle
+    from test_oracle_schedule import N_IMAGENET, _table
+    spe = N_IMAGENET // row["B"]
+    T = row["epochs"] * spe
+    extra = {}
+    lr = row["sched"]
+    if lr == "smith":
+        lr, extra = "step", dict(milestones=[e * spe for e in (150, 180, 210, 240, 270)], factor=2.0)
+    w = _schedule_workload(T, row["Tw"], lr, row["eta_max"], row["eta_min"], row["H_base"], row["coef"],
+                           power=3 if row["rule"] == "cubic" else 2, **extra)
+    cfg, keep = make_config(w)
+    t, H = qsr.host_schedule(cfg)
+    assert t[-1] == T and H.sum() == T
+    assert abs(100.0 * len(H) / T - row["pct"]) <= 0.05 + 1e-9
+    eta, Tw = _table(row)
+    oH, ot = oracle.schedule(eta, Tw, row["H_base"], row["coef"], 3 if row["rule"] == "cubic" else 2)
+    assert np.array_equal(H, oH) and np.array_equal(t, ot)
+
+
+@pytest.mark.parametrize("name,rounds", [("lsq", 28), ("mlp", 307), ("flat60m", 8), ("resmlp", 3), ("vit", 3),
+                                         ("flat350m", 4)])
+def test_host_schedule_of_the_named_workloads(name, rounds):
+    import oracle
+    from util import eta_of
+    w = workloads.get(name)
+    cfg, keep = make_config(w)
+    t, H = qsr.host_schedule(cfg)
+    oH, ot = oracle.schedule(eta_of(w), w.get("T_warm", 0), w["H_base"], w["alpha"])
+    assert len(t) == rounds and np.array_equal(H, oH) and np.array_equal(t, ot)
+
+
+@pytest.mark.parametrize("kw", [dict(power=3, alpha=0.012), dict(power=1, alpha=0.03), dict(power=0, H_base=7),
+                                dict(power=0, H_base=8, t_local_start=700), dict(t_local_start=300),
+                                dict(power=0, t_swap_start=1500), dict(alpha=100.0), dict(T_warm=2000),
+                                dict(H_base=5000), dict(alpha=0.0, H_base=1)])
+def test_host_schedule_variants_and_degenerate_cases(kw):
+    """The rule variants and the edge cases of the truncation and warm-up rules, against the oracle's Alg. 2
+    driver (post-local, SWAP, constant H; alpha so large that H = T; a run that is all warm-up)."""
+    from util import oracle_run
+    base = dict(T=2000, T_warm=0, lr="cosine", eta_max=0.008, eta_min=0.0, H_base=4, alpha=0.0175)
+    base.update(kw)
+    w = _schedule_workload(**base)
+    cfg, keep = make_config(w)
+    t, H = qsr.host_schedule(cfg)
+    orc = oracle_run(dict(w, model="external", K=1, P=1), theta0=np.zeros(1))
+    orc.step(w["T"], ext_g=np.zeros((w["T"], 1, 1)))
+    assert np.array_equal(t, orc.sync_log) and np.array_equal(H, orc.H_log) and t[-1] == w["T"]

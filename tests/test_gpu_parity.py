@@ -6,7 +6,7 @@ import pytest
 
 import oracle
 import workloads
-from util import assert_params_close, eta_of, gpu_ctx, oracle_run, rms_error_ratio
+from util import assert_mirror_matches_device, assert_params_close, eta_of, gpu_ctx, oracle_run, rms_error_ratio
 
 pytestmark = pytest.mark.gpu
 
@@ -141,6 +141,7 @@ def test_schedule_is_bit_exact_for_the_full_run(name):
     gt, gH = ctx.read_sync_log()
     assert list(gt) == list(st) and list(gH) == list(H)
     assert ctx.get_H() == (0, len(H), w0["T"])
+    assert_mirror_matches_device(ctx)
     ctx.close()
 
 
@@ -185,6 +186,7 @@ def test_flat60m_full_size_sampled(fuse_gradient):
         assert_params_close(p, orc.theta, what="flat60m t=%d" % upto)
         assert all(np.array_equal(p[k], p[0]) for k in range(16)) == (upto == 306)
     assert ctx.get_H() == (311, 1, 310)
+    assert_mirror_matches_device(ctx)
     m = ctx.state0[:, torch_idx(idx)].cpu().numpy()
     v = ctx.state1[:, torch_idx(idx)].cpu().numpy()
     assert_params_close(m, orc.st0, what="m"); assert_params_close(v, orc.st1, what="v")
@@ -501,14 +503,15 @@ def _oracle_gradients_in_threads(orc, workers, th0, capsys, what):
         out[k] = orc.grad(k, 0, th0)
 
     threads = [threading.Thread(target=work, args=(k,)) for k in workers]
-    t0 = time.time()
+    t0 = last = time.time()
     for th in threads:
         th.start()
     while any(th.is_alive() for th in threads):
-        threads[0].join(timeout=20.0)
-        if any(th.is_alive() for th in threads):
+        time.sleep(0.5)
+        if time.time() - last >= 20.0:
+            last = time.time()
             with capsys.disabled():
-                print("[%s: oracle gradients of %d workers, %.0f s]" % (what, len(workers), time.time() - t0), flush=True)
+                print("[%s: oracle gradients of %d workers, %.0f s]" % (what, len(workers), last - t0), flush=True)
     for th in threads:
         th.join()
     return out
@@ -799,6 +802,7 @@ def test_other_synchronization_schedules_are_bit_exact(kw):
     gt, gH = ctx.read_sync_log()
     assert list(gt) == list(orc.sync_log) and list(gH) == list(orc.H_log) and gt[-1] == 2000
     assert len(gt) > 3
+    assert_mirror_matches_device(ctx)
     ctx.close()
 
 
@@ -817,6 +821,7 @@ def test_other_learning_rate_schedules_are_bit_exact(lr, kw):
     gt, gH = ctx.read_sync_log()
     assert list(gt) == list(orc.sync_log) and list(gH) == list(orc.H_log) and gt[-1] == 1500
     assert_params_close(ctx.params.cpu().numpy(), orc.theta, what=lr)
+    assert_mirror_matches_device(ctx)
     ctx.close()
 
 
@@ -861,6 +866,7 @@ def test_degenerate_schedules(case):
     gt, gH = ctx.read_sync_log()
     assert list(gt) == list(orc.sync_log) and list(gH) == list(orc.H_log) and gt[-1] == w["T"]
     assert_params_close(ctx.params.cpu().numpy(), orc.theta, what=str(case))
+    assert_mirror_matches_device(ctx)
     ctx.close()
 
 
@@ -880,6 +886,7 @@ def test_learning_rate_table_with_zero_tail():
     gt, gH = ctx.read_sync_log()
     assert list(gt) == list(orc.sync_log) and list(gH) == list(orc.H_log)
     assert_params_close(ctx.params.cpu().numpy(), orc.theta, what="zero-tail table")
+    assert_mirror_matches_device(ctx)
     ctx.close()
 
 
@@ -1051,6 +1058,7 @@ def test_checkpoint_and_resume():
     bt, bH = b.read_sync_log()
     s = state[1]
     assert list(bt[s:]) == list(ref_t[s:]) and list(bH[s:]) == list(ref_H[s:]) and not bt[:s].any()
+    assert_mirror_matches_device(b); assert_mirror_matches_device(ref)
     with pytest.raises(qsr.QSRError):
         b.set_state((5, 0, 7, 3))            # h >= H
     with pytest.raises(qsr.QSRError):
@@ -1071,8 +1079,9 @@ def test_timing_statistics():
     ctx.timing(True)
     ctx.step(9)
     ms, cnt, lo, med = ctx.read_timing_stats()
-    assert cnt == [9, 9, 2, 7]                       # averaging ran after iterations 4 and 8
-    for i in range(4):
+    # averaging ran after iterations 4 and 8; enqueued one by one, no averaging kernel is launched elsewhere
+    assert cnt == [9, 9, 2, 0]
+    for i in range(3):
         assert 0 < lo[i] <= med[i] and lo[i] * cnt[i] <= ms[i] * (1 + 1e-6)
     assert ctx.read_timing() == ([0.0] * 4, [0] * 4)   # the pairs were consumed
     ctx.close()
@@ -1085,9 +1094,12 @@ def test_protocol_errors():
     with pytest.raises(qsr.QSRError):
         ctx.maybe_sync()                  # nothing to close
     ctx.local_step()
+    assert ctx.get_H() == (2, 0, 1) and ctx.get_state() == (1, 0, 1, 2)   # the step just enqueued counts
     with pytest.raises(qsr.QSRError):
         ctx.local_step()                  # maybe_sync missing
-    ctx.maybe_sync(); ctx.step()
+    ctx.maybe_sync()
+    assert ctx.get_H() == (2, 0, 1) and ctx.get_state() == (1, 0, 1, 2)
+    ctx.step()
     with pytest.raises(qsr.QSRError) as e:
         ctx.local_step()                  # past T
     assert e.value.code == -2

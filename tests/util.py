@@ -80,3 +80,11 @@ def rms_error_ratio(gpu, orc, rms=None):
         rms = np.sqrt(np.mean(orc * orc))
     err = gpu - orc
     return float(np.sqrt(np.mean(err * err)) / max(rms, 1e-300))
+
+
+def assert_mirror_matches_device(ctx):
+    """The rounds counted by the host's mirror of the schedule (which decides where an averaging kernel is
+    enqueued) equal the device scheduler's log, entry for entry."""
+    dt, dH = ctx.read_sync_log()
+    mt, mH = ctx.read_host_schedule()
+    assert list(dt) == list(mt) and list(dH) == list(mH), (list(dt), list(mt))
