@@ -236,6 +236,18 @@ int qsr_destroy(qsr_ctx *ctx);
  * buf_k <- (1/K) sum_k buf_k for every k.  Asynchronous on `stream`. */
 int qsr_average_rows(float *buf, int32_t K, int64_t P, void *stream);
 
+/* Stateless gradient clipping factors (App. C: clipping by global norm, per worker) of any [K][P]
+ * gradient buffer: coef[k] = min(1, max_norm / (||g_k||_2 + 1e-6)), norm[k] = ||g_k||_2, both DEVICE
+ * arrays of K floats; the caller multiplies row k by coef[k] (the update kernels of a context with
+ * clip_norm do so as they read the gradient).  workspace: DEVICE memory for the partial sums of
+ * squares, qsr_clip_workspace_bytes(K, P) bytes, 8-byte aligned, contents irrelevant before and
+ * after.  The sums are deterministic (fixed order).  Asynchronous on `stream`.  QSR_EINVAL on bad
+ * arguments (K outside 1..65535, P < 1, max_norm not positive and finite), QSR_ENOMEM if the
+ * workspace is too small. */
+int qsr_clip_workspace_bytes(int32_t K, int64_t P, size_t *bytes);
+int qsr_clip_factors(const float *grads, int32_t K, int64_t P, float max_norm, void *workspace,
+                     size_t workspace_bytes, float *coef, float *norm, void *stream);
+
 const char *qsr_strerror(int code);
 int qsr_last_hip_error(void); /* hipError_t of the last failed runtime call in this thread */
 

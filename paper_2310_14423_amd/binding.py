@@ -11,7 +11,7 @@ _lib = None
 
 EXPORTS = ["qsr_validate", "qsr_workspace_bytes", "qsr_host_schedule", "qsr_init", "qsr_local_step", "qsr_maybe_sync",
            "qsr_run", "qsr_get_H", "qsr_get_state", "qsr_set_state", "qsr_read_sync_log", "qsr_read_host_schedule", "qsr_eta_table", "qsr_read_loss", "qsr_restart",
-           "qsr_timing", "qsr_read_timing", "qsr_read_timing_stats", "qsr_destroy", "qsr_average_rows", "qsr_strerror",
+           "qsr_timing", "qsr_read_timing", "qsr_read_timing_stats", "qsr_destroy", "qsr_average_rows", "qsr_clip_workspace_bytes", "qsr_clip_factors", "qsr_strerror",
            "qsr_last_hip_error"]
 
 OPTS = {"sgdm": 0, "adamw": 1}
@@ -134,6 +134,24 @@ def average_rows(buf, stream=None):
     st = torch.cuda.current_stream().cuda_stream if stream is None else stream
     _check(lib().qsr_average_rows(C.c_void_p(buf.data_ptr()), C.c_int32(buf.shape[0]),
                                   C.c_int64(buf.shape[1]), C.c_void_p(st)), "qsr_average_rows")
+
+
+def clip_factors(grads, max_norm, stream=None):
+    """grads: 2-D float32 CUDA tensor [K][P].  Returns (coef, norm), float32 CUDA tensors of K entries:
+    the per-worker clipping factors min(1, max_norm / (||g_k|| + 1e-6)) and the norms."""
+    import torch
+    assert grads.is_cuda and grads.dtype == torch.float32 and grads.is_contiguous() and grads.dim() == 2
+    K, P = grads.shape
+    st = torch.cuda.current_stream().cuda_stream if stream is None else stream
+    n = C.c_size_t(0)
+    _check(lib().qsr_clip_workspace_bytes(C.c_int32(K), C.c_int64(P), C.byref(n)), "qsr_clip_workspace_bytes")
+    ws = torch.empty(max(n.value // 8, 1), dtype=torch.float64, device=grads.device)
+    coef = torch.empty(K, dtype=torch.float32, device=grads.device)
+    norm = torch.empty(K, dtype=torch.float32, device=grads.device)
+    _check(lib().qsr_clip_factors(C.c_void_p(grads.data_ptr()), C.c_int32(K), C.c_int64(P), C.c_float(max_norm),
+                                  C.c_void_p(ws.data_ptr()), C.c_size_t(n.value), C.c_void_p(coef.data_ptr()),
+                                  C.c_void_p(norm.data_ptr()), C.c_void_p(st)), "qsr_clip_factors")
+    return coef, norm
 
 
 def _allocate_state(torch, dev, K, P, second_moment, placement):

@@ -80,3 +80,35 @@ hipError_t launch_clip_coef(const float *g, int K, long long P, float max_norm, 
 }
 
 }  // namespace qsr
+
+// Stateless form for callers that hold gradients of their own (like qsr_average_rows for the
+// All-Reduce line): the K factors and norms of a [K][P] gradient buffer, with the partial sums in a
+// workspace the caller brings in.
+extern "C" int qsr_clip_workspace_bytes(int32_t K, int64_t P, size_t *bytes)
+{
+    if (!bytes) return QSR_EINVAL;
+    *bytes = 0;
+    if (K < 1 || K > 65535 || P < 1 || P > ((long long)1 << 34)) return QSR_EINVAL;
+    *bytes = (size_t)K * (size_t)qsr::clip_blocks_per_row(P) * sizeof(double);
+    return QSR_OK;
+}
+
+static int clip_args_ok(const float *grads, int32_t K, int64_t P, float max_norm, const float *coef, const float *norm)
+{
+    if (!grads || !coef || !norm || K < 1 || K > 65535 || P < 1 || P > ((long long)1 << 34)) return 0;
+    if (!(max_norm > 0.0f) || !(max_norm < INFINITY)) return 0;
+    return 1;
+}
+
+extern "C" int qsr_clip_factors(const float *grads, int32_t K, int64_t P, float max_norm, void *workspace,
+                                size_t workspace_bytes, float *coef, float *norm, void *stream)
+{
+    if (!clip_args_ok(grads, K, P, max_norm, coef, norm)) return QSR_EINVAL;
+    if (!workspace || ((uintptr_t)workspace & 7) != 0) return QSR_EINVAL;
+    size_t need = 0;
+    (void)qsr_clip_workspace_bytes(K, P, &need);
+    if (workspace_bytes < need) return QSR_ENOMEM;
+    hipError_t e = qsr::launch_clip_coef(grads, K, P, max_norm, (double *)workspace, coef, norm, (hipStream_t)stream);
+    if (e != hipSuccess) { qsr::set_last_hip_error((int)e); return QSR_EHIP; }
+    return QSR_OK;
+}

@@ -12,6 +12,7 @@
 using namespace qsr;
 
 static thread_local int g_last_hip = 0;
+void qsr::set_last_hip_error(int code) { g_last_hip = code; (void)hipGetLastError(); }
 
 #define HIP_TRY(expr)                                    \
     do {                                                 \

@@ -53,6 +53,9 @@ __device__ __forceinline__ void st_nt4(float4 *p, float4 v)
 // streams of the counter-based generator (second counter word)
 enum : uint32_t { STREAM_GRAD = 0, STREAM_X = 1, STREAM_NOISE = 2, STREAM_LABEL = 3 };
 
+// records the hipError_t that qsr_last_hip_error() reports for the calling thread
+void set_last_hip_error(int code);
+
 // ---- launchers (each returns the hipError_t of its launch) --------------------------------
 hipError_t launch_sched_init(DevState *st, SchedParams sp, hipStream_t s);
 hipError_t launch_sched_set(DevState *st, SchedParams sp, long long t, long long s_, long long h, long long H,

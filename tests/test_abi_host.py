@@ -171,3 +171,25 @@ def test_host_schedule_variants_and_degenerate_cases(kw):
     orc = oracle_run(dict(w, model="external", K=1, P=1), theta0=np.zeros(1))
     orc.step(w["T"], ext_g=np.zeros((w["T"], 1, 1)))
     assert np.array_equal(t, orc.sync_log) and np.array_equal(H, orc.H_log) and t[-1] == w["T"]
+
+
+def test_clip_factors_argument_checks():
+    """Host-side checks of the stateless clipping entry point: nothing is launched on bad arguments."""
+    L = qsr.lib()
+    n = C.c_size_t(7)
+    assert L.qsr_clip_workspace_bytes(C.c_int32(0), C.c_int64(10), C.byref(n)) == -1 and n.value == 0
+    assert L.qsr_clip_workspace_bytes(C.c_int32(4), C.c_int64(0), C.byref(n)) == -1
+    assert L.qsr_clip_workspace_bytes(C.c_int32(4), C.c_int64(100), C.byref(n)) == 0 and n.value == 4 * 8
+    assert L.qsr_clip_workspace_bytes(C.c_int32(2), C.c_int64(60_000_000), C.byref(n)) == 0 and n.value == 2 * 1024 * 8
+    p = C.c_void_p(4096)
+    call = lambda g, K, P, c, ws, wsb, coef, norm: L.qsr_clip_factors(
+        g, C.c_int32(K), C.c_int64(P), C.c_float(c), ws, C.c_size_t(wsb), coef, norm, None)
+    assert call(None, 2, 8, 1.0, p, 64, p, p) == -1
+    assert call(p, 0, 8, 1.0, p, 64, p, p) == -1
+    assert call(p, 2, 0, 1.0, p, 64, p, p) == -1
+    assert call(p, 2, 8, 0.0, p, 64, p, p) == -1
+    assert call(p, 2, 8, float("inf"), p, 64, p, p) == -1
+    assert call(p, 2, 8, 1.0, None, 64, p, p) == -1
+    assert call(p, 2, 8, 1.0, C.c_void_p(4097), 64, p, p) == -1      # misaligned workspace
+    assert call(p, 2, 8, 1.0, p, 8, p, p) == -4                       # workspace too small
+    assert call(p, 2, 8, 1.0, p, 64, None, p) == -1

@@ -1004,6 +1004,30 @@ def test_gradient_clipping(opt, K, P, extra):
     ctx.close()
 
 
+@pytest.mark.parametrize("K,P", [(1, 5), (3, 4099), (4, 65536 + 8), (16, 1 << 20), (2, 3_000_001)])
+def test_stateless_clip_factors(K, P):
+    """qsr_clip_factors on a caller's gradient buffer: norms and factors against the oracle's clipping
+    routine (App. C), rows far above, near and below the threshold; deterministic."""
+    import torch
+    import paper_2310_14423_amd as qsr
+    rng = np.random.default_rng(K * 13 + P)
+    scale = rng.choice([0.02, 2.0, 60.0], size=(K, 1)) / np.sqrt(P)
+    g = (rng.standard_normal((K, P)) * scale).astype(np.float32)
+    gd = torch.from_numpy(g).cuda()
+    coef, norm = qsr.clip_factors(gd, 2.0)
+    coef2, norm2 = qsr.clip_factors(gd, 2.0)
+    assert torch.equal(coef, coef2) and torch.equal(norm, norm2)
+    coef, norm = coef.cpu().numpy(), norm.cpu().numpy()
+    for k in range(K):
+        row = g[k].astype(np.float64)
+        want_norm = oracle.clip(row, 2.0)              # clips `row` in place, returns the norm before
+        assert norm[k] == pytest.approx(want_norm, rel=2e-7)
+        want_coef = min(1.0, 2.0 / (want_norm + 1e-6))
+        assert coef[k] == pytest.approx(want_coef, rel=2e-7)
+        assert np.allclose(row, g[k].astype(np.float64) * want_coef, rtol=1e-12, atol=0)
+    assert bool(torch.equal(gd.cpu(), torch.from_numpy(g)))     # the gradients themselves are not touched
+
+
 def test_array_placement_does_not_change_results():
     """On request the binding spreads large [K][P] arrays over the physical ranges of the HBM (a matter
     of speed only, and a benchmark's experiment: the default is four plain allocations): a run on
