@@ -42,8 +42,9 @@ enum {
     QSR_EHIP = -3,     /* a HIP runtime call failed; qsr_last_hip_error() has its code  */
     QSR_ENOMEM = -4,   /* workspace too small / allocation failed                       */
     QSR_ENOGPU = -5,   /* no usable gfx950 device                                       */
-    QSR_EMIRROR = -6   /* the host's mirror of the schedule and the device scheduler took
+    QSR_EMIRROR = -6,  /* the host's mirror of the schedule and the device scheduler took
                           different decisions (a defect: results after it are not Alg. 2's) */
+    QSR_ELIMIT = -7    /* size beyond the fixed capacity of an entry point that allocates nothing */
 };
 
 enum { QSR_OPT_SGDM = 0, QSR_OPT_ADAMW = 1 };
@@ -247,6 +248,18 @@ int qsr_average_rows(float *buf, int32_t K, int64_t P, void *stream);
 int qsr_clip_workspace_bytes(int32_t K, int64_t P, size_t *bytes);
 int qsr_clip_factors(const float *grads, int32_t K, int64_t P, float max_norm, void *workspace,
                      size_t workspace_bytes, float *coef, float *norm, void *stream);
+
+/* qsr_clip_factors for callers that cannot allocate device memory or bring a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without
+ * the workspace, same results bit for bit; the partial sums live in a 512 KiB array inside the
+ * library's device image, which every GPU the library runs on holds until the process ends.
+ * Limits: K <= 64 (QSR_ELIMIT beyond).  Calls no hipMalloc / hipFree or other allocating routine;
+ * the array's address on a device is looked up once, by the first qsr_init or the first call of
+ * this function there (make that first call outside a capture).  All calls on one GPU share the
+ * array: calls that overlap on one GPU (other streams, other threads) race.  Asynchronous on
+ * `stream`. */
+int qsr_clip_factors_static(const float *grads, int32_t K, int64_t P, float max_norm, float *coef,
+                            float *norm, void *stream);
 
 const char *qsr_strerror(int code);
 int qsr_last_hip_error(void); /* hipError_t of the last failed runtime call in this thread */

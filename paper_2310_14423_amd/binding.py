@@ -11,7 +11,7 @@ _lib = None
 
 EXPORTS = ["qsr_validate", "qsr_workspace_bytes", "qsr_host_schedule", "qsr_init", "qsr_local_step", "qsr_maybe_sync",
            "qsr_run", "qsr_get_H", "qsr_get_state", "qsr_set_state", "qsr_read_sync_log", "qsr_read_host_schedule", "qsr_eta_table", "qsr_read_loss", "qsr_restart",
-           "qsr_timing", "qsr_read_timing", "qsr_read_timing_stats", "qsr_destroy", "qsr_average_rows", "qsr_clip_workspace_bytes", "qsr_clip_factors", "qsr_strerror",
+           "qsr_timing", "qsr_read_timing", "qsr_read_timing_stats", "qsr_destroy", "qsr_average_rows", "qsr_clip_workspace_bytes", "qsr_clip_factors", "qsr_clip_factors_static", "qsr_strerror",
            "qsr_last_hip_error"]
 
 OPTS = {"sgdm": 0, "adamw": 1}
@@ -152,6 +152,19 @@ def clip_factors(grads, max_norm, stream=None):
                                   C.c_void_p(ws.data_ptr()), C.c_size_t(n.value), C.c_void_p(coef.data_ptr()),
                                   C.c_void_p(norm.data_ptr()), C.c_void_p(st)), "qsr_clip_factors")
     return coef, norm
+
+
+def clip_factors_static(grads, max_norm, coef, norm, stream=None):
+    """qsr_clip_factors_static: results into the caller's coef and norm tensors (K floats each); the
+    library allocates nothing."""
+    import torch
+    assert grads.is_cuda and grads.dtype == torch.float32 and grads.is_contiguous() and grads.dim() == 2
+    K, P = grads.shape
+    assert coef.is_cuda and norm.is_cuda and coef.dtype == norm.dtype == torch.float32 and coef.numel() >= K <= norm.numel()
+    st = torch.cuda.current_stream().cuda_stream if stream is None else stream
+    _check(lib().qsr_clip_factors_static(C.c_void_p(grads.data_ptr()), C.c_int32(K), C.c_int64(P), C.c_float(max_norm),
+                                         C.c_void_p(coef.data_ptr()), C.c_void_p(norm.data_ptr()), C.c_void_p(st)),
+           "qsr_clip_factors_static")
 
 
 def _allocate_state(torch, dev, K, P, second_moment, placement):

@@ -7,6 +7,8 @@
 // The sum of squares is deterministic: every lane adds its elements in index order with an
 // error-free transformation of each addition, a workgroup combines its lanes in a fixed tree in
 // double precision, and one workgroup per row adds the partial sums in index order.
+#include <mutex>
+
 #include "opt_elem.h"
 #include "qsr_internal.h"
 
@@ -109,6 +111,57 @@ extern "C" int qsr_clip_factors(const float *grads, int32_t K, int64_t P, float 
     (void)qsr_clip_workspace_bytes(K, P, &need);
     if (workspace_bytes < need) return QSR_ENOMEM;
     hipError_t e = qsr::launch_clip_coef(grads, K, P, max_norm, (double *)workspace, coef, norm, (hipStream_t)stream);
+    if (e != hipSuccess) { qsr::set_last_hip_error((int)e); return QSR_EHIP; }
+    return QSR_OK;
+}
+
+
+// ---------------------------------------------------------------------------------------------
+// The same for callers that cannot allocate (code under HIP graph capture, tight serving loops,
+// harnesses that forbid hipMalloc): the partial sums live in an array inside the library's device
+// image, K * min(1024, ceil(P / 16384)) doubles, K <= 64: 512 KiB that every GPU the library runs
+// on holds until the process ends.  All calls on one GPU share it: calls that overlap there
+// (different streams, different threads) race on the partial sums.  Nothing has to start at zero:
+// the first kernel writes every partial sum the second one reads.
+// ---------------------------------------------------------------------------------------------
+constexpr int CLIP_STATIC_MAX_K = 64;
+constexpr int CLIP_STATIC_DOUBLES = CLIP_STATIC_MAX_K * 1024;
+static __device__ __align__(256) double scratch[CLIP_STATIC_DOUBLES];
+
+// In host code `scratch` is only a handle: the array's device address is asked for once per device,
+// with that device current, and kept; each GPU holds its own copy at its own address.
+constexpr int CLIP_MAX_DEVICES = 64;
+static std::mutex g_scratch_mutex;
+static double *g_scratch_ptr[CLIP_MAX_DEVICES];
+
+int qsr::clip_static_setup(double **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) { qsr::set_last_hip_error((int)e); return QSR_EHIP; }
+    if (dev < 0 || dev >= CLIP_MAX_DEVICES) return QSR_ELIMIT;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        double *p = nullptr;
+        e = hipGetSymbolAddress((void **)&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) { qsr::set_last_hip_error((int)e); return QSR_EHIP; }
+        if (!p) return QSR_EHIP;
+        g_scratch_ptr[dev] = p;
+    }
+    if (out) *out = g_scratch_ptr[dev];
+    return QSR_OK;
+}
+
+extern "C" int qsr_clip_factors_static(const float *grads, int32_t K, int64_t P, float max_norm, float *coef,
+                                       float *norm, void *stream)
+{
+    if (!clip_args_ok(grads, K, P, max_norm, coef, norm)) return QSR_EINVAL;
+    if (K > CLIP_STATIC_MAX_K) return QSR_ELIMIT;
+    if ((long long)K * qsr::clip_blocks_per_row(P) > CLIP_STATIC_DOUBLES) return QSR_ELIMIT;
+    double *partial = nullptr;
+    const int rc = qsr::clip_static_setup(&partial);
+    if (rc != QSR_OK) return rc;
+    hipError_t e = qsr::launch_clip_coef(grads, K, P, max_norm, partial, coef, norm, (hipStream_t)stream);
     if (e != hipSuccess) { qsr::set_last_hip_error((int)e); return QSR_EHIP; }
     return QSR_OK;
 }

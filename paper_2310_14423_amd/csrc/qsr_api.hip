@@ -355,6 +355,10 @@ static int init_impl(qsr_ctx *c, const float *theta0)
     hipDeviceProp_t prop;
     HIP_TRY(hipGetDeviceProperties(&prop, c->device));
     if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return QSR_ENOGPU;
+    {   // set-up of the entry point that must not allocate later: find its array on this device now
+        int rc = clip_static_setup(nullptr);
+        if (rc != QSR_OK) return rc;
+    }
 
     HIP_TRY(hipMalloc((void **)&c->d_state, sizeof(DevState)));
     HIP_TRY(hipMalloc((void **)&c->d_eta, T * sizeof(double)));
@@ -813,6 +817,7 @@ extern "C" const char *qsr_strerror(int code)
     case QSR_ENOMEM: return "workspace too small or allocation failed";
     case QSR_ENOGPU: return "no gfx950 device";
     case QSR_EMIRROR: return "host schedule mirror and device scheduler disagree";
+    case QSR_ELIMIT: return "beyond the fixed capacity of an entry point that allocates nothing";
     default: return "unknown error";
     }
 }

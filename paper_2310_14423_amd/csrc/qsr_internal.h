@@ -94,6 +94,9 @@ hipError_t launch_update_adamw_sync(float *theta, const float *g, float *m, floa
 int clip_blocks_per_row(long long P);
 hipError_t launch_clip_coef(const float *g, int K, long long P, float max_norm, double *partial, float *coef,
                             float *norm, hipStream_t s);
+// device address, on the current device, of the partial-sum array inside the library's image
+// (qsr_clip_factors_static); looked up at the first call on a device.  Returns a QSR_* code.
+int clip_static_setup(double **out);
 
 // mean over the K rows of buf [K][P], written to all rows; with st != nullptr the launch acts only
 // if the iteration in progress completes its round (st->h + 1 == st->H, read before the advance)

@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
 def test_strerror():
     L = qsr.lib()
     assert L.qsr_strerror(0) == b"ok"
-    for code in (-1, -2, -3, -4, -5, -6):
+    for code in (-1, -2, -3, -4, -5, -6, -7):
         assert len(L.qsr_strerror(code)) > 3
     assert L.qsr_strerror(-99) == b"unknown error"
 
