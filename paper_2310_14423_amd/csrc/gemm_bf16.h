@@ -24,11 +24,32 @@
 // rows as its "B"), so that it produces the transposed tile: lane l then owns, for token row
 // m = l%32, four consecutive output columns n, which is what the epilogue's LDS staging writes
 // with 128-bit stores (see epilogue_via_lds).
+//
+// Operand layout.  Besides plain row-major, a bf16 matrix [R][C] (C a multiple of 32) can be stored
+// in blocks of 32 rows x 32 columns, each block 2 KiB contiguous, blocks ordered [row block]
+// [column block] (blk_off below).  Both kinds of GEMM then copy consecutive memory: a 256-row x
+// 64-deep slab of this kernel's operands is 8 pieces of 4 KiB (two neighbouring blocks) instead of
+// 256 pieces of 128 B a whole row (1.5 - 6 KiB) apart, and a 32-token x 192- or 384-feature slab of
+// the weight-gradient kernel (gemm_pp.h), which walks the same arrays along their rows, is 12 or
+// 24 KiB in one piece instead of 32 pieces; every global -> LDS copy instruction moves 1 KiB of
+// consecutive memory.  (Blocks of 256 rows x 32 columns, 32 KiB per slab here, were timed first:
+// this kernel gained 3-4 %, the weight-gradient kernel, whose slab was then 2 KiB pieces exactly
+// 16 KiB apart, lost 8 %.)  All weights (B operands) are blocked; activations are blocked where
+// their producers write them that way (BLKA), row-major otherwise.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 namespace qsr {
+
+// element offset of (r, c) in the blocked layout of an [R][C] matrix; R is padded to 256 rows (the
+// tiles of this kernel read whole 256-row panels)
+__host__ __device__ __forceinline__ long long blk_off(long long r, long long c, long long C)
+{
+    return ((r >> 5) * (C >> 5) + (c >> 5)) * 1024 + (r & 31) * 32 + (c & 31);
+}
+// elements a blocked [R][C] matrix occupies
+__host__ __device__ __forceinline__ long long blk_elems(long long R, long long C) { return ((R + 255) >> 8) * 256 * C; }
 
 typedef __bf16 bf16_t;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -109,13 +130,17 @@ __device__ __forceinline__ void epilogue_via_lds(f32x16 (&acc)[TM][TN], float *s
     }
 }
 
-template <int BM, int BN, int BK, int WM, int WN, class Epi>
+// BLKA: A is stored in 32 x 32 blocks (see above); B always is.  In LDS a slab of a blocked operand
+// is [2 column blocks][rows][32 k], rows of 64 B, slot s of row r holding piece s ^ ((r >> 2) & 3);
+// a row-major A slab is [rows][64 k] with slot = piece ^ ((r >> 1) & 7).
+template <int BM, int BN, int BK, int WM, int WN, bool BLKA, class Epi>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_bf16_kernel(GemmNT p, Epi epi, int batch)
 {
-    static_assert(BK == 64 || BK == 32, "rows are 8 or 4 pieces of 16 B");
-    constexpr int PPR = BK / 8;             // 16-byte pieces per row
-    constexpr int RPC = 64 / PPR;           // rows per 1 KiB chunk
-    constexpr int SWZ = BK == 64 ? 1 : 2;   // slot = piece ^ ((row >> SWZ) & (PPR - 1))
+    static_assert(BK == 64, "a slab is two 32-column blocks, or rows of 8 pieces of 16 B");
+    static_assert(BM == 256 && BN == 256, "tiles are one row block of the blocked layout");
+    constexpr int PPR = BK / 8;             // 16-byte pieces per row (row-major slab)
+    constexpr int RPC = 64 / PPR;           // rows per 1 KiB chunk (row-major slab)
+    constexpr int SWZ = 1;                  // row-major slab: slot = piece ^ ((row >> SWZ) & (PPR - 1))
     constexpr int NW = WM * WN;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     constexpr int A_CHUNKS = BM / RPC, B_CHUNKS = BN / RPC;   // 1 KiB chunks per slab
@@ -147,23 +172,31 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_bf16_kernel(GemmNT p, Ep
     const bf16_t *A = p.A + (long long)z * p.sA;
     const bf16_t *B = p.B + (long long)z * p.sB;
 
-    // per-lane global source of each chunk this wave copies: LDS slot (row, s) of a chunk holds
-    // the global piece s ^ ((row >> SWZ) & (PPR - 1)) of that row
-    const int lrow = lane / PPR, lslot = lane % PPR;
+    // Per-lane global source of each 1 KiB chunk this wave copies.  Row-major operand: chunk c is 8
+    // rows x 128 B, LDS slot (row, s) holds the global piece s ^ ((row >> 1) & 7) of that row.
+    // Blocked operand: chunk c is 16 rows x 64 B, half of a 32 x 32 block (c / 16 the column block of
+    // the slab, c % 16 the run of rows), consecutive in memory up to the permutation of the four
+    // 16-byte pieces inside each row: slot s of row r holds piece s ^ ((r >> 2) & 3).  Rows beyond the
+    // matrix inside the last 256-row panel are allocated (their values only reach accumulator rows
+    // never stored).
     const bf16_t *srcA[A_PER_WAVE], *srcB[B_PER_WAVE];
+    const int blk_lane = (lane >> 2) * 32 + (((lane & 3) ^ ((lane >> 4) & 3)) * 8);   // inside a blocked chunk
+    constexpr long long A_SLAB = BLKA ? 2 * 1024 : BK, B_SLAB = 2 * 1024;              // elements per slab step
 #pragma unroll
     for (int i = 0; i < A_PER_WAVE; ++i) {
-        int row = (wave * A_PER_WAVE + i) * RPC + lrow;
-        int piece = lslot ^ ((row >> SWZ) & (PPR - 1));
-        int gm = min(m0 + row, p.M - 1);
-        srcA[i] = A + (long long)gm * p.lda + piece * 8;
+        const int c = wave * A_PER_WAVE + i;
+        if (BLKA) {
+            srcA[i] = A + ((long long)(by * 8 + ((c & 15) >> 1)) * (p.K >> 5) + (c >> 4)) * 1024 + (c & 1) * 512 + blk_lane;
+        } else {
+            const int row = c * RPC + lane / PPR;
+            const int piece = (lane % PPR) ^ ((row >> SWZ) & (PPR - 1));
+            srcA[i] = A + (long long)min(m0 + row, p.M - 1) * p.lda + piece * 8;
+        }
     }
 #pragma unroll
     for (int i = 0; i < B_PER_WAVE; ++i) {
-        int row = (wave * B_PER_WAVE + i) * RPC + lrow;
-        int piece = lslot ^ ((row >> SWZ) & (PPR - 1));
-        int gn = min(n0 + row, p.N - 1);
-        srcB[i] = B + (long long)gn * p.ldb + piece * 8;
+        const int c = wave * B_PER_WAVE + i;
+        srcB[i] = B + ((long long)(bx * 8 + ((c & 15) >> 1)) * (p.K >> 5) + (c >> 4)) * 1024 + (c & 1) * 512 + blk_lane;
     }
     typedef __attribute__((address_space(3))) void lds_void;
     typedef __attribute__((address_space(1))) const void glb_void;
@@ -171,11 +204,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_bf16_kernel(GemmNT p, Ep
         bf16_t *sa = smem + stage * STAGE_ELEMS, *sb = sa + BM * BK;
 #pragma unroll
         for (int i = 0; i < A_PER_WAVE; ++i)
-            __builtin_amdgcn_global_load_lds((glb_void *)(srcA[i] + k0),
+            __builtin_amdgcn_global_load_lds((glb_void *)(srcA[i] + (long long)(k0 / BK) * A_SLAB),
                                              (lds_void *)(sa + (wave * A_PER_WAVE + i) * 512), 16, 0, 0);
 #pragma unroll
         for (int i = 0; i < B_PER_WAVE; ++i)
-            __builtin_amdgcn_global_load_lds((glb_void *)(srcB[i] + k0),
+            __builtin_amdgcn_global_load_lds((glb_void *)(srcB[i] + (long long)(k0 / BK) * B_SLAB),
                                              (lds_void *)(sb + (wave * B_PER_WAVE + i) * 512), 16, 0, 0);
     };
 
@@ -198,16 +231,19 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_bf16_kernel(GemmNT p, Ep
     bf16x8 fa[2][TM], fb[2][TN];
     auto load_frags = [&](int stage, int ks, int fbuf) {
         const bf16_t *sa = smem + stage * STAGE_ELEMS, *sb = sa + BM * BK;
-        const int piece = ks * 2 + (lane >> 5);
+        const int piece = ks * 2 + (lane >> 5);               // of the 8 pieces of a 64-deep row
+        // blocked slab: column block piece / 4, rows of four pieces
+        const int blk_base = (piece >> 2) * (256 * 32), bp = piece & 3;
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-            int row = wm * TM * 32 + i * 32 + (lane & 31);
-            fa[fbuf][i] = *(const bf16x8 *)(sa + row * BK + ((piece ^ ((row >> SWZ) & (PPR - 1))) * 8));
+            const int row = wm * TM * 32 + i * 32 + (lane & 31);
+            if (BLKA) fa[fbuf][i] = *(const bf16x8 *)(sa + blk_base + row * 32 + ((bp ^ ((row >> 2) & 3)) * 8));
+            else fa[fbuf][i] = *(const bf16x8 *)(sa + row * BK + ((piece ^ ((row >> SWZ) & (PPR - 1))) * 8));
         }
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-            int row = wn * TN * 32 + j * 32 + (lane & 31);
-            fb[fbuf][j] = *(const bf16x8 *)(sb + row * BK + ((piece ^ ((row >> SWZ) & (PPR - 1))) * 8));
+            const int row = wn * TN * 32 + j * 32 + (lane & 31);
+            fb[fbuf][j] = *(const bf16x8 *)(sb + blk_base + row * 32 + ((bp ^ ((row >> 2) & 3)) * 8));
         }
     };
     auto mfmas = [&](int fbuf) {
@@ -247,15 +283,16 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_bf16_kernel(GemmNT p, Ep
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));   // operand of the LDS transpose read
 
-template <int BM, int BN, int BK, int WM, int WN, class Epi>
+template <int BM, int BN, int BK, int WM, int WN, bool BLKA, class Epi>
 inline hipError_t launch_gemm_nt(const GemmNT &p, const Epi &epi, int batch, hipStream_t s)
 {
+    if (p.K % BK != 0 || p.K < BK) return hipErrorInvalidValue;
     const unsigned tiles = (unsigned)((p.N + BN - 1) / BN) * (unsigned)((p.M + BM - 1) / BM) * (unsigned)batch;
     dim3 grid((tiles + 7) / 8 * 8, 1, 1);
     constexpr size_t smem = 2 * (size_t)(BM + BN) * BK * sizeof(bf16_t);
     static_assert(smem <= 160 * 1024, "tile does not fit the 160 KB LDS");
     static_assert((size_t)WM * WN * 32 * (BN / WN + 4) * sizeof(float) <= smem, "epilogue staging does not fit the slab buffers");
-    auto kern = gemm_nt_bf16_kernel<BM, BN, BK, WM, WN, Epi>;
+    auto kern = gemm_nt_bf16_kernel<BM, BN, BK, WM, WN, BLKA, Epi>;
     static bool lds_limit_raised = false;     // per instantiation; contexts are not thread-safe
     if (smem > 64 * 1024 && !lds_limit_raised) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);

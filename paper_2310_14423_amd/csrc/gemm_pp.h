@@ -58,7 +58,12 @@
 
 namespace qsr {
 
-template <int NS, class Epi>
+// BLKA / BLKB: the operand is stored in 32-token x 32-feature blocks (gemm_bf16.h); lda / ldb then
+// hold its feature count.  A 1 KiB chunk of a slab (16 tokens x 32 features of one column block) is
+// then 1 KiB of consecutive memory, and a whole slab of a tile one piece of 12 or 24 KiB; row-major
+// a chunk is 16 pieces of 64 B a whole row apart.  Either way a slab lies 32 * ld elements behind
+// the one before.
+template <int NS, bool BLKA, bool BLKB, class Epi>
 __global__ __launch_bounds__(512) void gemm_pp_tn_kernel(GemmNT p, Epi epi, int Z)
 {
     constexpr int BM = 192, BN = 384, BK = 32, WN = 4;
@@ -106,8 +111,8 @@ __global__ __launch_bounds__(512) void gemm_pp_tn_kernel(GemmNT p, Epi epi, int 
         k_end = split > 1 ? min(p.K, k0 + p.k_chunk) : p.K;
         d_row = k0;
         d_stage = 0;
-        const bf16_t *A = p.A + (long long)z * p.sA + (long long)k0 * p.lda;
-        const bf16_t *B = p.B + (long long)z * p.sB + (long long)k0 * p.ldb;
+        const bf16_t *A = p.A + (long long)z * p.sA + (long long)k0 * p.lda;     // k0 is a multiple of 32:
+        const bf16_t *B = p.B + (long long)z * p.sB + (long long)k0 * p.ldb;     // the first block row of the range
 #pragma unroll
         for (int c = 0; c < CPW; ++c) {
             const int chunk = c * 8 + wave;
@@ -115,8 +120,13 @@ __global__ __launch_bounds__(512) void gemm_pp_tn_kernel(GemmNT p, Epi epi, int 
             const int cc = isA ? chunk : chunk - A_CHUNKS;
             const int fblk = cc >> 1, t = (cc & 1) * 16 + (lane >> 2);   // column block, token inside the slab
             const int f = fblk * 32 + (lane & 3) * 8;
-            src[c] = isA ? A + (long long)t * p.lda + min(m0 + f, p.M - 8)
-                         : B + (long long)t * p.ldb + min(n0 + f, p.N - 8);
+            if (isA) {
+                const int fc = min(m0 + f, p.M - 8);
+                src[c] = BLKA ? A + (long long)(fc >> 5) * 1024 + t * 32 + (fc & 31) : A + (long long)t * p.lda + fc;
+            } else {
+                const int fc = min(n0 + f, p.N - 8);
+                src[c] = BLKB ? B + (long long)(fc >> 5) * 1024 + t * 32 + (fc & 31) : B + (long long)t * p.ldb + fc;
+            }
         }
     };
     auto issue_slab = [&]() {                       // copies this wavefront's chunks of the next slab
@@ -279,13 +289,15 @@ inline int gemm_pp_cu_count()
     return n_cu;
 }
 
-template <class Epi>
+template <bool BLKA, bool BLKB, class Epi>
 inline hipError_t launch_gemm_pp_tn(const GemmNT &p, const Epi &epi, int batch, hipStream_t s)
 {
+    // blocked operands: 32-column blocks (the ranges of a split reduction start at multiples of 32 tokens)
+    if ((BLKA && p.lda % 32 != 0) || (BLKB && p.ldb % 32 != 0)) return hipErrorInvalidValue;
     constexpr int NS = 3;                     // 3 stages timed 4-6 % faster than 4
     constexpr size_t smem = (size_t)NS * (192 + 384) * 32 * 2;
     static_assert(smem <= 160 * 1024, "ring does not fit the 160 KB LDS");
-    auto kern = gemm_pp_tn_kernel<NS, Epi>;
+    auto kern = gemm_pp_tn_kernel<NS, BLKA, BLKB, Epi>;
     static bool lds_limit_raised = false;     // per instantiation; contexts are not thread-safe
     if (!lds_limit_raised) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);

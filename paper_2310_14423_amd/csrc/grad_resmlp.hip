@@ -10,8 +10,14 @@
 // matrix cores with fp32 accumulation (gemm_bf16.h); the residual stream, LayerNorm statistics,
 // loss and all gradients stay fp32.  The forward and data-gradient GEMMs are brought to the
 // K-contiguous "NT" form by keeping bf16 copies of the weights in both orientations; the
-// weight-gradient GEMMs reduce over the token axis and read the row-major bf16 activations as
-// they are ("TN" form, LDS transpose reads), so no transposed activation copies exist.
+// weight-gradient GEMMs reduce over the token axis and read the same bf16 activations as they are
+// ("TN" form, LDS transpose reads), so no transposed activation copies exist.  The bf16 weights
+// and the bf16 activations that GEMM epilogues and the LayerNorm forward pass produce (LayerNorm
+// output, GELU output and derivative, the gradient of the hidden layer) are stored in 32-row x
+// 32-column blocks (gemm_bf16.h), written that way by their producers, so that the slab copies of
+// the GEMMs read consecutive memory.  The bf16 copy of the residual gradient stays row-major (the
+// LayerNorm backward pass that writes it lost more on 64-byte store pieces than its two GEMMs
+// gained), and so does what the attention core reads and writes.
 // Per-block parameter packing: gamma[d], beta[d], W1[d][dh], b1[dh], W2[dh][d], b2[d].
 //
 // With n_heads > 0 each block first runs the attention half of a ViT encoder block,
@@ -46,7 +52,9 @@ struct ResWs {
     bf16_t *DXb;   long long sDXb;     // [M][d]
     bf16_t *DH;    long long sDH;      // [M][dh]
     float *DU;     long long sDU;      // [M][d]
-    bf16_t *W1b, *W1Tb, *W2b, *W2Tb; long long sW; // [L][d*dh] each
+    bf16_t *W1b, *W1Tb, *W2b, *W2Tb; long long sW; // [L][blocked d x dh or dh x d] each
+    long long mdB, mdhB;               // elements of one blocked [M][d] / [M][dh] activation
+    long long wB[2];                   // elements of one blocked [d][dh] / [dh][d] weight
     bf16_t *WTt;                       // [d][d], shared: teacher map transposed
     float *PART;   long long sPART;    // [2][wave_rows][d] partial dgamma, dbeta
     float *LPART;  long long sLPART;   // loss partials
@@ -80,20 +88,24 @@ static ResWs carve(const ModelDims &dm, void *ws, size_t *total)
         off += up256((size_t)per_replica * elt * (size_t)copies);
         return r;
     };
+    // blocked arrays: token rows padded to a multiple of 256, weight rows likewise
+    w.mdB = blk_elems(M, d); w.mdhB = blk_elems(M, dh);
+    w.wB[0] = blk_elems(d, dh); w.wB[1] = blk_elems(dh, d);
+    const long long wmax = w.wB[0] > w.wB[1] ? w.wB[0] : w.wB[1];
     w.sX = padded((sub + 1) * M * d, 4); w.X = (float *)take(w.sX, 4, K);
     w.sStat = padded(sub * M, 4);        w.MU = (float *)take(w.sStat, 4, K); w.RSTD = (float *)take(w.sStat, 4, K);
-    w.sH = padded(L * M * dh, 2);        w.H = (bf16_t *)take(w.sH, 2, K);
-    w.sU = padded(sub * M * d, 2);       w.U = (bf16_t *)take(w.sU, 2, K);
-    w.sA = padded(L * M * dh, 2);        w.A = (bf16_t *)take(w.sA, 2, K);
+    w.sH = padded(L * w.mdhB, 2);        w.H = (bf16_t *)take(w.sH, 2, K);
+    w.sU = padded(sub * w.mdB, 2);       w.U = (bf16_t *)take(w.sU, 2, K);
+    w.sA = padded(L * w.mdhB, 2);        w.A = (bf16_t *)take(w.sA, 2, K);
     w.sY = padded(M * d, 4);             w.Y = (float *)take(w.sY, 4, K);
     w.sDX = padded(M * d, 4);            w.DX = (float *)take(w.sDX, 4, K);
     w.sDXb = padded(M * d, 2);           w.DXb = (bf16_t *)take(w.sDXb, 2, K);
-    w.sDH = padded(M * dh, 2);           w.DH = (bf16_t *)take(w.sDH, 2, K);
-    w.sDU = padded(M * d, 4);            w.DU = (float *)take(w.sDU, 4, K);
-    w.sW = padded(L * d * dh, 2);
+    w.sDH = padded(w.mdhB, 2);           w.DH = (bf16_t *)take(w.sDH, 2, K);
+    w.sDU = padded(w.mdB > M * d ? w.mdB : M * d, 4); w.DU = (float *)take(w.sDU, 4, K);
+    w.sW = padded(L * wmax, 2);
     w.W1b = (bf16_t *)take(w.sW, 2, K);  w.W1Tb = (bf16_t *)take(w.sW, 2, K);
     w.W2b = (bf16_t *)take(w.sW, 2, K);  w.W2Tb = (bf16_t *)take(w.sW, 2, K);
-    w.WTt = (bf16_t *)take(d * d, 2, 1);
+    w.WTt = (bf16_t *)take(blk_elems(d, d), 2, 1);
     const long long wave_rows = (M + LN_ROWS_PER_WAVE - 1) / LN_ROWS_PER_WAVE;
     w.sPART = padded(2 * wave_rows * d, 4); w.PART = (float *)take(w.sPART, 4, K);
     w.sLPART = padded((M * d + 1023) / 1024, 4); w.LPART = (float *)take(w.sLPART, 4, K);
@@ -111,9 +123,10 @@ static ResWs carve(const ModelDims &dm, void *ws, size_t *total)
         w.sLSE = padded(L * heads * M, 4);   w.LSE = (float *)take(w.sLSE, 4, K);
         w.sDO = padded(M * d, 2);            w.DO = (bf16_t *)take(w.sDO, 2, K);
         w.sDQKV = padded(M * 3 * d, 2);      w.DQKV = (bf16_t *)take(w.sDQKV, 2, K);
-        w.sWq = padded(L * d * 3 * d, 2);
+        const long long wq = blk_elems(3 * d, d) > blk_elems(d, 3 * d) ? blk_elems(3 * d, d) : blk_elems(d, 3 * d);
+        w.sWq = padded(L * wq, 2);                           // blocked [d][3d] and [3d][d]
         w.Wqb = (bf16_t *)take(w.sWq, 2, K); w.WqTb = (bf16_t *)take(w.sWq, 2, K);
-        w.sWo = padded(L * d * d, 2);
+        w.sWo = padded(L * blk_elems(d, d), 2);
         w.Wob = (bf16_t *)take(w.sWo, 2, K); w.WoTb = (bf16_t *)take(w.sWo, 2, K);
     }
     if (total) *total = off;
@@ -131,27 +144,27 @@ size_t resmlp_workspace_bytes(const ModelDims &d)
 // layout / conversion kernels
 // ---------------------------------------------------------------------------------------------
 
-// in [R][C] (row stride ld_in) -> out [R][C] bf16 (optional) and outT [C][R] bf16 (row stride
-// ld_t), 64x64 tiles through LDS.  Batch index blockIdx.z = z * n_inner + l: z with the element
-// strides s_in, s_out, s_t (workers), l with the strides l_in, l_out (the blocks of the model, whose
-// matrices are R*C apart in both outputs), so that one launch converts a weight of all blocks.
+// in [R][C] (row stride ld_in) -> out [R][C] bf16 (optional) and outT [C][R] bf16, both in the
+// blocked layout of gemm_bf16.h (R and C multiples of 32), 64x64 tiles through LDS.  Batch index
+// blockIdx.z = z * n_inner + l: z with the element strides s_in, s_out, s_t (workers), l with the
+// strides l_in (input) and l_out, l_t (the blocks of the model), so that one launch converts a weight
+// of all blocks.
 template <class TIn>
 __global__ __launch_bounds__(256) void cvt_transpose_kernel(const TIn *__restrict__ in, long long ld_in,
                                                             long long s_in, long long l_in, bf16_t *__restrict__ out,
-                                                            long long s_out, bf16_t *__restrict__ outT,
-                                                            long long ld_t, long long s_t, int R, int C, int n_inner)
+                                                            long long s_out, long long l_out, bf16_t *__restrict__ outT,
+                                                            long long s_t, long long l_t, int R, int C, int n_inner)
 {
     __shared__ bf16_t tile[64][66];
     const int z = blockIdx.z / n_inner, l = blockIdx.z - z * n_inner;
     const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    const long long l_out = (long long)l * R * C;
     in += (long long)z * s_in + (long long)l * l_in;
     for (int r = ty; r < 64; r += 4) {
         bf16_t v = (bf16_t)0.0f;
         if (r0 + r < R && c0 + tx < C) {
             v = (bf16_t)in[(long long)(r0 + r) * ld_in + c0 + tx];
-            if (out) out[(long long)z * s_out + l_out + (long long)(r0 + r) * C + c0 + tx] = v;
+            if (out) out[(long long)z * s_out + (long long)l * l_out + blk_off(r0 + r, c0 + tx, C)] = v;
         }
         tile[r][tx] = v;
     }
@@ -159,33 +172,37 @@ __global__ __launch_bounds__(256) void cvt_transpose_kernel(const TIn *__restric
     if (outT) {
         for (int c = ty; c < 64; c += 4)
             if (c0 + c < C && r0 + tx < R)
-                outT[(long long)z * s_t + l_out + (long long)(c0 + c) * ld_t + r0 + tx] = tile[tx][c];
+                outT[(long long)z * s_t + (long long)l * l_t + blk_off(c0 + c, r0 + tx, R)] = tile[tx][c];
     }
 }
 
 template <class TIn>
 static hipError_t launch_cvt_transpose(const TIn *in, long long ld_in, long long s_in, long long l_in, bf16_t *out,
-                                       long long s_out, bf16_t *outT, long long ld_t, long long s_t,
+                                       long long s_out, bf16_t *outT, long long s_t,
                                        int R, int C, int batch, int n_inner, hipStream_t s)
 {
-    if ((long long)batch * n_inner > 65535) return hipErrorInvalidValue;
+    if ((long long)batch * n_inner > 65535 || R % 32 != 0 || C % 32 != 0) return hipErrorInvalidValue;
     dim3 grid((unsigned)((C + 63) / 64), (unsigned)((R + 63) / 64), (unsigned)(batch * n_inner));
-    cvt_transpose_kernel<TIn><<<grid, 256, 0, s>>>(in, ld_in, s_in, l_in, out, s_out, outT, ld_t, s_t, R, C, n_inner);
+    cvt_transpose_kernel<TIn><<<grid, 256, 0, s>>>(in, ld_in, s_in, l_in, out, s_out, blk_elems(R, C), outT, s_t,
+                                                   blk_elems(C, R), R, C, n_inner);
     return hipGetLastError();
 }
 
-// out[z][0..4*n4) = bf16(in[z][0..4*n4)), four elements per lane and trip; blockIdx.y = worker
+// out[z] = bf16(in[z]) for a row-major [rows][d] fp32 array, written in the blocked layout; four
+// elements per lane and trip (d a multiple of 4); blockIdx.y = worker
 __global__ __launch_bounds__(256) void f32_to_bf16_kernel(const float *__restrict__ in, long long s_in,
                                                           bf16_t *__restrict__ out, long long s_out,
-                                                          long long n4)
+                                                          long long n4, int d)
 {
     const float4 *src = (const float4 *)(in + (long long)blockIdx.y * s_in);
-    bf16x4 *dst = (bf16x4 *)(out + (long long)blockIdx.y * s_out);
+    bf16_t *dst = out + (long long)blockIdx.y * s_out;
     const long long stride = (long long)gridDim.x * 256;
+    const int d4 = d >> 2;
     for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
         const float4 v = src[i];
         const bf16x4 b = {(bf16_t)v.x, (bf16_t)v.y, (bf16_t)v.z, (bf16_t)v.w};
-        dst[i] = b;
+        const long long row = i / d4;
+        *(bf16x4 *)(dst + blk_off(row, (i - row * d4) * 4, d)) = b;
     }
 }
 
@@ -200,7 +217,8 @@ __device__ __forceinline__ float wave_sum(float v)
 }
 
 // One wavefront per token row, the row held in registers as VPL float4 per lane (d <= 256 VPL,
-// d a multiple of 4): statistics in fp32, output u = gamma*xhat + beta in bf16 (64-bit stores).
+// d a multiple of 32): statistics in fp32, output u = gamma*xhat + beta in bf16 (64-bit stores) in
+// the blocked layout.
 template <int VPL>
 __global__ __launch_bounds__(256) void ln_fwd_kernel(const float *__restrict__ X, long long sX,
                                                      const float *__restrict__ theta, long long sTh,
@@ -232,7 +250,7 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const float *__restrict__ X
         }
     }
     const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + LN_EPS);
-    bf16_t *u = U + (long long)z * sU + (long long)row * d;
+    bf16_t *u = U + (long long)z * sU;                  // blocked [M][d]
 #pragma unroll
     for (int c = 0; c < VPL; ++c) {
         const int j = (lane + c * 64) * 4;
@@ -240,7 +258,7 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const float *__restrict__ X
             const float4 gv = *(const float4 *)(gam + j), bv = *(const float4 *)(bet + j);
             bf16x4 o = {(bf16_t)fmaf(gv.x, (xv[c].x - mean) * rstd, bv.x), (bf16_t)fmaf(gv.y, (xv[c].y - mean) * rstd, bv.y),
                         (bf16_t)fmaf(gv.z, (xv[c].z - mean) * rstd, bv.z), (bf16_t)fmaf(gv.w, (xv[c].w - mean) * rstd, bv.w)};
-            *(bf16x4 *)(u + j) = o;
+            *(bf16x4 *)(u + blk_off(row, j, d)) = o;
         }
     }
     if (lane == 0) { MU[(long long)z * sStat + row] = mean; RSTD[(long long)z * sStat + row] = rstd; }
@@ -296,7 +314,7 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const TDU *__restrict__ DU,
             const int j = (lane + c * 64) * 4;
             float4 duv = make_float4(0.f, 0.f, 0.f, 0.f), xv = make_float4(mean, mean, mean, mean);
             if (j < d) {
-                duv = load4f(DU + (long long)z * sDU + o + j);
+                duv = load4f(DU + (long long)z * sDU + o + j);     // row-major in either type: no GEMM reads it
                 xv = *(const float4 *)(X + (long long)z * sX + o + j);
             }
             const float du[4] = {duv.x, duv.y, duv.z, duv.w}, xx[4] = {xv.x, xv.y, xv.z, xv.w};
@@ -466,13 +484,15 @@ struct EpiScaleF32 {             // C = scale * acc
                make_float4(v[0] * scale, v[1] * scale, v[2] * scale, v[3] * scale));
     }
 };
-struct EpiBf16 {                 // C = bf16(acc)
+template <bool BLK>
+struct EpiBf16 {                 // C = bf16(acc), row-major or blocked
     bf16_t *C; long long ldc, sC;
     typedef NoAux Aux;
     __device__ Aux pre(int, int, int) const { return Aux{}; }
     __device__ void operator()(int z, int m, int n, const float (&v)[4], const Aux &) const
     {
-        *(bf16x4 *)(C + (long long)z * sC + (long long)m * ldc + n) = pack4(v[0], v[1], v[2], v[3]);
+        const long long o = BLK ? blk_off(m, n, ldc) : (long long)m * ldc + n;
+        *(bf16x4 *)(C + (long long)z * sC + o) = pack4(v[0], v[1], v[2], v[3]);
     }
 };
 struct EpiBiasBf16 {             // C = bf16(acc + bias)
@@ -485,7 +505,7 @@ struct EpiBiasBf16 {             // C = bf16(acc + bias)
         *(bf16x4 *)(C + (long long)z * sC + (long long)m * ldc + n) = pack4(v[0] + b.x, v[1] + b.y, v[2] + b.z, v[3] + b.w);
     }
 };
-struct EpiBiasGelu {             // h = acc + b1; H = bf16(gelu'(h)); A = bf16(gelu(h))
+struct EpiBiasGelu {             // h = acc + b1; H = bf16(gelu'(h)); A = bf16(gelu(h)), both blocked
     // The backward pass needs h only through gelu'(h) = Phi(h) + h phi(h), and both factors are at
     // hand here: storing the derivative instead of h costs two instructions per element now and
     // saves the whole GELU evaluation in the data-gradient epilogue.
@@ -504,7 +524,7 @@ struct EpiBiasGelu {             // h = acc + b1; H = bf16(gelu'(h)); A = bf16(g
             a[i] = h[i] * c;
             dg[i] = fmaf(h[i], pdf, c);
         }
-        const long long o = (long long)m * ld + n;
+        const long long o = blk_off(m, n, ld);
         __builtin_nontemporal_store(pack4(dg[0], dg[1], dg[2], dg[3]), (bf16x4 *)(H + (long long)z * sH + o));
         __builtin_nontemporal_store(pack4(a[0], a[1], a[2], a[3]), (bf16x4 *)(A + (long long)z * sA + o));
     }
@@ -523,19 +543,19 @@ struct EpiBiasResidual {         // x_out = x_in + acc + b2
         st_nt4((float4 *)(Xout + o), make_float4(x.x + v[0] + b.x, x.y + v[1] + b.y, x.z + v[2] + b.z, x.w + v[3] + b.w));
     }
 };
-struct EpiGeluBwd {              // dh = acc * gelu'(h), H holding gelu'(h) from the forward pass
+struct EpiGeluBwd {              // dh = acc * gelu'(h), H holding gelu'(h) from the forward pass; both blocked
     const bf16_t *H; long long sH; bf16_t *DH; long long sDH; long long ld;
     typedef bf16x4 Aux;
     __device__ Aux pre(int z, int m, int n) const
     {
-        return *(const bf16x4 *)(H + (long long)z * sH + (long long)m * ld + n);
+        return *(const bf16x4 *)(H + (long long)z * sH + blk_off(m, n, ld));
     }
     __device__ void operator()(int z, int m, int n, const float (&v)[4], const Aux &hb) const
     {
         float r[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) r[i] = v[i] * (float)hb[i];
-        __builtin_nontemporal_store(pack4(r[0], r[1], r[2], r[3]), (bf16x4 *)(DH + (long long)z * sDH + (long long)m * ld + n));
+        __builtin_nontemporal_store(pack4(r[0], r[1], r[2], r[3]), (bf16x4 *)(DH + (long long)z * sDH + blk_off(m, n, ld)));
     }
 };
 
@@ -553,18 +573,19 @@ struct EpiGeluBwd {              // dh = acc * gelu'(h), H holding gelu'(h) from
 // NT: the plain tiled kernel (the persistent one timed the same to slower here: a workgroup that
 // goes on to its next tile must first see its epilogue's stores complete, where a fresh workgroup
 // starts at once).  TN: the persistent two-group kernel where the problem allows it.
-template <class Epi>
+// BLKA: the activation operand is blocked (the weights always are)
+template <bool BLKA, class Epi>
 static hipError_t gemm_nt(const GemmNT &p, const Epi &epi, int batch, hipStream_t s)
 {
-    return launch_gemm_nt<QSR_GEMM_BIG>(p, epi, batch, s);
+    return launch_gemm_nt<QSR_GEMM_BIG, BLKA>(p, epi, batch, s);
 }
-template <class Epi>
+template <bool BLKA, bool BLKB, class Epi>
 static hipError_t gemm_tn(const GemmNT &p, const Epi &epi, int batch, hipStream_t s)
 {
     // widths are multiples of 64 and a block of zeros stands in for ragged token counts, so every
     // weight gradient of this model qualifies
     if (!gemm_pp_tn_supports(p)) return hipErrorInvalidValue;
-    return launch_gemm_pp_tn(p, epi, batch, s);
+    return launch_gemm_pp_tn<BLKA, BLKB>(p, epi, batch, s);
 }
 
 #define TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return e_; } while (0)
@@ -591,6 +612,7 @@ __global__ __launch_bounds__(256) void splitk_sum_kernel(const float *__restrict
 // results are added up afterwards (the 768 x 768 output projection of 8 workers is 64 tiles of
 // 192 x 384 for 256 compute units: 0.37 ms as one range each, as long as a gradient four times
 // its size).
+template <bool BLKA, bool BLKB>
 static hipError_t wgrad(GemmNT p, float *dW, float *db, long long sOut, const ResWs &w, int batch, hipStream_t s)
 {
     p.zeros = w.ZERO;
@@ -602,13 +624,13 @@ static hipError_t wgrad(GemmNT p, float *dW, float *db, long long sOut, const Re
     if (split <= 1) {
         p.colsum_B = db; p.s_colsum = sOut;
         EpiScaleF32 epi{dW, p.N, sOut, 1.0f};
-        return gemm_tn(p, epi, batch, s);
+        return gemm_tn<BLKA, BLKB>(p, epi, batch, s);
     }
     const long long MN = (long long)p.M * p.N;
     p.split = split; p.k_chunk = k_chunk;
     p.colsum_B = w.SPLITKB; p.s_colsum = p.N;
     EpiScaleF32 epi{w.SPLITK, p.N, MN, 1.0f};
-    TRY(gemm_tn(p, epi, batch, s));
+    TRY((gemm_tn<BLKA, BLKB>(p, epi, batch, s)));
     splitk_sum_kernel<<<dim3((unsigned)((MN / 4 + 255) / 256), (unsigned)batch), 256, 0, s>>>(w.SPLITK, MN, split, dW, sOut);
     TRY(hipGetLastError());
     splitk_sum_kernel<<<dim3((unsigned)((p.N / 4 + 255) / 256), (unsigned)batch), 256, 0, s>>>(w.SPLITKB, p.N, split, db, sOut);
@@ -627,7 +649,8 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
     const long long per_block = per_attn + 2LL * d + (long long)d * dh + dh + (long long)dh * d + d;
     if (heads > 0 && !attn_supports(d, heads, S, M)) return hipErrorInvalidValue;
     ResWs w = carve(dm, ws, nullptr);
-    const long long Md = (long long)M * d, Mdh = (long long)M * dh;
+    const long long Md = (long long)M * d;            // a row-major [M][d] array (fp32 state and its relatives)
+    const long long MdB = w.mdB, MdhB = w.mdhB;       // a blocked [M][d] / [M][dh] bf16 array
     // Rows per wavefront of the LayerNorm backward pass: enough that all wavefronts of the launch
     // are resident at once (a launch of 1.5 times the chip's wavefront slots runs as one full wave of
     // workgroups and a half-empty one).  Resident wavefronts per CU follow from the kernel's registers.
@@ -650,7 +673,7 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
     auto ln_fwd = [&](int sub, long long off_gamma) -> hipError_t {
         dim3 grid((unsigned)((M + 3) / 4), (unsigned)K);
 #define LN_FWD(VPL) ln_fwd_kernel<VPL><<<grid, 256, 0, s>>>(w.X + (long long)sub * Md, w.sX, theta, P, off_gamma, \
-                        w.U + (long long)sub * Md, w.sU, w.MU + (long long)sub * M, w.RSTD + (long long)sub * M, w.sStat, M, d)
+                        w.U + (long long)sub * MdB, w.sU, w.MU + (long long)sub * M, w.RSTD + (long long)sub * M, w.sStat, M, d)
         const int vpl = (d + 255) / 256;
         if (vpl <= 1) LN_FWD(1); else if (vpl <= 2) LN_FWD(2); else if (vpl <= 3) LN_FWD(3); else LN_FWD(4);
 #undef LN_FWD
@@ -688,27 +711,30 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
     // launch per kind of weight, over all blocks and workers
     {
         const long long oW1 = per_attn + 2LL * d, oW2 = oW1 + (long long)d * dh + dh;
-        TRY(launch_cvt_transpose<float>(theta + oW1, dh, P, per_block, w.W1b, w.sW, w.W1Tb, d, w.sW, d, dh, K, L, s));
-        TRY(launch_cvt_transpose<float>(theta + oW2, d, P, per_block, w.W2b, w.sW, w.W2Tb, dh, w.sW, dh, d, K, L, s));
+        TRY(launch_cvt_transpose<float>(theta + oW1, dh, P, per_block, w.W1b, w.sW, w.W1Tb, w.sW, d, dh, K, L, s));
+        TRY(launch_cvt_transpose<float>(theta + oW2, d, P, per_block, w.W2b, w.sW, w.W2Tb, w.sW, dh, d, K, L, s));
         if (heads > 0) {
             const long long oWq = 2LL * d, oWo = oWq + 3 * dd + 3LL * d;
-            TRY(launch_cvt_transpose<float>(theta + oWq, 3LL * d, P, per_block, w.Wqb, w.sWq, w.WqTb, d, w.sWq, d, 3 * d, K, L, s));
-            TRY(launch_cvt_transpose<float>(theta + oWo, d, P, per_block, w.Wob, w.sWo, w.WoTb, d, w.sWo, d, d, K, L, s));
+            TRY(launch_cvt_transpose<float>(theta + oWq, 3LL * d, P, per_block, w.Wqb, w.sWq, w.WqTb, w.sWq, d, 3 * d, K, L, s));
+            TRY(launch_cvt_transpose<float>(theta + oWo, d, P, per_block, w.Wob, w.sWo, w.WoTb, w.sWo, d, d, K, L, s));
         }
     }
-    TRY(launch_cvt_transpose<float>(teacher, d, 0, 0, nullptr, 0, w.WTt, d, 0, d, d, 1, 1, s));
+    TRY(launch_cvt_transpose<float>(teacher, d, 0, 0, nullptr, 0, w.WTt, 0, d, d, 1, 1, s));
+    // elements of one block's blocked weight copies: as stored ([rows][cols]) and transposed
+    const long long wW1 = w.wB[0], wW1T = w.wB[1], wW2 = w.wB[1], wW2T = w.wB[0];
+    const long long wWq = blk_elems(d, 3 * d), wWqT = blk_elems(3 * d, d), wWo = blk_elems(d, d);
 
     // Sample(): tokens x_0 (fp32 in X[0], bf16 in U), teacher targets y = x_0 W_T / sqrt(d)
     TRY(launch_fill_normal(w.X, w.sX, K, Md, 1.0f, STREAM_X, dm.seed, st, s));
     {
         long long blocks = (Md / 4 + 255) / 256; if (blocks > 65535) blocks = 65535;   // d is a multiple of 64
-        f32_to_bf16_kernel<<<dim3((unsigned)blocks, (unsigned)K), 256, 0, s>>>(w.X, w.sX, w.U, w.sU, Md / 4);
+        f32_to_bf16_kernel<<<dim3((unsigned)blocks, (unsigned)K), 256, 0, s>>>(w.X, w.sX, w.U, w.sU, Md / 4, d);
         TRY(hipGetLastError());
     }
     {
         GemmNT p{w.U, w.WTt, M, d, d, d, d, w.sU, 0};
         EpiScaleF32 epi{w.Y, d, w.sY, 1.0f / sqrtf((float)d)};
-        TRY(gemm_nt(p, epi, K, s));
+        TRY(gemm_nt<true>(p, epi, K, s));
     }
 
     // forward
@@ -719,35 +745,34 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
             bf16_t *QKVl = w.QKV + (long long)l * M * 3 * d, *Ol = w.O + (long long)l * Md;
             TRY(ln_fwd(sub, oga));
             {
-                GemmNT p{w.U + (long long)sub * Md, w.WqTb + l * 3 * dd, M, 3 * d, d, d, d, w.sU, w.sWq};
+                GemmNT p{w.U + (long long)sub * MdB, w.WqTb + l * wWqT, M, 3 * d, d, d, d, w.sU, w.sWq};
                 EpiBiasBf16 epi{theta + obq, P, QKVl, 3LL * d, w.sQKV};
-                TRY(gemm_nt(p, epi, K, s));
+                TRY(gemm_nt<true>(p, epi, K, s));
             }
             att.QKV = QKVl; att.O = Ol; att.LSE = w.LSE + (long long)l * heads * M;
             TRY(launch_attn_fwd(att, heads, K, s));
             {
-                GemmNT p{Ol, w.WoTb + l * dd, M, d, d, d, d, w.sO, w.sWo};
+                GemmNT p{Ol, w.WoTb + l * wWo, M, d, d, d, d, w.sO, w.sWo};
                 EpiBiasResidual epi{theta + obo, P, w.X + (long long)sub * Md, w.X + (long long)(sub + 1) * Md, w.sX, d};
-                TRY(gemm_nt(p, epi, K, s));
+                TRY(gemm_nt<false>(p, epi, K, s));
             }
             ++sub;
         }
         const long long og = l * per_block + per_attn, ob1 = og + 2LL * d + (long long)d * dh,
                         ob2 = ob1 + dh + (long long)dh * d;
-        const long long ow = (long long)l * d * dh;
         const float *Xl = w.X + (long long)sub * Md;
         float *Xn = w.X + (long long)(sub + 1) * Md;
-        bf16_t *Ul = w.U + (long long)sub * Md, *Al = w.A + (long long)l * Mdh;
+        bf16_t *Ul = w.U + (long long)sub * MdB, *Al = w.A + (long long)l * MdhB;
         TRY(ln_fwd(sub, og));
         {
-            GemmNT p{Ul, w.W1Tb + ow, M, dh, d, d, d, w.sU, w.sW};
-            EpiBiasGelu epi{theta + ob1, P, w.H + (long long)l * Mdh, w.sH, Al, w.sA, dh};
-            TRY(gemm_nt(p, epi, K, s));
+            GemmNT p{Ul, w.W1Tb + l * wW1T, M, dh, d, d, d, w.sU, w.sW};
+            EpiBiasGelu epi{theta + ob1, P, w.H + (long long)l * MdhB, w.sH, Al, w.sA, dh};
+            TRY(gemm_nt<true>(p, epi, K, s));
         }
         {
-            GemmNT p{Al, w.W2Tb + ow, M, d, dh, dh, dh, w.sA, w.sW};
+            GemmNT p{Al, w.W2Tb + l * wW2T, M, d, dh, dh, dh, w.sA, w.sW};
             EpiBiasResidual epi{theta + ob2, P, Xl, Xn, w.sX, d};
-            TRY(gemm_nt(p, epi, K, s));
+            TRY(gemm_nt<true>(p, epi, K, s));
         }
     }
 
@@ -767,32 +792,31 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
         int sub = nsub * l + nsub - 1;
         const long long og = l * per_block + per_attn, oW1 = og + 2LL * d, ob1 = oW1 + (long long)d * dh,
                         oW2 = ob1 + dh, ob2 = oW2 + (long long)dh * d;
-        const long long ow = (long long)l * d * dh;
         // W2 and b2:  dW2 = a^T dx, db2 = column sums of dx (by-product of the same GEMM)
         {
-            GemmNT p{w.A + (long long)l * Mdh, w.DXb, dh, d, M, dh, d, w.sA, w.sDXb};
-            TRY(wgrad(p, g + oW2, g + ob2, P, w, K, s));
+            GemmNT p{w.A + (long long)l * MdhB, w.DXb, dh, d, M, dh, d, w.sA, w.sDXb};
+            TRY((wgrad<true, false>(p, g + oW2, g + ob2, P, w, K, s)));
         }
         // dh = (dx W2^T) * gelu'(h)
         {
-            GemmNT p{w.DXb, w.W2b + ow, M, dh, d, d, d, w.sDXb, w.sW};
-            EpiGeluBwd epi{w.H + (long long)l * Mdh, w.sH, w.DH, w.sDH, dh};
-            TRY(gemm_nt(p, epi, K, s));
+            GemmNT p{w.DXb, w.W2b + l * wW2, M, dh, d, d, d, w.sDXb, w.sW};
+            EpiGeluBwd epi{w.H + (long long)l * MdhB, w.sH, w.DH, w.sDH, dh};
+            TRY(gemm_nt<false>(p, epi, K, s));
         }
         // W1 and b1:  dW1 = u^T dh, db1 = column sums of dh
         {
-            GemmNT p{w.U + (long long)sub * Md, w.DH, d, dh, M, d, dh, w.sU, w.sDH};
-            TRY(wgrad(p, g + oW1, g + ob1, P, w, K, s));
+            GemmNT p{w.U + (long long)sub * MdB, w.DH, d, dh, M, d, dh, w.sU, w.sDH};
+            TRY((wgrad<true, true>(p, g + oW1, g + ob1, P, w, K, s)));
         }
         // du = dh W1^T, then LayerNorm backward + residual
         {
-            GemmNT p{w.DH, w.W1b + ow, M, d, dh, dh, dh, w.sDH, w.sW};
+            GemmNT p{w.DH, w.W1b + l * wW1, M, d, dh, dh, dh, w.sDH, w.sW};
             if (du16) {
-                EpiBf16 epi{DU16, d, sDU16};
-                TRY(gemm_nt(p, epi, K, s));
+                EpiBf16<false> epi{DU16, d, sDU16};
+                TRY(gemm_nt<true>(p, epi, K, s));
             } else {
                 EpiScaleF32 epi{w.DU, d, w.sDU, 1.0f};
-                TRY(gemm_nt(p, epi, K, s));
+                TRY(gemm_nt<true>(p, epi, K, s));
             }
         }
         TRY(ln_bwd(sub, og));
@@ -804,26 +828,26 @@ hipError_t launch_resmlp_grad(const ModelDims &dm, const float *theta, float *g,
             // Wo and bo:  dWo = o^T dx, dbo = column sums of dx
             {
                 GemmNT p{Ol, w.DXb, d, d, M, d, d, w.sO, w.sDXb};
-                TRY(wgrad(p, g + oWo, g + obo, P, w, K, s));
+                TRY((wgrad<false, false>(p, g + oWo, g + obo, P, w, K, s)));
             }
             // do = dx Wo^T
             {
-                GemmNT p{w.DXb, w.Wob + l * dd, M, d, d, d, d, w.sDXb, w.sWo};
-                EpiBf16 epi{w.DO, d, w.sDO};
-                TRY(gemm_nt(p, epi, K, s));
+                GemmNT p{w.DXb, w.Wob + l * wWo, M, d, d, d, d, w.sDXb, w.sWo};
+                EpiBf16<false> epi{w.DO, d, w.sDO};
+                TRY(gemm_nt<false>(p, epi, K, s));
             }
             att.QKV = QKVl; att.O = Ol; att.LSE = w.LSE + (long long)l * heads * M;
             TRY(launch_attn_bwd(att, heads, K, s));
             // Wqkv and bqkv:  dWqkv = u^T dqkv, dbqkv = column sums of dqkv
             {
-                GemmNT p{w.U + (long long)sub * Md, w.DQKV, d, 3 * d, M, d, 3LL * d, w.sU, w.sDQKV};
-                TRY(wgrad(p, g + oWq, g + obq, P, w, K, s));
+                GemmNT p{w.U + (long long)sub * MdB, w.DQKV, d, 3 * d, M, d, 3LL * d, w.sU, w.sDQKV};
+                TRY((wgrad<true, false>(p, g + oWq, g + obq, P, w, K, s)));
             }
             // du = dqkv Wqkv^T, then LayerNorm backward + residual
             {
-                GemmNT p{w.DQKV, w.Wqb + l * 3 * dd, M, d, 3 * d, 3LL * d, 3LL * d, w.sDQKV, w.sWq};
+                GemmNT p{w.DQKV, w.Wqb + l * wWq, M, d, 3 * d, 3LL * d, 3LL * d, w.sDQKV, w.sWq};
                 EpiScaleF32 epi{w.DU, d, w.sDU, 1.0f};
-                TRY(gemm_nt(p, epi, K, s));
+                TRY(gemm_nt<false>(p, epi, K, s));
             }
             TRY(ln_bwd(sub, oga));
         }
