@@ -29,6 +29,13 @@ def build(force=False):
         subprocess.check_call(["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-shared", "-fPIC",
                                "-Wall", "-Wextra", "-o", tmp] + _SRC + ["-lm"])
         os.replace(tmp, _SO)
+        # the driver of the sanitizer test (tests/test_oracle_sanitize.py builds it again with the
+        # sanitizers on): compiled here too, so that a build covers every C file of this package
+        drv = os.path.join(_HERE, "sanitize_driver.c")
+        exe = os.path.join(os.path.dirname(_SO), "sanitize_driver")
+        subprocess.check_call(["gcc", "-O1", "-ffp-contract=off", "-fopenmp", "-Wall", "-Wextra", "-o",
+                               exe + ".%d.tmp" % os.getpid(), drv] + _SRC + ["-lm"])
+        os.replace(exe + ".%d.tmp" % os.getpid(), exe)
     return _SO
 
 
