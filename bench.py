@@ -31,7 +31,13 @@ BYTES_PER_AVERAGE = 8
 # kernel of known size; profiles/*_hbm_traffic_pmc.md).  Valid only for the kernel source the
 # counters were taken on: keyed by the first 16 hex digits of its SHA-256; null otherwise.
 PMC_SOURCES = ["update.hip", "opt_elem.h", "philox.h"]
-PMC_TRAFFIC = {}
+PMC_TRAFFIC = {
+    # FETCH_SIZE x 2.000 (calibrated on the averaging kernel, which reads exactly 4 B x K x P) + WRITE_SIZE x 1.000
+    # (calibrated on broadcast_rows_kernel / fill_zero_kernel), median over the launches of a run
+    "flat350m+fuse_gradient": {"sha256_16": "89d287d57b69beea", "bytes": 268.8005e9},   # algorithmic 268.8e9
+    "flat60m+fuse_gradient": {"sha256_16": "89d287d57b69beea", "bytes": 23.0402e9},     # algorithmic 23.04e9
+    "flat60m": {"sha256_16": "89d287d57b69beea", "bytes": 26.8801e9},                   # gradient read from its buffer: 26.88e9
+}
 
 
 def measured_traffic(workload, fused_gradient):
