@@ -26,6 +26,7 @@
 // returns that row when K is a power of two.
 #include "opt_elem.h"
 #include "qsr_internal.h"
+#include "sched_dev.h"
 
 namespace qsr {
 
@@ -34,11 +35,8 @@ constexpr int AVG_KU = 16;
 
 // LDS-staged tile: W wavefronts, RUN x 64 float4 columns (RUN KiB contiguous per row and wavefront)
 template <int KMAX, int W, int RUN>
-__global__ __launch_bounds__(64 * W) void average_rows_tile_kernel(
-    float *__restrict__ buf, int K, long long P4, const DevState *__restrict__ st)
+__device__ __forceinline__ void average_tile_body(float *__restrict__ buf, int K, long long P4, float4 *avg_tile)
 {
-    extern __shared__ float4 avg_tile[];            // [K][RUN * 64]
-    if (st != nullptr && st->h + 1 != st->H) return;   // not the step that completes a round
     constexpr int TC = RUN * 64;
     constexpr int RPW = (KMAX + W - 1) / W;          // rows per wavefront
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -90,6 +88,31 @@ __global__ __launch_bounds__(64 * W) void average_rows_tile_kernel(
             }
         }
     }
+}
+
+// ADVANCE: the launch also closes the iteration.  Every workgroup reads the scheduler state when it
+// starts and takes a ticket when it is done; the one that draws the last ticket knows that all
+// others have read the state, and advances it.
+template <int KMAX, int W, int RUN, bool ADVANCE>
+__global__ __launch_bounds__(64 * W) void average_rows_tile_kernel(
+    float *__restrict__ buf, int K, long long P4, const DevState *st, DevState *st_adv, SchedParams sp)
+{
+    extern __shared__ float4 avg_tile[];            // [K][RUN * 64]
+    const bool act = st == nullptr || st->h + 1 == st->H;   // the step that completes a round
+    if (ADVANCE) {
+        if (act) average_tile_body<KMAX, W, RUN>(buf, K, P4, avg_tile);
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            __threadfence();
+            if (atomicAdd(&st_adv->ticket, 1u) == gridDim.x - 1) {
+                st_adv->ticket = 0;
+                sched_advance(st_adv, sp, -1);
+            }
+        }
+        return;
+    }
+    if (!act) return;
+    average_tile_body<KMAX, W, RUN>(buf, K, P4, avg_tile);
 }
 
 // any K: AVG_KU rows in flight at a time
@@ -145,18 +168,19 @@ static int avg_grid(long long items, int threads)
     return (int)blocks;
 }
 
-template <int KMAX, int W, int RUN>
-static hipError_t launch_tile(float *buf, int K, long long P4, const DevState *st, hipStream_t s)
+template <int KMAX, int W, int RUN, bool ADVANCE>
+static hipError_t launch_tile(float *buf, int K, long long P4, const DevState *st, DevState *st_adv, SchedParams sp,
+                              hipStream_t s)
 {
     const size_t lds = (size_t)K * RUN * 64 * sizeof(float4);
-    static bool raised = false;                       // above the default 64 KiB only for K = 32 x 2 KiB
+    static bool raised = false;                       // above the default only for K = 32 x 2 KiB
     if (lds > 48 * 1024 && !raised) {
-        hipError_t e = hipFuncSetAttribute((const void *)average_rows_tile_kernel<KMAX, W, RUN>,
+        hipError_t e = hipFuncSetAttribute((const void *)average_rows_tile_kernel<KMAX, W, RUN, ADVANCE>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, KMAX * RUN * 64 * (int)sizeof(float4));
         if (e != hipSuccess) return e;
         raised = true;
     }
-    average_rows_tile_kernel<KMAX, W, RUN><<<avg_grid(P4, RUN * 64), 64 * W, lds, s>>>(buf, K, P4, st);
+    average_rows_tile_kernel<KMAX, W, RUN, ADVANCE><<<avg_grid(P4, RUN * 64), 64 * W, lds, s>>>(buf, K, P4, st, st_adv, sp);
     return hipGetLastError();
 }
 
@@ -167,13 +191,26 @@ hipError_t launch_average_rows(float *buf, int K, long long P, const DevState *s
     if ((P & 3) == 0) {
         const long long P4 = P / 4;
         if (P4 > 0x7FFFFFFFll * 64) return hipErrorInvalidValue;
-        if (K <= 16) return launch_tile<16, 8, 1>(buf, K, P4, st, s);
-        if (K <= 32) return launch_tile<32, 2, 2>(buf, K, P4, st, s);
+        if (K <= 16) return launch_tile<16, 8, 1, false>(buf, K, P4, st, nullptr, SchedParams{}, s);
+        if (K <= 32) return launch_tile<32, 2, 2, false>(buf, K, P4, st, nullptr, SchedParams{}, s);
         average_rows_vec4_kernel<<<avg_grid(P4, AVG_THREADS), AVG_THREADS, 0, s>>>(buf, K, P4, st);
     } else {
         average_rows_scalar_kernel<<<avg_grid(P, AVG_THREADS), AVG_THREADS, 0, s>>>(buf, K, P, st);
     }
     return hipGetLastError();
+}
+
+// few workgroups (a ticket each), rows that the tile kernel takes
+bool average_can_advance(int K, long long P)
+{
+    return (P & 3) == 0 && K <= 32 && P / 4 <= 64 * 64;
+}
+
+hipError_t launch_average_rows_advance(float *buf, int K, long long P, DevState *st, SchedParams sp, hipStream_t s)
+{
+    if (!average_can_advance(K, P)) return hipErrorInvalidValue;
+    if (K <= 16) return launch_tile<16, 8, 1, true>(buf, K, P / 4, st, st, sp, s);
+    return launch_tile<32, 2, 2, true>(buf, K, P / 4, st, st, sp, s);
 }
 
 // Alg. 2's initialisation theta_k <- theta_bar^(0): copy src [P] into each of the K rows

@@ -216,15 +216,47 @@ __global__ __launch_bounds__(256) void skinny_bias_kernel(const float *__restric
                 for (int n = 0; n < NMAX; ++n) acc[n] = fma((double)av[u], (double)bv[u][n], acc[n]);
             }
     }
-    double mine = 0.0;
+    // Sum over the 64 lanes, NMAX = 16 columns at once: at each of the first four exchange steps a
+    // lane keeps half of its columns and hands the other half to its partner (which keeps those), so
+    // the values to exchange halve from step to step (8 + 4 + 2 + 1 exchanges, then two plain steps on
+    // the one value left: 17 instead of 16 x 6).  Lane l ends up with the sum of column
+    // 8 (l/32 % 2) + 4 (l/16 % 2) + 2 (l/8 % 2) + l/4 % 2.  A fixed order.
+    static_assert(NMAX == 16, "the exchange pattern is written for 16 columns");
+    double v8[8], v4[4], v2[2];
+    {
+        const bool up = (lane & 32) != 0;
 #pragma unroll
-    for (int n = 0; n < NMAX; ++n) {
-        double v = acc[n];
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-        if (lane == n) mine = v;
+        for (int j = 0; j < 8; ++j) {
+            const double keep = up ? acc[j + 8] : acc[j], send = up ? acc[j] : acc[j + 8];
+            v8[j] = keep + __shfl_xor(send, 32, 64);
+        }
     }
-    if (lane < N) C[k * sC + (long long)row * N + lane] = mine + (double)bias[k * sBias + lane];
+    {
+        const bool up = (lane & 16) != 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const double keep = up ? v8[j + 4] : v8[j], send = up ? v8[j] : v8[j + 4];
+            v4[j] = keep + __shfl_xor(send, 16, 64);
+        }
+    }
+    {
+        const bool up = (lane & 8) != 0;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const double keep = up ? v4[j + 2] : v4[j], send = up ? v4[j] : v4[j + 2];
+            v2[j] = keep + __shfl_xor(send, 8, 64);
+        }
+    }
+    double mine;
+    {
+        const bool up = (lane & 4) != 0;
+        const double keep = up ? v2[1] : v2[0], send = up ? v2[0] : v2[1];
+        mine = keep + __shfl_xor(send, 4, 64);
+    }
+    mine += __shfl_xor(mine, 2, 64);
+    mine += __shfl_xor(mine, 1, 64);
+    const int col = ((lane >> 5) & 1) * 8 + ((lane >> 4) & 1) * 4 + ((lane >> 3) & 1) * 2 + ((lane >> 2) & 1);
+    if ((lane & 3) == 0 && col < N) C[k * sC + (long long)row * N + col] = mine + (double)bias[k * sBias + col];
 }
 
 hipError_t launch_mlp2_grad(const ModelDims &d, const float *theta, float *g, const float *means,

@@ -428,10 +428,11 @@ extern "C" int qsr_init(const qsr_config *cfg, float *params, float *grads, floa
     c->t_host = 0; c->need_sync_call = false; c->timing = false; c->capturing = false;
     c->graph_exec = nullptr;
     // Iterations per captured graph: several where an iteration is a handful of short launches.
-    // Large problems are never replayed from a graph: their launch cost does not matter, and
-    // enqueued one by one an averaging kernel is launched only where the mirror says a round ends,
-    // while a graph has to hold a launch in every iteration for the device to skip.
-    c->graph_iters = (cfg->model == QSR_MODEL_RESMLP || (long long)cfg->K * cfg->P >= (1ll << 24)) ? 0 : 8;
+    // Larger problems are never replayed from a graph: replaying did not shorten their iterations
+    // (timed: only the least-squares workload gained), and enqueued one by one an averaging kernel is
+    // launched only where the mirror says a round ends, while a graph has to hold a launch in every
+    // iteration for the device to skip (7 us per iteration for the perceptron's 814 090 parameters).
+    c->graph_iters = (cfg->model == QSR_MODEL_RESMLP || (long long)cfg->K * cfg->P >= (1ll << 20)) ? 0 : 8;
     c->dims = make_dims(cfg);
     rc = init_impl(c, theta0);
     c->cfg.milestones = nullptr;
@@ -576,6 +577,14 @@ extern "C" int qsr_maybe_sync(qsr_ctx *c)
     if (!c->need_sync_call) return QSR_ESTATE;
     const bool all = c->capturing;
     const bool sync_now = mirror_sync_now(c);
+    // Replayed iterations of small problems: the averaging launch, which a graph holds in every
+    // iteration, also closes the iteration (one launch less where a launch is a third of the work)
+    if (all && !c->cfg.parallel && !c->cfg.fuse_sync && !c->cfg.average_state && average_can_advance(c->cfg.K, c->cfg.P)) {
+        HIP_TRY(launch_average_rows_advance(c->params, c->cfg.K, c->cfg.P, c->d_state, c->sp, c->stream));
+        mirror_advance(c);
+        c->need_sync_call = false;
+        return QSR_OK;
+    }
     // Parallel OPT keeps the workers identical, the fused form has averaged in qsr_local_step already
     if (!c->cfg.parallel && !c->cfg.fuse_sync && (all || sync_now)) {
         Bracket br(c, 2);

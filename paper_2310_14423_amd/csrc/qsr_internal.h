@@ -15,7 +15,7 @@ struct DevState {
     long long h;        // local steps done in the current round
     long long H;        // synchronization period of the current round (0 once t == T)
     int mismatch;       // set (and kept) when the host's mirror of the schedule expected another decision
-    int pad;
+    unsigned ticket;    // workgroups of an averaging launch that have finished (that launch then closes the iteration)
 };
 
 // Per-iteration scalars of the OPT update, prepared on the host in double precision and
@@ -101,6 +101,11 @@ int clip_static_setup(double **out);
 // mean over the K rows of buf [K][P], written to all rows; with st != nullptr the launch acts only
 // if the iteration in progress completes its round (st->h + 1 == st->H, read before the advance)
 hipError_t launch_average_rows(float *buf, int K, long long P, const DevState *st, hipStream_t s);
+// The same launch also closing the iteration: the workgroup that finishes last advances the scheduler
+// (sched_advance, no mirror check), which saves the one-thread launch behind it where an iteration
+// is a handful of microsecond kernels.  Only for launches of few workgroups: average_can_advance.
+bool average_can_advance(int K, long long P);
+hipError_t launch_average_rows_advance(float *buf, int K, long long P, DevState *st, SchedParams sp, hipStream_t s);
 
 hipError_t launch_broadcast_rows(float *dst, const float *src, int K, long long P, hipStream_t s);
 hipError_t launch_fill_zero(float *dst, long long n, hipStream_t s);
