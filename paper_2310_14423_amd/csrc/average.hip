@@ -7,17 +7,22 @@
 // 2 KiB contiguous from each), and after a barrier every lane adds up its columns from LDS and
 // the wavefront writes the mean back to the rows it loaded.  Any K: each lane owns four
 // consecutive parameters and walks the K rows in registers, 16 in flight at a time.
-// Timed on MI355X (HBM3E, 8 TB/s), array inside one allocation:
-//                                  K = 16, P = 60e6   K = 32, P = 60e6   K = 32, P = 350e6
-//   rows in registers, 64 threads      5.72-5.78 TB/s     5.34-5.40          5.25-5.32
-//   LDS tile, 8 wavefronts x 1 KiB     5.97               5.55               5.51
-//   LDS tile, 2 wavefronts x 2 KiB     5.69               5.77               5.59
+// Timed on MI355X (HBM3E, 8 TB/s), the other three state arrays of a run allocated beside it, three
+// passes each:
+//                                       K = 16, P = 60e6     K = 32, P = 350e6
+//   rows in registers, 64 threads         5.68-5.81 TB/s       5.27-5.31
+//   rows in registers, 256 threads        5.55-5.58            5.18-5.22
+//   LDS tile, 8 wavefronts x 1 KiB        5.79-5.80            5.49-5.50
+//   LDS tile, 2 wavefronts x 2 KiB        5.64-5.70            5.58-5.59
+//   LDS tile, 4 wavefronts x 2 KiB        5.61-5.64            5.52
 //   K split over the lanes of a
 //   wavefront, partial sums combined
-//   with shuffles                      5.05               4.89               5.12
-// (a plain copy kernel reaches 5.77 TB/s on this chip).  The LDS tile wins because a wavefront
-// touches fewer rows with longer runs; the shuffle variant loses because a wavefront then reads
-// only 256 B from each row.
+//   with shuffles                         5.05-5.06            5.12-5.13
+// (a plain copy kernel reaches 5.77 TB/s on this chip).  At K = 16 the register and the LDS variants
+// are equal within the spread of a pass; at K = 32 the LDS tile gains 5 % because a wavefront touches
+// fewer rows with longer runs (32 row loads in flight per lane cost the register variant its
+// occupancy).  The shuffle variant loses because a wavefront then reads only 256 B from each row.
+// Chosen: 8 x 1 KiB up to K = 16, 2 x 2 KiB up to K = 32.
 //
 // In every variant the sum runs over k in ascending order in fp32 with an error-free
 // transformation of every addition (the rounding error of each partial sum is carried in a

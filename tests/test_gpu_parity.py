@@ -404,8 +404,18 @@ RTOL_BF16 = 2e-2      # bf16 GEMM inputs, fp32 accumulation
 # 64-entry LayerNorm bias gradient summed over 100 tokens; 0.40 % for the value and output
 # projections and 0.72 % for the query and key projections of the attention sub-block (their
 # errors are Gaussian: kurtosis 3.03 over 590 000 entries).
-RMS_BF16_MLP = 8e-3
+# Hence: weight matrices of the MLP model 0.6 %, its short vectors (biases, LayerNorm parameters: 64 to
+# 3072 entries, whose rms error is itself an estimate from few samples) 0.8 %, everything 1 % where the
+# gradient passes through the attention core.
+RMS_BF16_MLP = 6e-3
+RMS_BF16_MLP_VEC = 8e-3
 RMS_BF16_ATTN = 1e-2
+
+
+def _rms_tol(w, name):
+    if w.get("n_heads", 0):
+        return RMS_BF16_ATTN
+    return RMS_BF16_MLP if name[0] == "W" else RMS_BF16_MLP_VEC
 
 
 def _assert_groups_close(w, gpu, orc, what, tail=None, weights_only_tail=False, rms_tol=None):
@@ -415,8 +425,6 @@ def _assert_groups_close(w, gpu, orc, what, tail=None, weights_only_tail=False, 
     rounding errors, measured here against the scale of the query bias's gradient.  With sequences
     of one token every query and key gradient is exactly zero (the only probability is 1): measured
     against the value projection's."""
-    if rms_tol is None:
-        rms_tol = RMS_BF16_ATTN if w.get("n_heads", 0) else RMS_BF16_MLP
     groups = dict(_resmlp_groups(w))
     rms_of = lambda nm: float(np.sqrt(np.mean(orc[..., groups[nm]] ** 2)))
     worst = (0.0, "")
@@ -431,7 +439,8 @@ def _assert_groups_close(w, gpu, orc, what, tail=None, weights_only_tail=False, 
         if rms is not None:        # exact value zero: the element bound against the borrowed scale is the check
             continue
         r = rms_error_ratio(gpu[..., sl], orc[..., sl])
-        assert r <= rms_tol, "%s %s: rms error %.3e of the group's rms (bound %.1e)" % (what, name, r, rms_tol)
+        tol = rms_tol if rms_tol is not None else _rms_tol(w, name)
+        assert r <= tol, "%s %s: rms error %.3e of the group's rms (bound %.1e)" % (what, name, r, tol)
         worst = max(worst, (r, name))
     print("%s: largest rms error of a group %.3e of its rms (%s)" % (what, worst[0], worst[1]))
     return worst
@@ -778,7 +787,7 @@ def test_resmlp_short_run():
     th0 = workloads.theta0(w).astype(np.float64)
     for name, sl in _resmlp_groups(w):
         assert_params_close(p[:, sl], orc.theta[:, sl], rtol=RTOL_BF16, what="resmlp params %s" % name)
-        assert rms_error_ratio(p[:, sl], orc.theta[:, sl]) <= RMS_BF16_MLP, name
+        assert rms_error_ratio(p[:, sl], orc.theta[:, sl]) <= _rms_tol(w, name), name
         # and the distance travelled from the initial parameters, which is what the run computed
         moved = orc.theta[:, sl] - th0[None, sl]
         r = rms_error_ratio(p[:, sl] - th0[None, sl], moved)
