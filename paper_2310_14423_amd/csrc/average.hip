@@ -149,18 +149,45 @@ __global__ __launch_bounds__(AVG_THREADS) void average_rows_vec4_kernel(
     }
 }
 
-// rows whose length is not a multiple of 4 are not 16-byte aligned: one element per lane
-__global__ __launch_bounds__(AVG_THREADS) void average_rows_scalar_kernel(
+// rows whose length is not a multiple of 4 are not 16-byte aligned: two elements per lane where the
+// length is even, else one; AVG_KU rows in flight at a time (one load per addition, as it was first
+// written, ran the perceptron's 8 x 814 090 parameters in 17.7 us: every load waited for the one before)
+template <int V>
+__global__ __launch_bounds__(AVG_THREADS) void average_rows_narrow_kernel(
     float *__restrict__ buf, int K, long long P, const DevState *__restrict__ st)
 {
     if (st != nullptr && st->h + 1 != st->H) return;
     const float fK = (float)K;
+    const long long PV = P / V;
     const long long stride = (long long)gridDim.x * AVG_THREADS;
-    for (long long i = (long long)blockIdx.x * AVG_THREADS + threadIdx.x; i < P; i += stride) {
-        float acc = 0.f, cmp = 0.f;
-        for (int k = 0; k < K; ++k) add_comp(acc, cmp, buf[(long long)k * P + i]);
-        float mean = (acc + cmp) / fK;
-        for (int k = 0; k < K; ++k) buf[(long long)k * P + i] = mean;
+    for (long long i = (long long)blockIdx.x * AVG_THREADS + threadIdx.x; i < PV; i += stride) {
+        float acc[V], cmp[V];
+#pragma unroll
+        for (int v = 0; v < V; ++v) { acc[v] = 0.f; cmp[v] = 0.f; }
+        for (int k0 = 0; k0 < K; k0 += AVG_KU) {
+            float r[AVG_KU][V];
+#pragma unroll
+            for (int u = 0; u < AVG_KU; ++u)
+                if (k0 + u < K) {
+                    const float *src = buf + (long long)(k0 + u) * P + i * V;
+                    if (V == 2) { const float2 t = *(const float2 *)src; r[u][0] = t.x; r[u][V - 1] = t.y; }
+                    else r[u][0] = *src;
+                }
+#pragma unroll
+            for (int u = 0; u < AVG_KU; ++u)
+                if (k0 + u < K) {
+#pragma unroll
+                    for (int v = 0; v < V; ++v) add_comp(acc[v], cmp[v], r[u][v]);
+                }
+        }
+        float mean[V];
+#pragma unroll
+        for (int v = 0; v < V; ++v) mean[v] = (acc[v] + cmp[v]) / fK;
+        for (int k = 0; k < K; ++k) {
+            float *dst = buf + (long long)k * P + i * V;
+            if (V == 2) *(float2 *)dst = make_float2(mean[0], mean[V - 1]);
+            else *dst = mean[0];
+        }
     }
 }
 
@@ -200,7 +227,8 @@ hipError_t launch_average_rows(float *buf, int K, long long P, const DevState *s
         if (K <= 32) return launch_tile<32, 2, 2, false>(buf, K, P4, st, nullptr, SchedParams{}, s);
         average_rows_vec4_kernel<<<avg_grid(P4, AVG_THREADS), AVG_THREADS, 0, s>>>(buf, K, P4, st);
     } else {
-        average_rows_scalar_kernel<<<avg_grid(P, AVG_THREADS), AVG_THREADS, 0, s>>>(buf, K, P, st);
+        if ((P & 1) == 0) average_rows_narrow_kernel<2><<<avg_grid(P / 2, AVG_THREADS), AVG_THREADS, 0, s>>>(buf, K, P, st);
+        else average_rows_narrow_kernel<1><<<avg_grid(P, AVG_THREADS), AVG_THREADS, 0, s>>>(buf, K, P, st);
     }
     return hipGetLastError();
 }

@@ -39,7 +39,10 @@ struct qsr_ctx {
     void *workspace;
     size_t workspace_bytes;
     // library-owned device memory
-    DevState *d_state;
+    DevState *d_state;       // two copies; `cur` is the one this iteration's kernels read (see fold_tick)
+    int cur;
+    bool fold_tick;          // the update kernel takes the scheduler's step on iterations that end no round
+    bool ticked;             // ... and has done so for the local step whose qsr_maybe_sync is pending
     double *d_eta;
     StepScalars *d_scal;
     long long *d_log_t, *d_log_H;
@@ -69,6 +72,9 @@ struct qsr_ctx {
     hipGraphExec_t graph_exec;
     int graph_iters;
 };
+
+static inline DevState *st_cur(qsr_ctx *c) { return c->d_state + c->cur; }
+
 
 // ------------------------------------------------------------------------------------------
 // configuration
@@ -360,7 +366,8 @@ static int init_impl(qsr_ctx *c, const float *theta0)
         if (rc != QSR_OK) return rc;
     }
 
-    HIP_TRY(hipMalloc((void **)&c->d_state, sizeof(DevState)));
+    HIP_TRY(hipMalloc((void **)&c->d_state, 2 * sizeof(DevState)));
+    HIP_TRY(hipMemset(c->d_state, 0, 2 * sizeof(DevState)));
     HIP_TRY(hipMalloc((void **)&c->d_eta, T * sizeof(double)));
     HIP_TRY(hipMalloc((void **)&c->d_scal, T * sizeof(StepScalars)));
     HIP_TRY(hipMalloc((void **)&c->d_log_t, T * sizeof(long long)));
@@ -388,7 +395,7 @@ static int init_impl(qsr_ctx *c, const float *theta0)
     HIP_TRY(launch_fill_zero(c->state0, n, c->stream));
     if (c->state1) HIP_TRY(launch_fill_zero(c->state1, n, c->stream));
     HIP_TRY(launch_fill_zero(c->d_loss, cfg.K, c->stream));
-    HIP_TRY(launch_sched_init(c->d_state, c->sp, c->stream));
+    HIP_TRY(launch_sched_init(st_cur(c), c->sp, c->stream));
     HIP_TRY(hipStreamSynchronize(c->stream));
     mirror_reset(c, 0, 0, 0, host_get_H(c->sp, c->eta.data(), 0));
     return QSR_OK;
@@ -433,6 +440,11 @@ extern "C" int qsr_init(const qsr_config *cfg, float *params, float *grads, floa
     // launched only where the mirror says a round ends, while a graph has to hold a launch in every
     // iteration for the device to skip (7 us per iteration for the perceptron's 814 090 parameters).
     c->graph_iters = (cfg->model == QSR_MODEL_RESMLP || (long long)cfg->K * cfg->P >= (1ll << 20)) ? 0 : 8;
+    // Contexts whose iterations are never replayed from a graph (a recorded launch could not be handed the
+    // copy of the scheduler state that alternates from iteration to iteration): the update kernel takes
+    // the scheduler's step on the iterations that end no round, and no scheduler kernel is launched there.
+    c->cur = 0; c->ticked = false;
+    c->fold_tick = c->graph_iters == 0 && !cfg->parallel && (cfg->clip_norm <= 0.0 || (cfg->P & 3) == 0);
     c->dims = make_dims(cfg);
     rc = init_impl(c, theta0);
     c->cfg.milestones = nullptr;
@@ -493,19 +505,19 @@ extern "C" int qsr_local_step(qsr_ctx *c)
         switch (cfg.model) {
         case QSR_MODEL_NOISE:
             HIP_TRY(launch_noise_grad(c->grads, cfg.K, cfg.P, (float)cfg.grad_sigma, cfg.seed,
-                                      c->d_state, c->stream));
+                                      st_cur(c), c->stream));
             break;
         case QSR_MODEL_LINREG:
             HIP_TRY(launch_linreg_grad(c->dims, c->params, c->grads, c->model_const, c->workspace,
-                                       c->d_loss, c->d_state, c->stream));
+                                       c->d_loss, st_cur(c), c->stream));
             break;
         case QSR_MODEL_MLP2:
             HIP_TRY(launch_mlp2_grad(c->dims, c->params, c->grads, c->model_const, c->workspace,
-                                     c->d_loss, c->d_state, c->stream));
+                                     c->d_loss, st_cur(c), c->stream));
             break;
         case QSR_MODEL_RESMLP:
             HIP_TRY(launch_resmlp_grad(c->dims, c->params, c->grads, c->model_const, c->workspace,
-                                       c->d_loss, c->d_state, c->stream));
+                                       c->d_loss, st_cur(c), c->stream));
             break;
         default: return QSR_EINVAL;
         }
@@ -524,6 +536,7 @@ extern "C" int qsr_local_step(qsr_ctx *c)
     const bool all = c->capturing;
     const bool sync_now = mirror_sync_now(c);
     const bool fused = cfg.fuse_sync != 0;
+    DevState *st_next = (c->fold_tick && !all && !sync_now) ? c->d_state + (c->cur ^ 1) : nullptr;
     if (!fused || all || !sync_now) {                   // OPT for all K workers at once
         Bracket br(c, 1);
         if (br.rc != QSR_OK) return br.rc;
@@ -531,24 +544,25 @@ extern "C" int qsr_local_step(qsr_ctx *c)
             HIP_TRY(launch_clip_coef(c->grads, cfg.K, cfg.P, (float)cfg.clip_norm, c->d_clip_part,
                                      c->d_clip_coef, c->d_clip_coef + cfg.K, c->stream));
         if (cfg.fuse_gradient && cfg.opt == QSR_OPT_SGDM)   // Eq. (1) and OPT in one pass (noise model)
-            HIP_TRY(launch_update_sgdm_noise(c->params, c->grads, c->state0, cfg.K, cfg.P, c->d_state, c->d_scal,
+            HIP_TRY(launch_update_sgdm_noise(c->params, c->grads, c->state0, cfg.K, cfg.P, st_cur(c), c->d_scal,
                                              (float)cfg.momentum, (float)cfg.weight_decay, (float)cfg.grad_sigma,
-                                             cfg.seed, cfg.fuse_gradient == 1, c->stream));
+                                             cfg.seed, cfg.fuse_gradient == 1, c->stream, st_next, &c->sp));
         else if (cfg.fuse_gradient)
-            HIP_TRY(launch_update_adamw_noise(c->params, c->grads, c->state0, c->state1, cfg.K, cfg.P, c->d_state,
+            HIP_TRY(launch_update_adamw_noise(c->params, c->grads, c->state0, c->state1, cfg.K, cfg.P, st_cur(c),
                                               c->d_scal, (float)(1.0 - cfg.beta1), (float)(1.0 - cfg.beta2),
                                               (float)cfg.eps, (float)cfg.grad_sigma, cfg.seed, cfg.fuse_gradient == 1,
-                                              c->stream));
+                                              c->stream, st_next, &c->sp));
         else if (cfg.opt == QSR_OPT_SGDM)
-            HIP_TRY(launch_update_sgdm(c->params, c->grads, c->state0, cfg.K, cfg.P, c->d_state, c->d_scal,
+            HIP_TRY(launch_update_sgdm(c->params, c->grads, c->state0, cfg.K, cfg.P, st_cur(c), c->d_scal,
                                        (float)cfg.momentum, (float)cfg.weight_decay, fused, c->d_clip_coef,
-                                       c->stream));
+                                       c->stream, st_next, &c->sp));
         else
-            HIP_TRY(launch_update_adamw(c->params, c->grads, c->state0, c->state1, cfg.K, cfg.P, c->d_state,
+            HIP_TRY(launch_update_adamw(c->params, c->grads, c->state0, c->state1, cfg.K, cfg.P, st_cur(c),
                                         c->d_scal, (float)(1.0 - cfg.beta1), (float)(1.0 - cfg.beta2),
-                                        (float)cfg.eps, fused, c->d_clip_coef, c->stream));
+                                        (float)cfg.eps, fused, c->d_clip_coef, c->stream, st_next, &c->sp));
         int rc = br.close(c->t_host);
         if (rc != QSR_OK) return rc;
+        if (st_next) { c->cur ^= 1; c->ticked = true; }    // the advanced state is in the other copy now
     }
     if (fused && (all || sync_now)) {                   // the round's last step: OPT and All-Reduce in one pass
         Bracket br(c, 2);                               // timed like an averaging launch
@@ -557,10 +571,10 @@ extern "C" int qsr_local_step(qsr_ctx *c)
             HIP_TRY(launch_clip_coef(c->grads, cfg.K, cfg.P, (float)cfg.clip_norm, c->d_clip_part,
                                      c->d_clip_coef, c->d_clip_coef + cfg.K, c->stream));
         if (cfg.opt == QSR_OPT_SGDM)
-            HIP_TRY(launch_update_sgdm_sync(c->params, c->grads, c->state0, cfg.K, cfg.P, c->d_state, c->d_scal,
+            HIP_TRY(launch_update_sgdm_sync(c->params, c->grads, c->state0, cfg.K, cfg.P, st_cur(c), c->d_scal,
                                             (float)cfg.momentum, (float)cfg.weight_decay, c->d_clip_coef, c->stream));
         else
-            HIP_TRY(launch_update_adamw_sync(c->params, c->grads, c->state0, c->state1, cfg.K, cfg.P, c->d_state,
+            HIP_TRY(launch_update_adamw_sync(c->params, c->grads, c->state0, c->state1, cfg.K, cfg.P, st_cur(c),
                                              c->d_scal, (float)(1.0 - cfg.beta1), (float)(1.0 - cfg.beta2),
                                              (float)cfg.eps, c->d_clip_coef, c->stream));
         int rc = br.close(c->t_host + 1);
@@ -575,12 +589,18 @@ extern "C" int qsr_maybe_sync(qsr_ctx *c)
 {
     if (!c) return QSR_EINVAL;
     if (!c->need_sync_call) return QSR_ESTATE;
+    if (c->ticked) {                     // no round ends here and the update kernel has advanced the scheduler
+        mirror_advance(c);
+        c->ticked = false;
+        c->need_sync_call = false;
+        return QSR_OK;
+    }
     const bool all = c->capturing;
     const bool sync_now = mirror_sync_now(c);
     // Replayed iterations of small problems: the averaging launch, which a graph holds in every
     // iteration, also closes the iteration (one launch less where a launch is a third of the work)
     if (all && !c->cfg.parallel && !c->cfg.fuse_sync && !c->cfg.average_state && average_can_advance(c->cfg.K, c->cfg.P)) {
-        HIP_TRY(launch_average_rows_advance(c->params, c->cfg.K, c->cfg.P, c->d_state, c->sp, c->stream));
+        HIP_TRY(launch_average_rows_advance(c->params, c->cfg.K, c->cfg.P, st_cur(c), c->sp, c->stream));
         mirror_advance(c);
         c->need_sync_call = false;
         return QSR_OK;
@@ -589,15 +609,15 @@ extern "C" int qsr_maybe_sync(qsr_ctx *c)
     if (!c->cfg.parallel && !c->cfg.fuse_sync && (all || sync_now)) {
         Bracket br(c, 2);
         if (br.rc != QSR_OK) return br.rc;
-        HIP_TRY(launch_average_rows(c->params, c->cfg.K, c->cfg.P, c->d_state, c->stream));
+        HIP_TRY(launch_average_rows(c->params, c->cfg.K, c->cfg.P, st_cur(c), c->stream));
         int rc = br.close(c->t_host);
         if (rc != QSR_OK) return rc;
         if (c->cfg.average_state) {          // same device-side decision, taken before the scheduler advances
-            HIP_TRY(launch_average_rows(c->state0, c->cfg.K, c->cfg.P, c->d_state, c->stream));
-            if (c->state1) HIP_TRY(launch_average_rows(c->state1, c->cfg.K, c->cfg.P, c->d_state, c->stream));
+            HIP_TRY(launch_average_rows(c->state0, c->cfg.K, c->cfg.P, st_cur(c), c->stream));
+            if (c->state1) HIP_TRY(launch_average_rows(c->state1, c->cfg.K, c->cfg.P, st_cur(c), c->stream));
         }
     }
-    HIP_TRY(launch_sched_advance(c->d_state, c->sp, all ? -1 : (sync_now ? 1 : 0), c->stream));
+    HIP_TRY(launch_sched_advance(st_cur(c), c->sp, all ? -1 : (sync_now ? 1 : 0), c->stream));
     mirror_advance(c);
     c->need_sync_call = false;
     return QSR_OK;
@@ -660,14 +680,15 @@ extern "C" int qsr_run(qsr_ctx *c, int64_t n)
 }
 
 // Device scheduler state to the host.  Between qsr_local_step and its qsr_maybe_sync the device has
-// not advanced its counters yet (the advance is the last launch of an iteration): the step just
-// enqueued is added here, so that callers see t and h count it, as the protocol says.
+// not advanced its counters yet where the advance is the last launch of an iteration: the step just
+// enqueued is added here, so that callers see t and h count it, as the protocol says.  (Where the
+// update kernel has taken the step itself, the counters already include it.)
 static int fetch_state(qsr_ctx *c)
 {
-    HIP_TRY(hipMemcpyAsync(c->h_state, c->d_state, sizeof(DevState), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(hipMemcpyAsync(c->h_state, st_cur(c), sizeof(DevState), hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(hipStreamSynchronize(c->stream));
     if (c->h_state->mismatch) return QSR_EMIRROR;
-    if (c->need_sync_call) { c->h_state->t += 1; c->h_state->h += 1; }
+    if (c->need_sync_call && !c->ticked) { c->h_state->t += 1; c->h_state->h += 1; }
     return QSR_OK;
 }
 
@@ -739,7 +760,7 @@ extern "C" int qsr_set_state(qsr_ctx *c, const int64_t state[4])
     if (t < 0 || t > T || s < 0 || s > t || h < 0 || h > t) return QSR_EINVAL;
     if (t == T ? (H != 0 || h != 0) : (H < 1 || h >= H || H - h > T - t)) return QSR_EINVAL;
     if (c->need_sync_call) return QSR_ESTATE;
-    HIP_TRY(launch_sched_set(c->d_state, c->sp, t, s, h, H, c->stream));
+    HIP_TRY(launch_sched_set(st_cur(c), c->sp, t, s, h, H, c->stream));
     c->t_host = t;
     mirror_reset(c, t, s, h, H);
     return QSR_OK;
@@ -748,9 +769,10 @@ extern "C" int qsr_set_state(qsr_ctx *c, const int64_t state[4])
 extern "C" int qsr_restart(qsr_ctx *c)
 {
     if (!c) return QSR_EINVAL;
-    HIP_TRY(launch_sched_init(c->d_state, c->sp, c->stream));
+    HIP_TRY(launch_sched_init(st_cur(c), c->sp, c->stream));
     c->t_host = 0;
     c->need_sync_call = false;
+    c->ticked = false;
     mirror_reset(c, 0, 0, 0, host_get_H(c->sp, c->eta.data(), 0));
     return QSR_OK;
 }

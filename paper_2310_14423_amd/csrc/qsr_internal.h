@@ -67,20 +67,27 @@ hipError_t launch_sched_advance(DevState *st, SchedParams sp, int expect_sync, h
 
 // fused_sync: leave the step that completes a round to launch_update_*_sync.
 // row_coef: K clipping factors the gradient rows are multiplied by as they are read, or nullptr.
+// st_next != nullptr (with sp; not for clipped rows whose length is not a multiple of 4): the kernel also
+// takes the scheduler's end-of-iteration step, on an iteration that does not end a round: the advanced
+// state goes to *st_next, a second copy that no kernel of this iteration reads.
 hipError_t launch_update_sgdm(float *theta, float *g, float *buf, int K, long long P,
                               const DevState *st, const StepScalars *sc, float mu, float lambda,
-                              bool fused_sync, const float *row_coef, hipStream_t s);
+                              bool fused_sync, const float *row_coef, hipStream_t s,
+                              DevState *st_next = nullptr, const SchedParams *sp = nullptr);
 hipError_t launch_update_adamw(float *theta, float *g, float *m, float *v, int K, long long P,
                                const DevState *st, const StepScalars *sc, float c1, float c2,
-                               float eps, bool fused_sync, const float *row_coef, hipStream_t s);
+                               float eps, bool fused_sync, const float *row_coef, hipStream_t s,
+                               DevState *st_next = nullptr, const SchedParams *sp = nullptr);
 // the same updates with the optimizer-only workloads' gradient g = sigma * N(0,1) drawn inside the
 // kernel (and written to g if store_g); P must be a multiple of 4
 hipError_t launch_update_sgdm_noise(float *theta, float *g, float *buf, int K, long long P, const DevState *st,
                                     const StepScalars *sc, float mu, float lambda, float sigma, uint64_t seed,
-                                    bool store_g, hipStream_t s);
+                                    bool store_g, hipStream_t s, DevState *st_next = nullptr,
+                                    const SchedParams *sp = nullptr);
 hipError_t launch_update_adamw_noise(float *theta, float *g, float *m, float *v, int K, long long P,
                                      const DevState *st, const StepScalars *sc, float c1, float c2, float eps,
-                                     float sigma, uint64_t seed, bool store_g, hipStream_t s);
+                                     float sigma, uint64_t seed, bool store_g, hipStream_t s,
+                                     DevState *st_next = nullptr, const SchedParams *sp = nullptr);
 // update + averaging in one pass over the [K][P] buffers, only on the step that completes a round
 hipError_t launch_update_sgdm_sync(float *theta, const float *g, float *buf, int K, long long P,
                                    const DevState *st, const StepScalars *sc, float mu, float lambda,

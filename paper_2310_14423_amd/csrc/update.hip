@@ -8,6 +8,7 @@
 // 5.0-5.1 TB/s for 256-thread blocks in a capped persistent grid and 5.77 TB/s for a plain
 // copy kernel; non-temporal loads and stores were each worth 3-5 %.
 #include "opt_elem.h"
+#include "sched_dev.h"
 #include "philox.h"
 #include "qsr_internal.h"
 
@@ -34,13 +35,27 @@ __device__ __forceinline__ void stg_nt(float4 *p, float4 v) { st_nt4(p, v); }
 // the kernel moves 12 B read + 12 B written = 24 B per element.
 struct NoiseDraw { float sigma; uint64_t seed; int store; };
 
+// The scheduler's end-of-iteration step taken by the update kernel itself, on an iteration that
+// does not end a round (the host's mirror says so; a disagreement is latched as a mismatch): the
+// state is read from the copy every kernel of this iteration reads and the advanced state written
+// to the other copy, which the next iteration's kernels are handed.  No kernel of this iteration
+// reads that one, so no ordering between workgroups is needed, and the one-thread scheduler launch
+// (4 us of dispatch latency, 3 % of a perceptron iteration) goes away.
+__device__ __forceinline__ void tick_into(const DevState *st, DevState *st_next, const SchedParams &sp)
+{
+    DevState nx = *st;
+    sched_advance(&nx, sp, 0);
+    *st_next = nx;
+}
+
 template <bool CLIP, bool NOISE>
 __global__ __launch_bounds__(UPD_THREADS) void update_adamw_kernel(
     float4 *__restrict__ theta, float4 *__restrict__ g, float4 *__restrict__ m,
     float4 *__restrict__ v, long long n4, long long n, const DevState *__restrict__ st,
     const StepScalars *__restrict__ sc, float c1, float c2, float eps, int fused_sync,
-    const float *__restrict__ row_coef, NoiseDraw nd)
+    const float *__restrict__ row_coef, NoiseDraw nd, DevState *__restrict__ st_next, SchedParams sp)
 {
+    if (st_next != nullptr && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) tick_into(st, st_next, sp);
     if (fused_sync && st->h + 1 == st->H) return;
     float gs = 1.0f;
     if (CLIP || NOISE) {
@@ -108,8 +123,9 @@ __global__ __launch_bounds__(UPD_THREADS) void update_sgdm_kernel(
     float4 *__restrict__ theta, float4 *__restrict__ g, float4 *__restrict__ buf,
     long long n4, long long n, const DevState *__restrict__ st,
     const StepScalars *__restrict__ sc, float mu, float lambda, int fused_sync,
-    const float *__restrict__ row_coef, NoiseDraw nd)
+    const float *__restrict__ row_coef, NoiseDraw nd, DevState *__restrict__ st_next, SchedParams sp)
 {
+    if (st_next != nullptr && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) tick_into(st, st_next, sp);
     if (fused_sync && st->h + 1 == st->H) return;
     float gs = 1.0f;
     if (CLIP || NOISE) {
@@ -372,17 +388,19 @@ hipError_t launch_update_sgdm_sync(float *theta, const float *g, float *buf, int
 // row_coef != nullptr: clipped update, one grid row per worker
 hipError_t launch_update_adamw(float *theta, float *g, float *m, float *v, int K, long long P,
                                const DevState *st, const StepScalars *sc, float c1, float c2,
-                               float eps, bool fused_sync, const float *row_coef, hipStream_t s)
+                               float eps, bool fused_sync, const float *row_coef, hipStream_t s, DevState *st_next,
+                               const SchedParams *sp)
 {
+    const SchedParams spv = sp ? *sp : SchedParams{};
     const int fs = fused_sync ? 1 : 0;
     const NoiseDraw none{0.f, 0, 0};
     if (row_coef == nullptr) {
         const long long n = (long long)K * P, n4 = n / 4;
         update_adamw_kernel<false, false><<<update_grid(n4), UPD_THREADS, 0, s>>>(
-            (float4 *)theta, (float4 *)g, (float4 *)m, (float4 *)v, n4, n, st, sc, c1, c2, eps, fs, nullptr, none);
+            (float4 *)theta, (float4 *)g, (float4 *)m, (float4 *)v, n4, n, st, sc, c1, c2, eps, fs, nullptr, none, st_next, spv);
     } else if ((P & 3) == 0) {
         update_adamw_kernel<true, false><<<dim3((unsigned)update_grid(P / 4), (unsigned)K), UPD_THREADS, 0, s>>>(
-            (float4 *)theta, (float4 *)g, (float4 *)m, (float4 *)v, P / 4, P, st, sc, c1, c2, eps, fs, row_coef, none);
+            (float4 *)theta, (float4 *)g, (float4 *)m, (float4 *)v, P / 4, P, st, sc, c1, c2, eps, fs, row_coef, none, st_next, spv);
     } else {
         update_clip_scalar_kernel<<<dim3((unsigned)sync_grid(P), (unsigned)K), SYNC_THREADS, 0, s>>>(
             theta, g, m, v, P, st, sc, c1, c2, eps, fs, row_coef);
@@ -392,17 +410,19 @@ hipError_t launch_update_adamw(float *theta, float *g, float *m, float *v, int K
 
 hipError_t launch_update_sgdm(float *theta, float *g, float *buf, int K, long long P,
                               const DevState *st, const StepScalars *sc, float mu, float lambda,
-                              bool fused_sync, const float *row_coef, hipStream_t s)
+                              bool fused_sync, const float *row_coef, hipStream_t s, DevState *st_next,
+                              const SchedParams *sp)
 {
+    const SchedParams spv = sp ? *sp : SchedParams{};
     const int fs = fused_sync ? 1 : 0;
     const NoiseDraw none{0.f, 0, 0};
     if (row_coef == nullptr) {
         const long long n = (long long)K * P, n4 = n / 4;
         update_sgdm_kernel<false, false><<<update_grid(n4), UPD_THREADS, 0, s>>>(
-            (float4 *)theta, (float4 *)g, (float4 *)buf, n4, n, st, sc, mu, lambda, fs, nullptr, none);
+            (float4 *)theta, (float4 *)g, (float4 *)buf, n4, n, st, sc, mu, lambda, fs, nullptr, none, st_next, spv);
     } else if ((P & 3) == 0) {
         update_sgdm_kernel<true, false><<<dim3((unsigned)update_grid(P / 4), (unsigned)K), UPD_THREADS, 0, s>>>(
-            (float4 *)theta, (float4 *)g, (float4 *)buf, P / 4, P, st, sc, mu, lambda, fs, row_coef, none);
+            (float4 *)theta, (float4 *)g, (float4 *)buf, P / 4, P, st, sc, mu, lambda, fs, row_coef, none, st_next, spv);
     } else {
         update_clip_scalar_kernel<<<dim3((unsigned)sync_grid(P), (unsigned)K), SYNC_THREADS, 0, s>>>(
             theta, g, buf, nullptr, P, st, sc, mu, lambda, 0.f, fs, row_coef);
@@ -413,23 +433,26 @@ hipError_t launch_update_sgdm(float *theta, float *g, float *buf, int K, long lo
 // The optimizer-only workloads' gradient g = sigma * N(0,1) drawn inside the update (P a multiple of 4)
 hipError_t launch_update_adamw_noise(float *theta, float *g, float *m, float *v, int K, long long P,
                                      const DevState *st, const StepScalars *sc, float c1, float c2, float eps,
-                                     float sigma, uint64_t seed, bool store_g, hipStream_t s)
+                                     float sigma, uint64_t seed, bool store_g, hipStream_t s, DevState *st_next,
+                                     const SchedParams *sp)
 {
     if ((P & 3) != 0) return hipErrorInvalidValue;
+    const SchedParams spv = sp ? *sp : SchedParams{};
     update_adamw_kernel<false, true><<<dim3((unsigned)update_grid(P / 4), (unsigned)K), UPD_THREADS, 0, s>>>(
         (float4 *)theta, (float4 *)g, (float4 *)m, (float4 *)v, P / 4, P, st, sc, c1, c2, eps, 0, nullptr,
-        NoiseDraw{sigma, seed, store_g ? 1 : 0});
+        NoiseDraw{sigma, seed, store_g ? 1 : 0}, st_next, spv);
     return hipGetLastError();
 }
 
 hipError_t launch_update_sgdm_noise(float *theta, float *g, float *buf, int K, long long P, const DevState *st,
                                     const StepScalars *sc, float mu, float lambda, float sigma, uint64_t seed,
-                                    bool store_g, hipStream_t s)
+                                    bool store_g, hipStream_t s, DevState *st_next, const SchedParams *sp)
 {
     if ((P & 3) != 0) return hipErrorInvalidValue;
+    const SchedParams spv = sp ? *sp : SchedParams{};
     update_sgdm_kernel<false, true><<<dim3((unsigned)update_grid(P / 4), (unsigned)K), UPD_THREADS, 0, s>>>(
         (float4 *)theta, (float4 *)g, (float4 *)buf, P / 4, P, st, sc, mu, lambda, 0, nullptr,
-        NoiseDraw{sigma, seed, store_g ? 1 : 0});
+        NoiseDraw{sigma, seed, store_g ? 1 : 0}, st_next, spv);
     return hipGetLastError();
 }
 

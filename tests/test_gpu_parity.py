@@ -1099,6 +1099,42 @@ def test_checkpoint_and_resume():
     ref.close(); b.close()
 
 
+@pytest.mark.parametrize("K,P", [(4, 1 << 18), (4, 4096)])
+def test_scheduler_state_between_the_calls_of_an_iteration(K, P):
+    """Contexts of 2^20 replica-parameters and more are never replayed from a graph, and there the
+    update kernel takes the scheduler's end-of-iteration step itself on iterations that end no round;
+    smaller ones launch the scheduler kernel in qsr_maybe_sync.  Either way a caller sees the same
+    thing between qsr_local_step and qsr_maybe_sync and after it: the step just enqueued counts, the
+    round closes in qsr_maybe_sync; and the log, a restart and a restored state follow the oracle."""
+    w = workloads.get("flat60m", K=K, P=P, T=64, H_base=3, alpha=0.0, power=0, fuse_gradient=2)
+    orc = oracle_run(w)
+    ctx = gpu_ctx(w)
+    for t in range(1, 11):                       # rounds of 3: iterations 3, 6, 9 end one
+        ctx.local_step()
+        h = t % 3 if t % 3 else 3
+        assert ctx.get_state() == (t, (t - 1) // 3, h, 3), t          # before the round is closed
+        ctx.maybe_sync()
+        assert ctx.get_state() == (t, t // 3, t % 3, 3), t
+    orc.step(10)
+    assert_params_close(ctx.params.cpu().numpy(), orc.theta, what="after 10 iterations")
+    assert_mirror_matches_device(ctx)
+    # a state restored inside a round, then single calls and qsr_run mixed
+    ctx.set_state((20, 6, 2, 3))
+    ctx.local_step()
+    assert ctx.get_state() == (21, 6, 3, 3)
+    ctx.maybe_sync()
+    assert ctx.get_state() == (21, 7, 0, 3)
+    ctx.run(5); ctx.step(2)
+    assert ctx.get_state() == (28, 9, 1, 3)
+    ctx.restart()
+    ctx.step(64)
+    assert ctx.get_state() == (64, 22, 0, 0)
+    st, Hs = ctx.read_sync_log()
+    assert list(st) == [3 * i for i in range(1, 22)] + [64] and list(Hs) == [3] * 21 + [1]
+    assert_mirror_matches_device(ctx)
+    ctx.close()
+
+
 def torch_equal(a, b):
     import torch
     return bool(torch.equal(a, b))
