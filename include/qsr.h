@@ -14,8 +14,10 @@
  * The scheduler state (t, s, h, H), the learning-rate table and the log of averaging
  * points live in device memory; the two calls above only enqueue kernels on the caller's
  * stream and never synchronise.  The host keeps a mirror of the four integers, advanced with the
- * same arithmetic from the same table, which only decides whether an averaging kernel is enqueued
- * for an iteration; the device takes every decision again, logs the rounds, and any disagreement
+ * same arithmetic from the same table, which only decides which kernels are enqueued for an
+ * iteration (an averaging kernel where a round ends; where none ends, the update kernel may carry the
+ * scheduler's counting step instead of a launch of its own); the device takes every decision again,
+ * logs the rounds, and any disagreement
  * between the two is reported as QSR_EMIRROR by the calls that read the state.  All `float*` / `void*` buffer arguments are DEVICE
  * pointers unless marked (host); they stay owned by the caller, who must keep them alive
  * and untouched by other streams until qsr_destroy.  The library allocates only its own

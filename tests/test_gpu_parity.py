@@ -143,6 +143,18 @@ def test_schedule_is_bit_exact_for_the_full_run(name):
     assert ctx.get_H() == (0, len(H), w0["T"])
     assert_mirror_matches_device(ctx)
     ctx.close()
+    # and against Eq. (2) in exact rational arithmetic, a second implementation that shares nothing with
+    # either: the floating-point evaluation may differ from it only on a knife edge
+    from fractions import Fraction
+    import math
+    t, Tw, T = 0, w0.get("T_warm", 0), w0["T"]
+    for Hs in gH:
+        e = float(eta[max(t, Tw)])
+        v = (Fraction(w0["alpha"]) / Fraction(e)) ** 2 if e > 0 else Fraction(T)
+        if abs(float(v) - round(float(v))) > 1e-9:
+            assert Hs == min(max(w0["H_base"], math.floor(v)), T - t), (name, t)
+        t += int(Hs)
+    assert t == T
 
 
 @pytest.mark.parametrize("fuse_gradient", [0, 1, 2])
