@@ -565,6 +565,10 @@ struct EpiGeluBwd {              // dh = acc * gelu'(h), H holding gelu'(h) from
 // 1200 workgroups), also for the two GEMMs with the heavy GELU epilogues (128x256x32 tiles, two
 // workgroups per CU so that one's epilogue could overlap the other's main loop, timed the same to
 // 4 % slower: they fetch 1.5 times the bytes from L2, which is what bounds the main loop).
+// The same tile on 4 wavefronts of 128x128 (2, 2: a third fewer LDS fragment reads per
+// instruction, the 256 accumulator registers in the AGPRs, one wavefront per SIMD) compiles
+// without spills and is 8 - 17 % slower (500 against 461 us, 872 against 744 with the GELU
+// epilogue): with one wavefront per SIMD nothing covers its own waits.
 // The weight gradients (768 x 3072 outputs per worker, reduction over the tokens) go to the
 // persistent two-group kernel of gemm_pp.h, whose 192x384 tiles make exactly 256 workgroups for 8
 // workers.
