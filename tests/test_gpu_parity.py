@@ -998,7 +998,10 @@ def test_fused_sync_on_noise_workload():
 @pytest.mark.parametrize("opt", ["adamw", "sgdm"])
 @pytest.mark.parametrize("K,P,extra", [(4, 65536 + 8, {}), (3, 4099, {}), (4, 30000, dict(fuse_sync=True)),
                                        (3, 1001, dict(fuse_sync=True)),
-                                       (4, 20000, dict(parallel=True, H_base=1, power=0, alpha=0.0))])
+                                       (4, 20000, dict(parallel=True, H_base=1, power=0, alpha=0.0)),
+                                       # 2^20 replica-parameters and more: the clipped update kernel also takes
+                                       # the scheduler's step (rows of a length that is a multiple of 4 only)
+                                       (5, 1 << 18, {}), (3, 400001, {}), (5, 1 << 18, dict(fuse_sync=True))])
 def test_gradient_clipping(opt, K, P, extra):
     """Clipping by global norm per worker (App. C): gradients far above, around and below the
     threshold; aligned and unaligned rows; with the fused synchronization and with Parallel OPT
