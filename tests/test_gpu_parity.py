@@ -57,7 +57,10 @@ def test_update_and_averaging_with_external_gradients(opt, kw, K, P):
     ctx.close()
 
 
-@pytest.mark.parametrize("K,P", [(1, 7), (2, 4096), (3, 1001), (16, 40000), (32, 12345), (5, 1 << 18)])
+@pytest.mark.parametrize("K,P", [(1, 7), (2, 4096), (3, 1001), (16, 40000), (32, 12345), (5, 1 << 18),
+                                 # rows 8-byte aligned only, more rows than are in flight at a time; more
+                                 # than 32 workers (rows in registers, 16 at a time)
+                                 (20, 30002), (40, 4100)])
 def test_average_rows(K, P):
     import torch
     import paper_2310_14423_amd as qsr
@@ -273,7 +276,9 @@ def test_lsq_gradient_and_loss_single_step():
                                   # rows shorter than a group of four draws; more classes than the
                                   # loss kernel sums bias gradients for; a contraction cut in two
                                   dict(d_in=3, d_hidden=9, d_out=20, B_loc=10, K=2),
-                                  dict(d_in=300, d_hidden=40, d_out=16, B_loc=32, K=2)])
+                                  dict(d_in=300, d_hidden=40, d_out=16, B_loc=32, K=2),
+                                  # more samples than the output-layer backward kernel stages at a time
+                                  dict(d_in=20, d_hidden=70, d_out=7, B_loc=300, K=2)])
 def test_mlp2_gradient_single_step(dims):
     w = workloads.get("mlp", T=4, **dims)
     ctx = gpu_ctx(w)
