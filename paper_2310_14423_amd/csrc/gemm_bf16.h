@@ -224,7 +224,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_bf16_kernel(GemmNT p, Ep
     // ks+1 are read from LDS while the MFMAs of step ks issue, and the last step of a slab is
     // held in registers across the barrier, so that its MFMAs cover the burst of first fragment
     // reads of the next slab that all wavefronts start at once after the barrier (worth 10 % at
-    // K = 3072 over stopping with empty MFMA queues at every barrier).
+    // K = 3072 over stopping with empty MFMA queues at every barrier).  The compiler waits for ALL
+    // outstanding LDS reads in two of the four steps of a slab (lgkmcnt(0) right after the next
+    // step's six reads went out); with the reads written as asm and waited for by hand (at most
+    // six outstanding) every step's reads fly behind the previous step's multiplications, and the
+    // kernels take the same time to 2 %: the SIMD's other wavefront already filled those gaps.
     const int nk = p.K / BK;
     constexpr int KS = BK / 16;
     static_assert(KS % 2 == 0, "fragment double buffer parity");
