@@ -60,7 +60,8 @@ __global__ __launch_bounds__(256 * KSPLIT) void sgemm_kernel(GemmArgs a)
     // (timed on MI355X, 128 x 784 x 1024, 8 workers, with the products still on the vector ALUs:
     // 178 us per launch without, 98 us with; 46 us with the products on the matrix cores.  Six
     // slabs ahead or 32-deep slabs timed the same to slower; 64-deep slabs one ahead, for the weight
-    // gradient whose contraction is 128 long: 29.5 against 27.4 us).
+    // gradient whose contraction is 128 long: 29.5 against 27.4 us; 64 x 256 tiles with four wavefronts
+    // of 64 x 64 side by side, one fragment read per instruction: 30.4 us).
     constexpr int PF = 3;
     constexpr int R = TK / 4;                       // elements of each operand per thread and slab
     float ra[PF][R], rb[PF][R];
